@@ -1,0 +1,421 @@
+/*
+ * agoq_ref.c -- CPU oracle for the AGoQ quantization hot path.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It is the slow, plain
+ * definition that the HIP kernels are checked against.  It shares nothing
+ * with the GPU library (no header, no helper, no table) and only the tests,
+ * the smoke check and the benchmark's CPU-baseline leg may call it.
+ *
+ * What it computes (paper: "System Overview" -- activations are stored as
+ * block-wise low-bit codes and dequantized to BF16 before the backward pass;
+ * "Layer-Aware Activation Quantization / Other Operations" -- block size 128;
+ * "Precision-Preserved Gradient Quantization" -- gradients kept as 8-bit
+ * block-wise codes, and the local step of the 8-bit All-Reduce dequantizes
+ * the chunks received from the peers to FP32, sums them, and quantizes the
+ * sum again; "Dynamic Bit-width Compensation", Eq. (dynamic) -- per-stage
+ * bit-width).
+ *
+ * The paper names the scheme but prints no arithmetic.  The reading used
+ * here (every line of it is a reading, listed in the design notes):
+ *   - uniform symmetric integer grid, qmax = 2^(b-1) - 1, no zero point;
+ *   - blocks ("groups") are G contiguous elements of the flat buffer;
+ *   - all arithmetic is IEEE binary32, round-to-nearest-even, no fused
+ *     multiply-add except the one fmaf written out in the reduce;
+ *   - amax  = max |x_j| over the group;
+ *   - amax < 2^-100 (includes 0): scale = 0 and every code = 0;
+ *   - scale = amax / qmax,  inv = qmax / amax   (two separate divisions);
+ *   - code  = clamp(rint(x_j * inv), -qmax, +qmax)   (rint = ties to even);
+ *   - 8-bit codes are int8; narrower codes are two's-complement fields of
+ *     b bits packed little-endian into the byte stream, element j of the
+ *     buffer occupying bits [j*b, j*b+b) of that stream (for b = 4: even
+ *     element in the low nibble, odd element in the high nibble);
+ *   - dequantize: v = (float)code * scale; activations return bf16(v) with
+ *     round-to-nearest-even;
+ *   - reduce: acc = 0; for k = 0..K-1 in that order: acc = fmaf(code_k,
+ *     scale_k, acc); then the group of acc values is quantized with b = 8.
+ *
+ * Parity status of each function:
+ *   act_quant / act_dequant / grad_quant / grad_reduce_requant /
+ *   grad_accumulate / grad_dequant / dbca_bits:  pinned by tests/test_oracle_*.py
+ *   (exact-arithmetic brute force over all bf16 patterns, closed forms on
+ *   power-of-two scales, tie cases, byte-level packing fixtures, the
+ *   round-trip bound, library cross-checks and the values the paper prints
+ *   for the four-stage pipeline).
+ *   Non-finite inputs (NaN, Inf) are outside the contract: parity unpinned.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
+ * Parallelism is over groups only; a group is always handled by one thread
+ * from start to end, so results do not depend on the thread count.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define REF_OK 0
+#define REF_ERR_NULL 1
+#define REF_ERR_BITS 2
+#define REF_ERR_GROUP 3
+#define REF_ERR_SHAPE 4
+#define REF_ERR_K 6
+
+/* Groups whose largest magnitude is below this are stored as all-zero. */
+static const float REF_AMAX_MIN = 0x1p-100f;
+
+/* ---- bf16 <-> fp32 ------------------------------------------------------ */
+
+static float bf16_bits_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16; /* bf16 is the top half of a binary32 */
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* Round a finite binary32 to bf16, nearest, ties to even. */
+static uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint32_t lsb = (u >> 16) & 1u; /* parity of the bit that survives */
+    u += 0x7FFFu + lsb;            /* > half rounds up; == half rounds to even */
+    return (uint16_t)(u >> 16);
+}
+
+/* exported so that the tests can pin the conversion on its own */
+float agoq_ref_bf16_to_f32(uint16_t h) { return bf16_bits_to_f32(h); }
+uint16_t agoq_ref_f32_to_bf16(float f) { return f32_to_bf16_bits(f); }
+
+/* ---- the group quantizer ------------------------------------------------ */
+
+static int qmax_of_bits(int bits) { return (1 << (bits - 1)) - 1; }
+
+static int bits_supported(int bits)
+{
+    return bits == 4 || bits == 8;
+}
+
+/* Quantize G fp32 values to integer codes in [-qmax, qmax]; returns scale. */
+static float quantize_group(const float *x, int G, int qmax, int *q)
+{
+    float amax = 0.0f;
+    for (int j = 0; j < G; ++j) {
+        float a = fabsf(x[j]);
+        if (a > amax)
+            amax = a;
+    }
+    if (amax < REF_AMAX_MIN) {
+        for (int j = 0; j < G; ++j)
+            q[j] = 0;
+        return 0.0f;
+    }
+    const float fq = (float)qmax;
+    const float scale = amax / fq;
+    const float inv = fq / amax;
+    for (int j = 0; j < G; ++j) {
+        float t = x[j] * inv;
+        float r = rintf(t); /* default rounding mode: ties to even */
+        if (r > fq)
+            r = fq;
+        if (r < -fq)
+            r = -fq;
+        q[j] = (int)r;
+    }
+    return scale;
+}
+
+/* ---- bit-stream packing: element j lives in bits [j*b, j*b + b) --------- */
+
+static void put_code(uint8_t *stream, int64_t j, int bits, int q)
+{
+    uint32_t field = (uint32_t)q & ((1u << bits) - 1u); /* two's complement */
+    int64_t bit0 = j * bits;
+    for (int t = 0; t < bits; ++t) {
+        int64_t p = bit0 + t;
+        uint8_t m = (uint8_t)(1u << (p & 7));
+        if ((field >> t) & 1u)
+            stream[p >> 3] |= m;
+        else
+            stream[p >> 3] &= (uint8_t)~m;
+    }
+}
+
+static int get_code(const uint8_t *stream, int64_t j, int bits)
+{
+    uint32_t field = 0;
+    int64_t bit0 = j * bits;
+    for (int t = 0; t < bits; ++t) {
+        int64_t p = bit0 + t;
+        field |= (uint32_t)((stream[p >> 3] >> (p & 7)) & 1u) << t;
+    }
+    if (field & (1u << (bits - 1))) /* sign bit of the field */
+        return (int)field - (1 << bits);
+    return (int)field;
+}
+
+/* ---- argument checks ---------------------------------------------------- */
+
+static int check_shape(int64_t numel, int group, int bits)
+{
+    if (!bits_supported(bits))
+        return REF_ERR_BITS;
+    if (group < 1 || group > 4096)
+        return REF_ERR_GROUP;
+    if (numel <= 0 || numel % group != 0)
+        return REF_ERR_SHAPE;
+    if (((int64_t)group * bits) % 8 != 0) /* a group is a whole number of bytes */
+        return REF_ERR_GROUP;
+    return REF_OK;
+}
+
+/* ---- activations -------------------------------------------------------- */
+
+/* x: numel bf16 bit patterns.  codes: numel*bits/8 bytes.  scales: numel/group. */
+int agoq_ref_act_quant(const uint16_t *x, int64_t numel, int group, int bits,
+                       uint8_t *codes, float *scales)
+{
+    if (!x || !codes || !scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, bits);
+    if (rc)
+        return rc;
+    const int qmax = qmax_of_bits(bits);
+    const int64_t n_groups = numel / group;
+    const int64_t group_bytes = (int64_t)group * bits / 8;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float xf[4096];
+        int q[4096];
+        const uint16_t *xg = x + g * group;
+        for (int j = 0; j < group; ++j)
+            xf[j] = bf16_bits_to_f32(xg[j]);
+        scales[g] = quantize_group(xf, group, qmax, q);
+        uint8_t *cg = codes + g * group_bytes; /* groups start on byte boundaries */
+        for (int j = 0; j < group; ++j)
+            put_code(cg, j, bits, q[j]);
+    }
+    return REF_OK;
+}
+
+int agoq_ref_act_dequant(const uint8_t *codes, const float *scales, int64_t numel,
+                         int group, int bits, uint16_t *y)
+{
+    if (!codes || !scales || !y)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, bits);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+    const int64_t group_bytes = (int64_t)group * bits / 8;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        const uint8_t *cg = codes + g * group_bytes;
+        const float s = scales[g];
+        for (int j = 0; j < group; ++j) {
+            float v = (float)get_code(cg, j, bits) * s;
+            y[g * group + j] = f32_to_bf16_bits(v);
+        }
+    }
+    return REF_OK;
+}
+
+/* ---- gradients ---------------------------------------------------------- */
+
+int agoq_ref_grad_quant(const float *grad, int64_t numel, int group, int8_t *codes,
+                        float *scales)
+{
+    if (!grad || !codes || !scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        int q[4096];
+        scales[g] = quantize_group(grad + g * group, group, 127, q);
+        for (int j = 0; j < group; ++j)
+            codes[g * group + j] = (int8_t)q[j];
+    }
+    return REF_OK;
+}
+
+/* int8 codes + scales -> fp32 values (what an optimizer would read). */
+int agoq_ref_grad_dequant(const int8_t *codes, const float *scales, int64_t numel,
+                          int group, float *out)
+{
+    if (!codes || !scales || !out)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g)
+        for (int j = 0; j < group; ++j)
+            out[g * group + j] = (float)codes[g * group + j] * scales[g];
+    return REF_OK;
+}
+
+/*
+ * Local step of the 8-bit All-Reduce.  Chunk k starts at in_codes +
+ * k*stride_codes (numel int8) and in_scales + k*stride_scales (numel/group
+ * fp32).  Summation order is the chunk index, one fmaf per term.
+ */
+int agoq_ref_grad_reduce_requant(const int8_t *in_codes, int64_t stride_codes,
+                                 const float *in_scales, int64_t stride_scales, int K,
+                                 int64_t numel, int group, int8_t *out_codes,
+                                 float *out_scales)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    if (K < 1 || K > 64)
+        return REF_ERR_K;
+    const int64_t n_groups = numel / group;
+    if (stride_codes < numel || stride_scales < n_groups)
+        return REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float acc[4096];
+        int q[4096];
+        for (int j = 0; j < group; ++j) {
+            float a = 0.0f;
+            for (int k = 0; k < K; ++k) {
+                float c = (float)in_codes[k * stride_codes + g * group + j];
+                float s = in_scales[k * stride_scales + g];
+                a = fmaf(c, s, a);
+            }
+            acc[j] = a;
+        }
+        out_scales[g] = quantize_group(acc, group, 127, q);
+        for (int j = 0; j < group; ++j)
+            out_codes[g * group + j] = (int8_t)q[j];
+    }
+    return REF_OK;
+}
+
+/*
+ * The same sums in binary64, in the same order, without requantizing: the
+ * yardstick for "how far is the fp32 accumulation from the exact sum".
+ * abs_sum receives sum_k |code_k * scale_k| (may be NULL).
+ */
+int agoq_ref_grad_reduce_f64(const int8_t *in_codes, int64_t stride_codes,
+                             const float *in_scales, int64_t stride_scales, int K,
+                             int64_t numel, int group, double *sum, double *abs_sum)
+{
+    if (!in_codes || !in_scales || !sum)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    if (K < 1 || K > 64)
+        return REF_ERR_K;
+    for (int64_t i = 0; i < numel; ++i) {
+        double a = 0.0, b = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double term = (double)in_codes[k * stride_codes + i] *
+                          (double)in_scales[k * stride_scales + i / group];
+            a += term;
+            b += fabs(term);
+        }
+        sum[i] = a;
+        if (abs_sum)
+            abs_sum[i] = b;
+    }
+    return REF_OK;
+}
+
+/*
+ * Local gradient accumulation: the stored 8-bit main gradient is dequantized,
+ * the new micro-batch gradient is added in fp32 (one rounding:
+ * acc = fmaf(code, scale, g_new)), and the sum is quantized back to 8 bits.
+ * g_new is fp32 (new_is_bf16 = 0) or bf16 bit patterns (new_is_bf16 = 1).
+ */
+int agoq_ref_grad_accumulate(const int8_t *main_codes, const float *main_scales,
+                             const void *g_new, int new_is_bf16, int64_t numel, int group,
+                             int8_t *out_codes, float *out_scales)
+{
+    if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float acc[4096];
+        int q[4096];
+        const float s = main_scales[g];
+        for (int j = 0; j < group; ++j) {
+            int64_t i = g * group + j;
+            float add = new_is_bf16 ? bf16_bits_to_f32(((const uint16_t *)g_new)[i])
+                                    : ((const float *)g_new)[i];
+            acc[j] = fmaf((float)main_codes[i], s, add);
+        }
+        out_scales[g] = quantize_group(acc, group, 127, q);
+        for (int j = 0; j < group; ++j)
+            out_codes[g * group + j] = (int8_t)q[j];
+    }
+    return REF_OK;
+}
+
+/* ---- Dynamic Bit-width Compensation (Eq. "dynamic") --------------------- */
+
+/*
+ * Interleaved 1F1B with n stages: stage i (1-based) holds N_i = 3n - 2i + 1
+ * micro-batches of activations at its peak (first stage the most: the text
+ * gives 11, 9, 7, 5 for n = 4; the printed formula has the index reversed).
+ * B_i = 4 * N_1 / N_i, rounded to the nearest integer (halves up), at least
+ * 4 and at most 8.
+ */
+int agoq_ref_dbca_stored_microbatches(int n_stages, int stage)
+{
+    if (n_stages < 1 || stage < 1 || stage > n_stages)
+        return -1;
+    return 3 * n_stages - 2 * stage + 1;
+}
+
+int agoq_ref_dbca_bits(int n_stages, int stage, int *bits_out)
+{
+    if (!bits_out)
+        return REF_ERR_NULL;
+    if (n_stages < 1 || stage < 1 || stage > n_stages)
+        return REF_ERR_SHAPE;
+    int n1 = agoq_ref_dbca_stored_microbatches(n_stages, 1);
+    int ni = agoq_ref_dbca_stored_microbatches(n_stages, stage);
+    double b = 4.0 * (double)n1 / (double)ni;
+    int r = (int)floor(b + 0.5);
+    if (r < 4)
+        r = 4;
+    if (r > 8)
+        r = 8;
+    *bits_out = r;
+    return REF_OK;
+}
+
+/* ---- thread control for the timed baseline ------------------------------ */
+
+int agoq_ref_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void agoq_ref_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

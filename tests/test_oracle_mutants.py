@@ -1,0 +1,98 @@
+"""Do the pins bite?  Each case plants ONE plausible mistake in a copy of the oracle's
+source (CPU only, in a temporary directory), builds it, and requires that at least one
+of the pin tests fails on the broken build.  The committed oracle is never modified."""
+import inspect
+import os
+import subprocess
+
+import pytest
+
+import test_oracle_quant_pins as quant_pins
+import test_oracle_reduce_pins as reduce_pins
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "agoq_ref.c")
+
+# (name, text in the oracle source, replacement)
+MUTANTS = [
+    ("half_away_rounding", "float r = rintf(t);", "float r = roundf(t);"),
+    ("truncation_instead_of_rounding", "float r = rintf(t);", "float r = truncf(t);"),
+    ("inv_as_reciprocal_of_scale", "const float inv = fq / amax;", "const float inv = 1.0f / scale;"),
+    ("scale_by_multiplying_reciprocal", "const float scale = amax / fq;",
+     "const float scale = amax * (1.0f / fq);"),
+    ("asymmetric_qmax", "return (1 << (bits - 1)) - 1;", "return (1 << (bits - 1));"),
+    ("absmax_without_abs", "float a = fabsf(x[j]);", "float a = x[j];"),
+    ("no_tiny_group_rule", "static const float REF_AMAX_MIN = 0x1p-100f;",
+     "static const float REF_AMAX_MIN = 0.0f;"),
+    ("nibbles_swapped", "put_code(cg, j, bits, q[j]);", "put_code(cg, j ^ 1, bits, q[j]);"),
+    ("decode_without_sign_extension", "return (int)field - (1 << bits);", "return (int)field;"),
+    ("bf16_by_truncation", "u += 0x7FFFu + lsb;", "u += 0u * lsb;"),
+    ("bf16_ties_up", "u += 0x7FFFu + lsb;", "u += 0x8000u + 0u * lsb;"),
+    ("reduce_two_roundings", "a = fmaf(c, s, a);", "a = a + c * s;"),
+    ("reduce_reverse_order", "for (int k = 0; k < K; ++k) {\n                float c = (float)in_codes",
+     "for (int k = K - 1; k >= 0; --k) {\n                float c = (float)in_codes"),
+    ("reduce_wrong_scale_row", "float s = in_scales[k * stride_scales + g];",
+     "float s = in_scales[g];"),
+    ("reduce_codes_ignore_stride", "in_codes[k * stride_codes + g * group + j]",
+     "in_codes[k * numel + g * group + j]"),
+    ("accumulate_two_roundings", "acc[j] = fmaf((float)main_codes[i], s, add);",
+     "acc[j] = (float)main_codes[i] * s + add;"),
+    ("accumulate_drops_new_gradient", "acc[j] = fmaf((float)main_codes[i], s, add);",
+     "acc[j] = fmaf((float)main_codes[i], s, 0.0f * add);"),
+    ("dbca_printed_index", "return 3 * n_stages - 2 * stage + 1;", "return n_stages + 2 * stage - 1;"),
+    ("dbca_floor_instead_of_round", "int r = (int)floor(b + 0.5);", "int r = (int)floor(b);"),
+    ("dbca_no_cap", "if (r > 8)\n        r = 8;", ""),
+    ("dequant_uses_previous_group_scale", "const float s = scales[g];\n        for (int j = 0; j < group; ++j) {\n            float v",
+     "const float s = scales[g > 0 ? g - 1 : 0];\n        for (int j = 0; j < group; ++j) {\n            float v"),
+]
+
+
+def pin_tests():
+    """Every pin test of the two pin modules, expanded over its parametrisation."""
+    cases = []
+    for mod in (quant_pins, reduce_pins):
+        for name, fn in inspect.getmembers(mod, inspect.isfunction):
+            if not name.startswith("test_") or "ref" not in inspect.signature(fn).parameters:
+                continue
+            grids = [{}]
+            for mark in getattr(fn, "pytestmark", []):
+                if mark.name != "parametrize":
+                    continue
+                names = [n.strip() for n in mark.args[0].split(",")]
+                new = []
+                for g in grids:
+                    for val in mark.args[1]:
+                        vals = val if len(names) > 1 else (val,)
+                        new.append({**g, **dict(zip(names, vals))})
+                grids = new
+            cases += [(fn, g) for g in grids]
+    return cases
+
+
+def killed_by(oracle_obj):
+    for fn, kwargs in pin_tests():
+        try:
+            fn(ref=oracle_obj, **kwargs)
+        except Exception as exc:  # an assertion, or the oracle rejecting / mangling a call
+            return "%s%s: %s" % (fn.__name__, kwargs or "", type(exc).__name__)
+    return None
+
+
+def test_pins_pass_on_the_unmodified_source(tmp_path, ref):
+    assert killed_by(ref.Oracle()) is None
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, ref, name, old, new):
+    import warnings
+    text = open(SRC).read()
+    assert text.count(old) == 1, "mutation site must be unique: %r" % old
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new))
+    lib = tmp_path / ("libmutant_%s.so" % name)
+    subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+                           "-w", "-shared", "-fPIC", "-o", str(lib), str(src), "-lm"])
+    with warnings.catch_warnings():
+        warnings.simplefilter("ignore")
+        verdict = killed_by(ref.Oracle(str(lib)))
+    assert verdict is not None, "no pin noticed the planted mistake %r" % name
