@@ -1,0 +1,165 @@
+/*
+ * agoq.h -- C ABI of the AGoQ quantization hot path for AMD MI355X (gfx950).
+ *
+ * The library implements the storage side of AGoQ's training-memory scheme:
+ * block-wise low-bit storage of activations between forward and backward,
+ * 8-bit storage of gradients, and the local, precision-preserving step of the
+ * 8-bit All-Reduce.  Each entry point below names the passage of the paper
+ * that defines the operation.
+ *
+ * Conventions shared by every device entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The
+ *     library never allocates, frees, copies to the host or synchronizes.
+ *   - A call enqueues its kernel(s) on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) of the CURRENT device and returns at
+ *     once.  Outputs are complete when the stream reaches that point.
+ *   - Return value: AGOQ_OK (0) or a positive AGOQ_ERR_* code.  On error
+ *     nothing has been enqueued and no output byte has been touched.
+ *   - `group` (block size) is 64 or 128 elements; groups are runs of `group`
+ *     consecutive elements of the flat buffer, so a row-major [rows, cols]
+ *     tensor with cols % group == 0 is quantized along its last dimension.
+ *     `numel` must be a positive multiple of `group` (the paper defines no
+ *     partial block).
+ *   - Every tensor pointer must be 16-byte aligned.  Input and output
+ *     buffers must not overlap unless an entry point says otherwise.
+ *   - Arithmetic is IEEE binary32 with round-to-nearest-even throughout; for
+ *     a group with largest magnitude amax and qmax = 2^(bits-1) - 1:
+ *         amax <  2^-100 :  scale = 0, every code 0
+ *         otherwise      :  scale = amax / qmax,  inv = qmax / amax
+ *                           code  = rint(x * inv)   (ties to even; |code| <= qmax)
+ *     and dequantization is value = (float)code * scale.
+ *   - Inputs must be finite; NaN/Inf give unspecified codes (never a fault).
+ *   - Code layout: 8-bit codes are int8, one per element.  4-bit codes are
+ *     two's-complement nibbles, byte m holding element 2m in bits 0-3 and
+ *     element 2m+1 in bits 4-7.  Scales are fp32, one per group, in group
+ *     order.
+ */
+#ifndef AGOQ_H
+#define AGOQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    AGOQ_OK = 0,
+    AGOQ_ERR_NULL = 1,  /* a required pointer is NULL */
+    AGOQ_ERR_BITS = 2,  /* bits is not 4 or 8 */
+    AGOQ_ERR_GROUP = 3, /* group is not 64 or 128 */
+    AGOQ_ERR_SHAPE = 4, /* numel <= 0, numel % group != 0, or a stride below its extent */
+    AGOQ_ERR_ALIGN = 5, /* a pointer (or a chunk stride) breaks 16-byte alignment */
+    AGOQ_ERR_K = 6,     /* K outside 1..64 */
+    AGOQ_ERR_HIP = 7    /* the HIP runtime refused the launch */
+};
+
+/*
+ * Quantize and pack an activation for storage until the backward pass
+ * (paper: "System Overview", activations are stored at about 4 bits after the
+ * forward pass; "Layer-Aware Activation Quantization / Other Operations",
+ * block-wise quantization with block size 128; "Dynamic Bit-width
+ * Compensation", later pipeline stages use wider codes).
+ *   x_bf16 : in,  numel bf16 values
+ *   bits   : 4 or 8, the width the bit map assigns to this tensor
+ *   codes  : out, numel*bits/8 bytes
+ *   scales : out, numel/group fp32
+ */
+int agoq_act_quant(const void *x_bf16, int64_t numel, int group, int bits, void *codes,
+                   float *scales, void *stream);
+
+/*
+ * Unpack and dequantize a stored activation to bf16 for the backward pass
+ * (paper: "System Overview": quantized activations are dequantized to
+ * BF16 before gradient computation).  y = bf16(code * scale), the product
+ * rounded to fp32 first and then to bf16, both to nearest-even.
+ *   codes, scales : in, as written by agoq_act_quant (any codes are legal,
+ *                   including -8 / -128)
+ *   y_bf16        : out, numel bf16 values
+ */
+int agoq_act_dequant(const void *codes, const float *scales, int64_t numel, int group, int bits,
+                     void *y_bf16, void *stream);
+
+/*
+ * Store a gradient as 8-bit block-wise codes (paper: "Precision-Preserved
+ * Gradient Quantization": the main gradient is kept in 8 bits).
+ *   grad   : in,  numel fp32
+ *   codes  : out, numel int8
+ *   scales : out, numel/group fp32
+ */
+int agoq_grad_quant(const float *grad, int64_t numel, int group, int8_t *codes, float *scales,
+                    void *stream);
+
+/*
+ * Local step of the 8-bit All-Reduce (paper: "Precision-Preserved Gradient
+ * Quantization": after the All-to-All each device dequantizes the chunks it
+ * received to FP32, reduces them locally and quantizes the result again for
+ * the All-Gather).  The K chunks are this device's shard as sent by K peers,
+ * laid out as one receive buffer: chunk k starts at in_codes +
+ * k*chunk_stride_codes and in_scales + k*chunk_stride_scales.
+ *   for each element i of group g:
+ *       acc = 0;  for k = 0 .. K-1 (in this order):  acc = fma(code_k[i], scale_k[g], acc)
+ *   then the group of acc values is quantized to 8 bits as in agoq_grad_quant.
+ *   The summation order is fixed, so the result is bit-reproducible.
+ *   chunk_stride_codes  : elements between chunks, >= numel, multiple of 16
+ *   chunk_stride_scales : elements between chunks, >= numel/group
+ *   K : 1..64
+ */
+int agoq_grad_reduce_requant(const int8_t *in_codes, int64_t chunk_stride_codes,
+                             const float *in_scales, int64_t chunk_stride_scales, int K,
+                             int64_t numel, int group, int8_t *out_codes, float *out_scales,
+                             void *stream);
+
+/* ---- host-only helpers: pure functions, no device access ---------------- */
+
+/* Bytes of packed codes for numel elements at `bits` per element; -1 if bits is unsupported. */
+int64_t agoq_codes_bytes(int64_t numel, int bits);
+
+/* Number of scales (groups); -1 if numel is not a positive multiple of group. */
+int64_t agoq_num_groups(int64_t numel, int group);
+
+/*
+ * Dynamic Bit-width Compensation (paper: "Dynamic Bit-width Compensation",
+ * Eq. (dynamic)).  Under interleaved 1F1B with n_stages pipeline stages,
+ * stage i (1-based) holds N_i = 3*n_stages - 2*i + 1 micro-batches of
+ * activations at its peak (11, 9, 7, 5 for four stages), and is given
+ * B_i = 4*N_1/N_i bits, rounded to the nearest integer, at least 4 and at
+ * most 8 (4, 5, 6, 8 for four stages).
+ * agoq_dbca_stored_microbatches returns N_i, or -1 for bad arguments.
+ * agoq_dbca_bits writes B_i to *bits_out; AGOQ_ERR_SHAPE for bad arguments.
+ */
+int agoq_dbca_stored_microbatches(int n_stages, int stage_1based);
+int agoq_dbca_bits(int n_stages, int stage_1based, int *bits_out);
+
+/*
+ * Bit map of one decoder layer (paper: Table "memory_comparison", row AGoQ,
+ * and "Other Operations": the stored tensors are the inputs of the two
+ * RMSNorms, the input of the attention output projection, and the two inputs
+ * of SiLU & Multiply; attention's own tensors stay in bf16).  The slots of
+ * bits_out are, in order: norm1 input, out-proj input, norm2 input, gate, up.
+ * With only 4- and 8-bit codes a stage's target width B (4..8, from
+ * agoq_dbca_bits) is realized as a mix: B=4 all 4-bit; B=5 both norm inputs
+ * 8-bit; B=6 and B=7 norm inputs and gate 8-bit; B=8 all 8-bit.
+ */
+enum { AGOQ_SLOT_NORM1_IN = 0, AGOQ_SLOT_OPROJ_IN = 1, AGOQ_SLOT_NORM2_IN = 2,
+       AGOQ_SLOT_GATE = 3, AGOQ_SLOT_UP = 4, AGOQ_LAYER_SLOTS = 5 };
+int agoq_layer_bitmap(int target_bits, int bits_out[AGOQ_LAYER_SLOTS]);
+
+/*
+ * Bytes that one layer's five stored tensors occupy under a bit map
+ * (codes plus, if with_scales != 0, 4 bytes per group), for `tokens` rows,
+ * model width `hidden` and MLP width `ffn`.  -1 for bad arguments.
+ */
+int64_t agoq_layer_stored_bytes(int64_t tokens, int64_t hidden, int64_t ffn, int group,
+                                const int bits[AGOQ_LAYER_SLOTS], int with_scales);
+
+/* Static string for a status code. */
+const char *agoq_strerror(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int agoq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGOQ_H */

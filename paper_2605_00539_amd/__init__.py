@@ -1,0 +1,17 @@
+"""AGoQ quantization hot path for AMD MI355X: thin Python binding over libagoq.so.
+
+The functions below marshal torch device tensors into the C ABI declared in
+include/agoq.h (same names without the prefix).  Every step of the method runs in the
+HIP kernels of that library; there is no fallback: without the built library, or
+without a GPU, the calls raise.
+"""
+from .binding import (AgoqError, act_dequant, act_quant, codes_bytes, dbca_bits,
+                      dbca_stored_microbatches, grad_quant, grad_reduce_requant,
+                      layer_bitmap, layer_stored_bytes, library_path, load_library,
+                      num_groups, strerror, version)
+
+__all__ = [
+    "AgoqError", "act_quant", "act_dequant", "grad_quant", "grad_reduce_requant",
+    "codes_bytes", "num_groups", "dbca_bits", "dbca_stored_microbatches", "layer_bitmap",
+    "layer_stored_bytes", "strerror", "version", "load_library", "library_path",
+]

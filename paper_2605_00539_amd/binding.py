@@ -1,0 +1,201 @@
+"""ctypes binding of libagoq.so.  Argument marshalling only."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libagoq.so")
+_lib = None
+
+_I64 = ctypes.c_int64
+_INT = ctypes.c_int
+_P = ctypes.c_void_p
+_SLOTS = 5
+
+
+class AgoqError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("agoq status %d: %s" % (status, message))
+        self.status = status
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libagoq.so (built by paper_2605_00539_amd/build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            "libagoq.so is not built: run `python -m paper_2605_00539_amd.build` "
+            "(or __graft_entry__.build()) first; there is no fallback path")
+    # torch ships its own HIP runtime; importing it first makes this library bind to the
+    # same runtime, so that torch's device pointers and streams are valid here
+    import torch  # noqa: F401
+    L = ctypes.CDLL(_LIB_PATH)
+    L.agoq_act_quant.argtypes = [_P, _I64, _INT, _INT, _P, _P, _P]
+    L.agoq_act_dequant.argtypes = [_P, _P, _I64, _INT, _INT, _P, _P]
+    L.agoq_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
+    L.agoq_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
+    L.agoq_codes_bytes.argtypes = [_I64, _INT]
+    L.agoq_codes_bytes.restype = _I64
+    L.agoq_num_groups.argtypes = [_I64, _INT]
+    L.agoq_num_groups.restype = _I64
+    L.agoq_dbca_stored_microbatches.argtypes = [_INT, _INT]
+    L.agoq_dbca_bits.argtypes = [_INT, _INT, ctypes.POINTER(_INT)]
+    L.agoq_layer_bitmap.argtypes = [_INT, ctypes.POINTER(_INT * _SLOTS)]
+    L.agoq_layer_stored_bytes.argtypes = [_I64, _I64, _I64, _INT, ctypes.POINTER(_INT * _SLOTS), _INT]
+    L.agoq_layer_stored_bytes.restype = _I64
+    L.agoq_strerror.argtypes = [_INT]
+    L.agoq_strerror.restype = ctypes.c_char_p
+    L.agoq_version.argtypes = []
+    _lib = L
+    return L
+
+
+def strerror(status):
+    return load_library().agoq_strerror(int(status)).decode()
+
+
+def version():
+    return load_library().agoq_version()
+
+
+def _check(status):
+    if status != 0:
+        raise AgoqError(status, strerror(status))
+
+
+def _dev(t, dtype, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a tensor on the GPU" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _raw(ptr):
+    return ctypes.c_void_p(ptr)
+
+
+# ---- device entry points ------------------------------------------------------
+
+def act_quant(x, group, bits, codes=None, scales=None, stream=None):
+    """x: bf16 tensor on the GPU.  Returns (codes uint8 [numel*bits/8], scales float32 [numel/group])."""
+    import torch
+    L = load_library()
+    x = _dev(x, torch.bfloat16, "x")
+    n = x.numel()
+    if codes is None:
+        codes = torch.empty(max(n * bits // 8, 1), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    with torch.cuda.device(x.device):
+        _check(L.agoq_act_quant(_raw(x.data_ptr()), n, group, bits, _raw(codes.data_ptr()),
+                                _raw(scales.data_ptr()), _stream(stream)))
+    return codes, scales
+
+
+def act_dequant(codes, scales, numel, group, bits, out=None, stream=None):
+    """Returns a flat bf16 tensor of numel elements."""
+    import torch
+    L = load_library()
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    if out is None:
+        out = torch.empty(numel, dtype=torch.bfloat16, device=codes.device)
+    _dev(out, torch.bfloat16, "out")
+    with torch.cuda.device(codes.device):
+        _check(L.agoq_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
+                                  bits, _raw(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def grad_quant(grad, group, codes=None, scales=None, stream=None):
+    """grad: fp32 tensor on the GPU.  Returns (codes int8 [numel], scales float32 [numel/group])."""
+    import torch
+    L = load_library()
+    grad = _dev(grad, torch.float32, "grad")
+    n = grad.numel()
+    if codes is None:
+        codes = torch.empty(max(n, 1), dtype=torch.int8, device=grad.device)
+    if scales is None:
+        scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=grad.device)
+    _dev(codes, torch.int8, "codes")
+    _dev(scales, torch.float32, "scales")
+    with torch.cuda.device(grad.device):
+        _check(L.agoq_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
+                                 _raw(scales.data_ptr()), _stream(stream)))
+    return codes, scales
+
+
+def grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_scales=None,
+                        stream=None):
+    """in_codes: int8 [K, stride_c]; in_scales: float32 [K, stride_s] (the receive buffer of the
+    All-to-All, chunk k in row k).  Returns (codes int8 [numel], scales float32 [numel/group])."""
+    import torch
+    L = load_library()
+    _dev(in_codes, torch.int8, "in_codes")
+    _dev(in_scales, torch.float32, "in_scales")
+    if in_codes.dim() != 2 or in_scales.dim() != 2 or in_codes.shape[0] != in_scales.shape[0]:
+        raise ValueError("expected in_codes [K, stride_c] and in_scales [K, stride_s]")
+    K = in_codes.shape[0]
+    if out_codes is None:
+        out_codes = torch.empty(max(numel, 1), dtype=torch.int8, device=in_codes.device)
+    if out_scales is None:
+        out_scales = torch.empty(max(numel // max(group, 1), 1), dtype=torch.float32,
+                                 device=in_codes.device)
+    _dev(out_codes, torch.int8, "out_codes")
+    _dev(out_scales, torch.float32, "out_scales")
+    with torch.cuda.device(in_codes.device):
+        _check(L.agoq_grad_reduce_requant(
+            _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
+            in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),
+            _raw(out_scales.data_ptr()), _stream(stream)))
+    return out_codes, out_scales
+
+
+# ---- host helpers ---------------------------------------------------------------
+
+def codes_bytes(numel, bits):
+    return load_library().agoq_codes_bytes(numel, bits)
+
+
+def num_groups(numel, group):
+    return load_library().agoq_num_groups(numel, group)
+
+
+def dbca_stored_microbatches(n_stages, stage):
+    return load_library().agoq_dbca_stored_microbatches(n_stages, stage)
+
+
+def dbca_bits(n_stages, stage):
+    out = _INT(0)
+    _check(load_library().agoq_dbca_bits(n_stages, stage, ctypes.byref(out)))
+    return out.value
+
+
+def layer_bitmap(target_bits):
+    arr = (_INT * _SLOTS)()
+    _check(load_library().agoq_layer_bitmap(target_bits, ctypes.byref(arr)))
+    return list(arr)
+
+
+def layer_stored_bytes(tokens, hidden, ffn, group, bits, with_scales=True):
+    arr = (_INT * _SLOTS)(*bits)
+    return load_library().agoq_layer_stored_bytes(tokens, hidden, ffn, group, ctypes.byref(arr),
+                                                  1 if with_scales else 0)

@@ -1,0 +1,479 @@
+// HIP kernels and C ABI of the AGoQ quantization hot path for gfx950 (MI355X).
+//
+// Every kernel here is a streaming pass: read a tensor once, write its encoded
+// (or decoded) form once.  The bound is HBM bandwidth, so the design goals are
+//   * 16-byte loads, several in flight per lane, issued before any use;
+//   * one quantization group per DPP row (16 lanes) or half row, so the
+//     abs-max reduction is a few cross-lane VALU ops and never touches LDS;
+//   * codes packed in registers and stored as whole dwords / 16-byte vectors.
+// No MFMA: nothing on this path is a contraction.
+//
+// Arithmetic contract (identical for all kernels): IEEE binary32, round to
+// nearest even, no contraction.  scale = amax / qmax and inv = qmax / amax are
+// true divisions; code = rint(x * inv).  rint is realised by adding 1.5 * 2^23:
+// for |t| <= 2^22 the sum lies in [2^23, 2^24) where the spacing of binary32 is
+// exactly 1, so the addition itself rounds t to the nearest integer, ties to
+// even, and the low mantissa bits hold the integer in two's complement.
+// Because |x| <= amax, |x * inv| <= qmax * (1 + 2^-22), whose nearest integer
+// is at most qmax: the codes need no clamp.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "agoq.h"
+
+namespace {
+
+typedef uint32_t u32;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 256;           // 4 wavefronts
+constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
+constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
+
+__device__ __forceinline__ float as_f32(u32 u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ u32 as_u32(float f) { return __builtin_bit_cast(u32, f); }
+
+// DPP controls (row = 16 lanes)
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i within 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i within 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ u32 dpp_max_u32(u32 v)
+{
+    u32 o = (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+    return v > o ? v : o;
+}
+
+// Maximum over the LANES consecutive lanes (4, 8 or 16, aligned) that share a group.
+// Operates on magnitude bit patterns: for non-negative finite floats the unsigned
+// integer order of the bits is the order of the values.
+template <int LANES>
+__device__ __forceinline__ u32 group_max_bits(u32 m)
+{
+    m = dpp_max_u32<kDppXor1>(m);
+    m = dpp_max_u32<kDppXor2>(m);
+    if (LANES >= 8) m = dpp_max_u32<kDppHalfMirror>(m);
+    if (LANES >= 16) m = dpp_max_u32<kDppMirror>(m);
+    return m;
+}
+
+__device__ __forceinline__ u32 umax(u32 a, u32 b) { return a > b ? a : b; }
+
+// scale and inv of a group from the bits of its abs-max.
+template <int QMAX>
+__device__ __forceinline__ void scale_and_inv(u32 amax_bits, float& scale, float& inv)
+{
+    const float amax = as_f32(amax_bits);
+    const bool live = amax_bits >= kAmaxMinBits;
+    const float den = live ? amax : 1.0f;
+    const float s = __fdiv_rn(amax, (float)QMAX);
+    const float r = __fdiv_rn((float)QMAX, den);
+    scale = live ? s : 0.0f;
+    inv = live ? r : 0.0f;
+}
+
+// round(x * inv) as the low bits of the returned word (two's complement).
+__device__ __forceinline__ u32 code_bits(float x, float inv)
+{
+    return as_u32(__fadd_rn(__fmul_rn(x, inv), kRoundMagic));
+}
+
+__device__ __forceinline__ u32 push_nibble(u32 packed, u32 code)
+{
+    // shifts the pair {code, packed} right by 4: the new nibble enters at the top, so
+    // after eight pushes the first element sits in bits 0-3
+    return __builtin_amdgcn_alignbit(code, packed, 4);
+}
+
+__device__ __forceinline__ u32 push_byte(u32 packed, u32 code)
+{
+    return __builtin_amdgcn_alignbit(code, packed, 8);
+}
+
+__device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);   // round to nearest even
+    return __builtin_bit_cast(u32, h);
+}
+
+// ---------------------------------------------------------------------------
+// Activation quantize: bf16 -> 4- or 8-bit codes + fp32 scale per group.
+// One lane owns 8 consecutive elements (one 16-byte load) of a group;
+// GROUP/8 consecutive lanes own a group.
+// ---------------------------------------------------------------------------
+template <int BITS, int GROUP, int UNROLL>
+__global__ __launch_bounds__(kBlock) void act_quant_kernel(const u32x4* __restrict__ x,
+                                                           int64_t n_vec, void* __restrict__ codes,
+                                                           float* __restrict__ scales)
+{
+    constexpr int LANES = GROUP / 8;
+    constexpr int QMAX = (1 << (BITS - 1)) - 1;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    u32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        v[u] = u32x4{0, 0, 0, 0};
+        if (vi < n_vec) v[u] = x[vi];
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        float f[8];
+        u32 m = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32 w = v[u][j];
+            f[2 * j] = as_f32(w << 16);
+            f[2 * j + 1] = as_f32(w & 0xFFFF0000u);
+            m = umax(m, umax((w << 16) & 0x7FFFFFFFu, w & 0x7FFF0000u));
+        }
+        m = group_max_bits<LANES>(m);
+        float scale, inv;
+        scale_and_inv<QMAX>(m, scale, inv);
+        if (vi < n_vec) {
+            if (BITS == 4) {
+                u32 p = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
+                ((u32*)codes)[vi] = p;
+            } else {
+                u32 p0 = 0, p1 = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
+#pragma unroll
+                for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
+                ((u32x2*)codes)[vi] = u32x2{p0, p1};
+            }
+            if ((threadIdx.x & (LANES - 1)) == 0) scales[vi / LANES] = scale;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Activation dequantize: codes + scales -> bf16.  One lane produces 8 elements
+// (one 16-byte store).
+// ---------------------------------------------------------------------------
+template <int BITS, int GROUP, int UNROLL>
+__global__ __launch_bounds__(kBlock) void act_dequant_kernel(const void* __restrict__ codes,
+                                                             const float* __restrict__ scales,
+                                                             int64_t n_vec, u32x4* __restrict__ y)
+{
+    constexpr int LANES = GROUP / 8;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    u32x2 c[UNROLL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        c[u] = u32x2{0, 0};
+        s[u] = 0.0f;
+        if (vi < n_vec) {
+            if (BITS == 4)
+                c[u][0] = ((const u32*)codes)[vi];
+            else
+                c[u] = ((const u32x2*)codes)[vi];
+            s[u] = scales[vi / LANES];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        float f[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            int q;
+            if (BITS == 4)
+                q = __builtin_amdgcn_sbfe((int)c[u][0], 4 * j, 4);
+            else
+                q = __builtin_amdgcn_sbfe((int)c[u][j >> 2], 8 * (j & 3), 8);
+            f[j] = __fmul_rn((float)q, s[u]);
+        }
+        if (vi < n_vec)
+            y[vi] = u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                          pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])};
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Gradient quantize: fp32 -> int8 codes + fp32 scale per group.
+// 16 lanes (one DPP row) own a group; a lane holds VPL 16-byte vectors of it,
+// vector p of lane l being elements [p*64 + 4l, p*64 + 4l + 4) of the group, so
+// each load instruction reads whole 256-byte runs.
+// ---------------------------------------------------------------------------
+template <int GROUP, int UNROLL>
+__global__ __launch_bounds__(kBlock) void grad_quant_kernel(const f32x4* __restrict__ g,
+                                                            int64_t n_groups,
+                                                            u32* __restrict__ codes,
+                                                            float* __restrict__ scales)
+{
+    constexpr int VPL = GROUP / 64;   // vectors per lane: 1 (group 64) or 2 (group 128)
+    constexpr int VPG = GROUP / 4;    // vectors per group
+    const int lane16 = threadIdx.x & 15;
+    const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    f32x4 v[UNROLL][VPL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+#pragma unroll
+        for (int p = 0; p < VPL; ++p) {
+            v[u][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (grp < n_groups) v[u][p] = g[grp * VPG + p * 16 + lane16];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+        u32 m = 0;
+#pragma unroll
+        for (int p = 0; p < VPL; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) m = umax(m, as_u32(v[u][p][j]) & 0x7FFFFFFFu);
+        m = group_max_bits<16>(m);
+        float scale, inv;
+        scale_and_inv<127>(m, scale, inv);
+        if (grp < n_groups) {
+#pragma unroll
+            for (int p = 0; p < VPL; ++p) {
+                u32 w = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w = push_byte(w, code_bits(v[u][p][j], inv));
+                codes[grp * VPG + p * 16 + lane16] = w;
+            }
+            if (lane16 == 0) scales[grp] = scale;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Local reduce of K int8 chunks + requantize.  One lane owns 16 consecutive
+// elements (one 16-byte load per chunk, one 16-byte store); GROUP/16 lanes own
+// a group.  acc = fma(code_k, scale_k, acc) for k = 0..K-1 in that order.
+// KT > 0: K known at compile time (all loads hoisted); KT == 0: run-time K.
+// ---------------------------------------------------------------------------
+template <int GROUP>
+__device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi,
+                                              bool valid, u32x4* __restrict__ out_codes,
+                                              float* __restrict__ out_scales)
+{
+    constexpr int LANES = GROUP / 16;
+    u32 m = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
+    m = group_max_bits<LANES>(m);
+    float scale, inv;
+    scale_and_inv<127>(m, scale, inv);
+    if (valid) {
+        u32x4 w = {0, 0, 0, 0};
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[d] = push_byte(w[d], code_bits(acc[4 * d + j], inv));
+        out_codes[vi] = w;
+        if ((threadIdx.x & (LANES - 1)) == 0) out_scales[vi / LANES] = scale;
+    }
+}
+
+__device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, float s)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = __builtin_amdgcn_sbfe((int)c[d], 8 * j, 8);
+            acc[4 * d + j] = __fmaf_rn((float)q, s, acc[4 * d + j]);
+        }
+}
+
+template <int GROUP, int KT>
+__global__ __launch_bounds__(kBlock) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
+                                                             int64_t stride_codes,
+                                                             const float* __restrict__ in_scales,
+                                                             int64_t stride_scales, int K,
+                                                             int64_t n_vec,
+                                                             u32x4* __restrict__ out_codes,
+                                                             float* __restrict__ out_scales)
+{
+    constexpr int LANES = GROUP / 16;
+    const int64_t vi = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool valid = vi < n_vec;
+    const int64_t vc = valid ? vi : 0;      // out-of-range lanes read element 0, store nothing
+    const int64_t grp = vc / LANES;
+    float acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+
+    if (KT > 0) {
+        u32x4 c[KT > 0 ? KT : 1];
+        float s[KT > 0 ? KT : 1];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            c[k] = ((const u32x4*)(in_codes + (int64_t)k * stride_codes))[vc];
+            s[k] = in_scales[(int64_t)k * stride_scales + grp];
+        }
+#pragma unroll
+        for (int k = 0; k < KT; ++k) reduce_term(acc, c[k], s[k]);
+    } else {
+        int k = 0;
+        for (; k + 4 <= K; k += 4) {
+            u32x4 c[4];
+            float s[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                c[t] = ((const u32x4*)(in_codes + (int64_t)(k + t) * stride_codes))[vc];
+                s[t] = in_scales[(int64_t)(k + t) * stride_scales + grp];
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) reduce_term(acc, c[t], s[t]);
+        }
+        for (; k < K; ++k) {
+            const u32x4 c = ((const u32x4*)(in_codes + (int64_t)k * stride_codes))[vc];
+            const float s = in_scales[(int64_t)k * stride_scales + grp];
+            reduce_term(acc, c, s);
+        }
+    }
+    reduce_finish<GROUP>(acc, vi, valid, out_codes, out_scales);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline int check_common(int64_t numel, int group)
+{
+    if (group != 64 && group != 128) return AGOQ_ERR_GROUP;
+    if (numel <= 0 || numel % group != 0) return AGOQ_ERR_SHAPE;
+    return AGOQ_OK;
+}
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? AGOQ_OK : AGOQ_ERR_HIP;
+}
+
+inline unsigned blocks_for(int64_t items, int per_block)
+{
+    return (unsigned)((items + per_block - 1) / per_block);
+}
+
+constexpr int kActUnroll = 4;
+constexpr int kGradUnroll = 2;
+
+}  // namespace
+
+extern "C" {
+
+int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void* codes,
+                   float* scales, void* stream)
+{
+    if (!x_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
+    if (bits != 4 && bits != 8) return AGOQ_ERR_BITS;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    const dim3 grid(blocks_for(n_vec, kBlock * kActUnroll)), block(kBlock);
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4* x = (const u32x4*)x_bf16;
+    if (bits == 4 && group == 128)
+        act_quant_kernel<4, 128, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    else if (bits == 4)
+        act_quant_kernel<4, 64, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    else if (group == 128)
+        act_quant_kernel<8, 128, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    else
+        act_quant_kernel<8, 64, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    return launch_status();
+}
+
+int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int group, int bits,
+                     void* y_bf16, void* stream)
+{
+    if (!codes || !scales || !y_bf16) return AGOQ_ERR_NULL;
+    if (bits != 4 && bits != 8) return AGOQ_ERR_BITS;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    const dim3 grid(blocks_for(n_vec, kBlock * kActUnroll)), block(kBlock);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* y = (u32x4*)y_bf16;
+    if (bits == 4 && group == 128)
+        act_dequant_kernel<4, 128, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else if (bits == 4)
+        act_dequant_kernel<4, 64, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else if (group == 128)
+        act_dequant_kernel<8, 128, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else
+        act_dequant_kernel<8, 64, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    return launch_status();
+}
+
+int agoq_grad_quant(const float* grad, int64_t numel, int group, int8_t* codes, float* scales,
+                    void* stream)
+{
+    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_groups = numel / group;
+    const dim3 grid(blocks_for(n_groups * 16, kBlock * kGradUnroll)), block(kBlock);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_quant_kernel<128, kGradUnroll><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
+                                                                    (u32*)codes, scales);
+    else
+        grad_quant_kernel<64, kGradUnroll><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
+                                                                   (u32*)codes, scales);
+    return launch_status();
+}
+
+int agoq_grad_reduce_requant(const int8_t* in_codes, int64_t chunk_stride_codes,
+                             const float* in_scales, int64_t chunk_stride_scales, int K,
+                             int64_t numel, int group, int8_t* out_codes, float* out_scales,
+                             void* stream)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (K < 1 || K > 64) return AGOQ_ERR_K;
+    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
+    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
+        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
+        return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 16;
+    const dim3 grid(blocks_for(n_vec, kBlock)), block(kBlock);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* oc = (u32x4*)out_codes;
+#define AGOQ_LAUNCH_REDUCE(G, KT)                                                              \
+    grad_reduce_kernel<G, KT><<<grid, block, 0, st>>>(in_codes, chunk_stride_codes, in_scales, \
+                                                      chunk_stride_scales, K, n_vec, oc, out_scales)
+    if (group == 128) {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE(128, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE(128, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE(128, 16); break;
+        default: AGOQ_LAUNCH_REDUCE(128, 0); break;
+        }
+    } else {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE(64, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE(64, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE(64, 16); break;
+        default: AGOQ_LAUNCH_REDUCE(64, 0); break;
+        }
+    }
+#undef AGOQ_LAUNCH_REDUCE
+    return launch_status();
+}
+
+}  // extern "C"

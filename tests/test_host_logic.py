@@ -1,0 +1,105 @@
+"""CPU-only checks of the library's host side: it loads, exports every symbol the header
+declares, and its pure host helpers give the values the paper prints."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def agoq():
+    import paper_2605_00539_amd as lib
+    if not os.path.exists(lib.library_path()):
+        from paper_2605_00539_amd import build
+        build.build()
+    lib.load_library()
+    return lib
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "agoq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(agoq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(agoq):
+    names = declared_symbols()
+    assert {"agoq_act_quant", "agoq_act_dequant", "agoq_grad_quant",
+            "agoq_grad_reduce_requant"} <= set(names)
+    L = ctypes.CDLL(agoq.library_path())
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_size_helpers(agoq):
+    assert agoq.codes_bytes(1 << 20, 4) == 1 << 19
+    assert agoq.codes_bytes(1 << 20, 8) == 1 << 20
+    assert agoq.codes_bytes(128, 5) == -1
+    assert agoq.num_groups(4096 * 14336, 128) == 4096 * 14336 // 128
+    assert agoq.num_groups(100, 64) == -1
+    assert agoq.strerror(0) == "ok" and "group" in agoq.strerror(3)
+    assert agoq.version() >= 100
+
+
+def load_kv(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = line.split(":")
+                out[k.strip()] = v.split()
+    return out
+
+
+def test_dbca_values_printed_in_the_paper(agoq):
+    gold = load_kv("dbca_four_stages.txt")
+    n = int(gold["n_stages"][0])
+    assert [agoq.dbca_stored_microbatches(n, i) for i in range(1, n + 1)] == \
+        [int(v) for v in gold["stored_microbatches"]]
+    assert [agoq.dbca_bits(n, i) for i in range(1, n + 1)] == [int(v) for v in gold["bits"]]
+    assert agoq.dbca_stored_microbatches(4, 0) == -1 and agoq.dbca_stored_microbatches(4, 5) == -1
+    with pytest.raises(agoq.AgoqError):
+        agoq.dbca_bits(4, 5)
+
+
+def test_dbca_matches_oracle_for_all_small_pipelines(agoq, ref):
+    for n in range(1, 33):
+        for i in range(1, n + 1):
+            assert agoq.dbca_bits(n, i) == ref.dbca_bits(n, i)
+            assert agoq.dbca_stored_microbatches(n, i) == ref.dbca_stored_microbatches(n, i)
+
+
+def test_layer_memory_units_of_the_paper(agoq):
+    # Table "memory_comparison": with every stored tensor at 4 bits (code bytes only, ffn = 4h)
+    # a layer keeps 0.25U + 0.5U + 2U = 2.75U besides attention's 5U
+    gold = {k: float(v[0]) for k, v in load_kv("memory_units.txt").items()}
+    tokens, hidden = 4096, 4096
+    U = tokens * hidden * 2
+    bits = agoq.layer_bitmap(4)
+    assert bits == [4, 4, 4, 4, 4]
+    stored = agoq.layer_stored_bytes(tokens, hidden, 4 * hidden, 128, bits, with_scales=False)
+    want_units = gold["agoq_linear"] + gold["agoq_rmsnorm"] + gold["agoq_act_func"]
+    assert stored == int(want_units * U)
+    assert want_units + gold["agoq_attention"] == gold["agoq_total"]
+    # per component
+    one = lambda slot_bits: agoq.layer_stored_bytes(tokens, hidden, 4 * hidden, 128, slot_bits, False)
+    assert stored - one([8, 4, 4, 4, 4]) == -int(0.25 * U)       # one norm input: 0.25U at 4 bits
+    # scales add 4 bytes per group of 128: 4.25 bits per element in total
+    with_scales = agoq.layer_stored_bytes(tokens, hidden, 4 * hidden, 128, bits, True)
+    assert with_scales * 16 == stored * 17
+
+
+def test_stage_bitmaps_average_width(agoq):
+    # seq 8192 on the 8B shape: closed forms for the four stage maps (codes + scales)
+    want = {4: 178257920, 5: 211812352, 6: 270532608, 8: 346030080}
+    for b, total in want.items():
+        bits = agoq.layer_bitmap(b)
+        assert agoq.layer_stored_bytes(8192, 4096, 14336, 128, bits, True) == total
+    assert agoq.layer_bitmap(5) == [8, 4, 8, 4, 4] and agoq.layer_bitmap(6) == [8, 4, 8, 8, 4]
+    with pytest.raises(agoq.AgoqError):
+        agoq.layer_bitmap(3)
