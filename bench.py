@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the AGoQ quantization hot path on one MI355X.
+
+One "step" is one pass of the whole path over the LLaMA-8B-shaped workload:
+  * quantize the five stored activations of a decoder layer (seq 4096, micro-batch 1:
+    three [4096,4096] and two [4096,14336] bf16 tensors) under the bit map
+    norm inputs 8-bit, linear / FFN-intermediate inputs 4-bit, group 128;
+  * store one decoder layer's fp32 gradient (218,103,808 elements) as int8, group 128;
+  * local reduce + requantize of K=8 such int8 gradients (the receive buffer of the
+    All-to-All), n = 218,103,808;
+  * dequantize the five stored activations back to bf16.
+The order puts ~3 GB of gradient traffic between writing the activation codes and reading
+them back, so no launch finds its input in the last-level cache.
+
+The figure of merit is effective HBM bandwidth: algorithmic bytes (read the tensor once,
+write codes + scales once, or the reverse) divided by time.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0
+GROUP = 128
+K_CHUNKS = 8
+SLOT_NAMES = ("norm1_in", "oproj_in", "norm2_in", "gate", "up")
+
+
+def algo_bytes_act(numel, bits, group=GROUP):
+    return numel * 2 + numel * bits // 8 + 4 * (numel // group)
+
+
+def algo_bytes_grad_quant(numel, group=GROUP):
+    return numel * 4 + numel + 4 * (numel // group)
+
+
+def algo_bytes_reduce(numel, K, group=GROUP):
+    return (K + 1) * (numel + 4 * (numel // group))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's share of the path and uses no collective; "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as wl
+    import paper_2605_00539_amd as agoq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    agoq.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- inputs (seeded, synthetic, generated on the device) ---------------------------
+    acfg = wl.CONFIGS["llama8b_act"]
+    gcfg = wl.CONFIGS["llama8b_grad"]
+    rows = acfg["acts"]["A"]["rows"]
+    hidden, ffn = acfg["acts"]["A"]["cols"], acfg["acts"]["F"]["cols"]
+    bitmap = agoq.layer_bitmap(5)                 # [8, 4, 8, 4, 4]
+    acts, act_bits = [], []
+    for slot, name in enumerate(SLOT_NAMES):
+        cols = ffn if name in ("gate", "up") else hidden
+        x = wl.act_device(rows, cols, acfg["seed"] + slot, acfg["dist"],
+                          wl.n_outlier_channels(cols, acfg["outlier_frac"]), acfg["outlier_scale"])
+        acts.append(x.reshape(-1))
+        act_bits.append(bitmap[slot])
+    n_grad = gcfg["n"]
+    grad = wl.grad_device(n_grad, gcfg["seed"], gcfg["sigma"], gcfg["spike_frac"], gcfg["spike_scale"])
+    # the K peers' int8 gradients: quantize K seeded gradients with the library (set-up, untimed)
+    n_groups = n_grad // GROUP
+    in_codes = torch.empty((K_CHUNKS, n_grad), dtype=torch.int8, device=dev)
+    in_scales = torch.empty((K_CHUNKS, n_groups), dtype=torch.float32, device=dev)
+    for k in range(K_CHUNKS):
+        gk = grad if k == 0 else wl.grad_device(n_grad, gcfg["seed"] + 1 + k, gcfg["sigma"],
+                                                gcfg["spike_frac"], gcfg["spike_scale"])
+        agoq.grad_quant(gk, GROUP, codes=in_codes[k], scales=in_scales[k])
+        torch.cuda.synchronize()
+        del gk
+
+    # ---- outputs, allocated once ------------------------------------------------------
+    act_codes = [torch.empty(x.numel() * b // 8, dtype=torch.uint8, device=dev) for x, b in zip(acts, act_bits)]
+    act_scales = [torch.empty(x.numel() // GROUP, dtype=torch.float32, device=dev) for x in acts]
+    act_out = [torch.empty_like(x) for x in acts]
+    g_codes = torch.empty(n_grad, dtype=torch.int8, device=dev)
+    g_scales = torch.empty(n_groups, dtype=torch.float32, device=dev)
+    r_codes = torch.empty(n_grad, dtype=torch.int8, device=dev)
+    r_scales = torch.empty(n_groups, dtype=torch.float32, device=dev)
+
+    bytes_quant = sum(algo_bytes_act(x.numel(), b) for x, b in zip(acts, act_bits))
+    bytes_dequant = bytes_quant
+    bytes_gq = algo_bytes_grad_quant(n_grad)
+    bytes_red = algo_bytes_reduce(n_grad, K_CHUNKS)
+    bytes_step = bytes_quant + bytes_dequant + bytes_gq + bytes_red
+
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        """One pass of the path.  ev: optional dict of per-kernel-class event lists."""
+        def mark(name):
+            if ev is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record(stream)
+                ev[name].append(e)
+        mark("t0")
+        for x, b, c, s in zip(acts, act_bits, act_codes, act_scales):
+            agoq.act_quant(x, GROUP, b, codes=c, scales=s, stream=stream)
+        mark("t1")
+        agoq.grad_quant(grad, GROUP, codes=g_codes, scales=g_scales, stream=stream)
+        mark("t2")
+        agoq.grad_reduce_requant(in_codes, in_scales, n_grad, GROUP, out_codes=r_codes,
+                                 out_scales=r_scales, stream=stream)
+        mark("t3")
+        for x, b, c, s, y in zip(acts, act_bits, act_codes, act_scales, act_out):
+            agoq.act_dequant(c, s, x.numel(), GROUP, b, out=y, stream=stream)
+        mark("t4")
+
+    # ---- warm-up, then the timed region -------------------------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # events around the dominant kernel (the K-way reduce) of every timed step, on the
+    # stream the kernels are launched on
+    red_events = []
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        for x, b, c, s in zip(acts, act_bits, act_codes, act_scales):
+            agoq.act_quant(x, GROUP, b, codes=c, scales=s, stream=stream)
+        agoq.grad_quant(grad, GROUP, codes=g_codes, scales=g_scales, stream=stream)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        agoq.grad_reduce_requant(in_codes, in_scales, n_grad, GROUP, out_codes=r_codes,
+                                 out_scales=r_scales, stream=stream)
+        e1.record(stream)
+        red_events.append((e0, e1))
+        for x, b, c, s, y in zip(acts, act_bits, act_codes, act_scales, act_out):
+            agoq.act_dequant(c, s, x.numel(), GROUP, b, out=y, stream=stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = bytes_step / (elapsed / args.steps) / 1e9
+    red_ms = sum(a.elapsed_time(b) for a, b in red_events) / len(red_events)
+    red_gbps = bytes_red / (red_ms * 1e-3) / 1e9
+
+    # ---- per-kernel-class breakdown (separate, untimed for `value`) ----------------------
+    ev = {k: [] for k in ("t0", "t1", "t2", "t3", "t4")}
+    for _ in range(min(args.steps, 20)):
+        step(ev)
+    torch.cuda.synchronize()
+
+    def avg_ms(a, b):
+        return sum(x.elapsed_time(y) for x, y in zip(ev[a], ev[b])) / len(ev[a])
+
+    kernels = {}
+    for name, a, b, nbytes in (("act_quant_layer", "t0", "t1", bytes_quant),
+                               ("grad_quant", "t1", "t2", bytes_gq),
+                               ("grad_reduce_requant_k8", "t2", "t3", bytes_red),
+                               ("act_dequant_layer", "t3", "t4", bytes_dequant)):
+        ms = avg_ms(a, b)
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        kernels[name] = {"us": round(ms * 1e3, 2), "GB/s": round(gbps, 1),
+                         "frac_of_peak": round(gbps / PEAK_HBM_GBPS, 4), "algo_MB": round(nbytes / 1e6, 1)}
+
+    # ---- CPU baseline: the oracle on a bounded sample of the same inputs -------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_codes,
+                           g_scales, in_codes, in_scales, r_codes, r_scales, n_grad)
+
+    out = {
+        "metric": "effective HBM GB/s (quant, dequant, grad reduce) and % of MI355X peak",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "LLaMA-8B-shaped decoder layer: 5 stored activations seq 4096 mb 1 "
+                        "(bits %s, group 128) quant+dequant, fp32 gradient of 218,103,808 -> int8, "
+                        "8-chunk local reduce+requant" % (bitmap,),
+            "group": GROUP, "K": K_CHUNKS, "algo_bytes_per_step": bytes_step,
+        },
+        "frac_of_peak": round(value / PEAK_HBM_GBPS, 4),
+        "roofline": {
+            "bound": "hbm", "kernel": "grad_reduce_kernel<128,8>",
+            "achieved": round(red_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+            "frac": round(red_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+            "algo_bytes_per_launch": bytes_red, "avg_launch_us": round(red_ms * 1e3, 2),
+        },
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_codes, g_scales,
+                 in_codes, in_scales, r_codes, r_scales, n_grad):
+    """Time the oracle (as it stands) on the host, on a bounded sample of the step's inputs:
+    all five activations (quant + dequant), the first 1/4 of the gradient (grad quant), and
+    the first 1/16 of the 8 int8 chunks (reduce).  Also checks the GPU outputs of the last
+    step against the oracle on that sample."""
+    import numpy as np
+    import oracle
+
+    def bits_of(t):
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+    threads = oracle.max_threads()
+    nbytes, secs, ok = 0, 0.0, True
+    for x, b, c, s, y in zip(acts, act_bits, act_codes, act_scales, act_out):
+        xb = bits_of(x)
+        t = time.perf_counter()
+        oc, os_ = oracle.act_quant(xb, GROUP, b)
+        oy = oracle.act_dequant(oc, os_, xb.size, GROUP, b)
+        secs += time.perf_counter() - t
+        nbytes += 2 * algo_bytes_act(xb.size, b)
+        ok &= np.array_equal(c.cpu().numpy(), oc) and np.array_equal(
+            s.cpu().numpy().view(np.uint32), os_.view(np.uint32)) and np.array_equal(bits_of(y), oy)
+    ng = (n_grad // 4) // GROUP * GROUP
+    gh = grad[:ng].cpu().numpy()
+    t = time.perf_counter()
+    oc, os_ = oracle.grad_quant(gh, GROUP)
+    secs += time.perf_counter() - t
+    nbytes += algo_bytes_grad_quant(ng)
+    ok &= np.array_equal(g_codes[:ng].cpu().numpy(), oc) and np.array_equal(
+        g_scales[:ng // GROUP].cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    nr = (n_grad // 16) // GROUP * GROUP
+    ch = np.ascontiguousarray(in_codes[:, :nr].cpu().numpy())
+    sh = np.ascontiguousarray(in_scales[:, :nr // GROUP].cpu().numpy())
+    t = time.perf_counter()
+    oc, os_ = oracle.grad_reduce_requant(ch, sh, nr, GROUP)
+    secs += time.perf_counter() - t
+    nbytes += algo_bytes_reduce(nr, K_CHUNKS)
+    ok &= np.array_equal(r_codes[:nr].cpu().numpy(), oc) and np.array_equal(
+        r_scales[:nr // GROUP].cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    return {
+        "value": round(nbytes / secs / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": "all 5 activations quant+dequant, first 1/4 of the gradient (grad quant), "
+                  "first 1/16 of the 8 chunks (reduce): %.0f MB algorithmic in %.2f s" % (nbytes / 1e6, secs),
+        "gpu_matches_oracle_on_sample": bool(ok),
+    }
+
+
+if __name__ == "__main__":
+    sys.exit(main())
