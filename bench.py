@@ -25,6 +25,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0
+# HBM bytes per launch of the K=8 reduce kernel on this workload, from hardware counters
+# (FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy; summary under profiles/)
+TRAFFIC_REDUCE_K8_BYTES = 2032821975
 GROUP = 128
 K_CHUNKS = 8
 SLOT_NAMES = ("norm1_in", "oproj_in", "norm2_in", "gate", "up")
@@ -48,6 +51,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 1 GiB device copy a few times and exit: gives the hardware "
+                         "counters a kernel of known traffic to be scaled against")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share of the path and uses no collective; "
@@ -64,6 +70,16 @@ def main():
     agoq.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_copy:
+        n = 1 << 28                                   # 1 GiB of fp32 read, 1 GiB written
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "read_bytes_per_launch": 4 * n,
+                          "write_bytes_per_launch": 4 * n, "launches": 5}))
+        return 0
 
     # ---- inputs (seeded, synthetic, generated on the device) ---------------------------
     acfg = wl.CONFIGS["llama8b_act"]
@@ -204,7 +220,7 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "grad_reduce_kernel<128,8>",
             "achieved": round(red_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-            "frac": round(red_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+            "frac": round(red_gbps / PEAK_HBM_GBPS, 4), "traffic": TRAFFIC_REDUCE_K8_BYTES,
             "algo_bytes_per_launch": bytes_red, "avg_launch_us": round(red_ms * 1e3, 2),
         },
         "kernels": kernels,

@@ -29,12 +29,90 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBlock = 256;           // 4 wavefronts
+// ---- launch shapes and cache hints, per kernel (measured on MI355X) ------------------
+// Each macro can be overridden on the compiler command line for tuning sweeps.
+#ifndef AGOQ_AQ_BLOCK          // activation quantize
+#define AGOQ_AQ_BLOCK 128
+#endif
+#ifndef AGOQ_AQ_UNROLL
+#define AGOQ_AQ_UNROLL 2
+#endif
+#ifndef AGOQ_AQ_NTL
+#define AGOQ_AQ_NTL 1
+#endif
+#ifndef AGOQ_AQ_NTS
+#define AGOQ_AQ_NTS 1
+#endif
+#ifndef AGOQ_DQ_BLOCK          // activation dequantize
+#define AGOQ_DQ_BLOCK 512
+#endif
+#ifndef AGOQ_DQ_UNROLL4
+#define AGOQ_DQ_UNROLL4 4
+#endif
+#ifndef AGOQ_DQ_UNROLL8        // 8-bit codes, large tensors
+#define AGOQ_DQ_UNROLL8 2
+#endif
+#ifndef AGOQ_DQ_UNROLL8_SMALL  // 8-bit codes, tensors that fit one resident set of workgroups
+#define AGOQ_DQ_UNROLL8_SMALL 4
+#endif
+#ifndef AGOQ_DQ_SMALL_VECS     // "small" = at most this many 16-byte output vectors
+#define AGOQ_DQ_SMALL_VECS (4 << 20)
+#endif
+#ifndef AGOQ_DQ_NTC            // code loads
+#define AGOQ_DQ_NTC 1
+#endif
+#ifndef AGOQ_DQ_NTSC           // scale loads
+#define AGOQ_DQ_NTSC 0
+#endif
+#ifndef AGOQ_DQ_NTS
+#define AGOQ_DQ_NTS 1
+#endif
+#ifndef AGOQ_GQ_BLOCK          // gradient quantize
+#define AGOQ_GQ_BLOCK 256
+#endif
+#ifndef AGOQ_GQ_UNROLL
+#define AGOQ_GQ_UNROLL 1
+#endif
+#ifndef AGOQ_GQ_NTL
+#define AGOQ_GQ_NTL 1
+#endif
+#ifndef AGOQ_GQ_NTS
+#define AGOQ_GQ_NTS 1
+#endif
+#ifndef AGOQ_RD_BLOCK          // reduce + requantize
+#define AGOQ_RD_BLOCK 512
+#endif
+#ifndef AGOQ_RD_NTC
+#define AGOQ_RD_NTC 1
+#endif
+#ifndef AGOQ_RD_NTSC
+#define AGOQ_RD_NTSC 1
+#endif
+#ifndef AGOQ_RD_NTS
+#define AGOQ_RD_NTS 1
+#endif
+
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
 constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
 
 __device__ __forceinline__ float as_f32(u32 u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ u32 as_u32(float f) { return __builtin_bit_cast(u32, f); }
+
+// Streaming loads and stores: every byte is touched once, so the caches may drop it early.
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* p, T v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
 
 // DPP controls (row = 16 lanes)
 constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
@@ -71,8 +149,13 @@ __device__ __forceinline__ void scale_and_inv(u32 amax_bits, float& scale, float
     const float amax = as_f32(amax_bits);
     const bool live = amax_bits >= kAmaxMinBits;
     const float den = live ? amax : 1.0f;
+#ifdef AGOQ_EXP_NODIV   // timing experiment only: wrong arithmetic
+    const float s = amax * (1.0f / (float)QMAX);
+    const float r = (float)QMAX * __builtin_amdgcn_rcpf(den);
+#else
     const float s = __fdiv_rn(amax, (float)QMAX);
     const float r = __fdiv_rn((float)QMAX, den);
+#endif
     scale = live ? s : 0.0f;
     inv = live ? r : 0.0f;
 }
@@ -110,12 +193,14 @@ __device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
 // GROUP/8 consecutive lanes own a group.
 // ---------------------------------------------------------------------------
 template <int BITS, int GROUP, int UNROLL>
-__global__ __launch_bounds__(kBlock) void act_quant_kernel(const u32x4* __restrict__ x,
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
                                                            int64_t n_vec, void* __restrict__ codes,
                                                            float* __restrict__ scales)
 {
     constexpr int LANES = GROUP / 8;
     constexpr int QMAX = (1 << (BITS - 1)) - 1;
+    constexpr int kBlock = AGOQ_AQ_BLOCK;
+    constexpr bool NTL = AGOQ_AQ_NTL, NTS = AGOQ_AQ_NTS;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
     u32x4 v[UNROLL];
@@ -123,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void act_quant_kernel(const u32x4* __restri
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         v[u] = u32x4{0, 0, 0, 0};
-        if (vi < n_vec) v[u] = x[vi];
+        if (vi < n_vec) v[u] = ld<NTL>(x + vi);
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -145,16 +230,16 @@ __global__ __launch_bounds__(kBlock) void act_quant_kernel(const u32x4* __restri
                 u32 p = 0;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
-                ((u32*)codes)[vi] = p;
+                st<NTS>((u32*)codes + vi, p);
             } else {
                 u32 p0 = 0, p1 = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
 #pragma unroll
                 for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
-                ((u32x2*)codes)[vi] = u32x2{p0, p1};
+                st<NTS>((u32x2*)codes + vi, u32x2{p0, p1});
             }
-            if ((threadIdx.x & (LANES - 1)) == 0) scales[vi / LANES] = scale;
+            if ((threadIdx.x & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
         }
     }
 }
@@ -164,11 +249,13 @@ __global__ __launch_bounds__(kBlock) void act_quant_kernel(const u32x4* __restri
 // (one 16-byte store).
 // ---------------------------------------------------------------------------
 template <int BITS, int GROUP, int UNROLL>
-__global__ __launch_bounds__(kBlock) void act_dequant_kernel(const void* __restrict__ codes,
+__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
                                                              const float* __restrict__ scales,
                                                              int64_t n_vec, u32x4* __restrict__ y)
 {
     constexpr int LANES = GROUP / 8;
+    constexpr int kBlock = AGOQ_DQ_BLOCK;
+    constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
     u32x2 c[UNROLL];
@@ -180,10 +267,10 @@ __global__ __launch_bounds__(kBlock) void act_dequant_kernel(const void* __restr
         s[u] = 0.0f;
         if (vi < n_vec) {
             if (BITS == 4)
-                c[u][0] = ((const u32*)codes)[vi];
+                c[u][0] = ld<NTC>((const u32*)codes + vi);
             else
-                c[u] = ((const u32x2*)codes)[vi];
-            s[u] = scales[vi / LANES];
+                c[u] = ld<NTC>((const u32x2*)codes + vi);
+            s[u] = ld<NTSC>(scales + vi / LANES);
         }
     }
 #pragma unroll
@@ -200,8 +287,8 @@ __global__ __launch_bounds__(kBlock) void act_dequant_kernel(const void* __restr
             f[j] = __fmul_rn((float)q, s[u]);
         }
         if (vi < n_vec)
-            y[vi] = u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
-                          pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])};
+            st<NTS>(y + vi, u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                                  pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])});
     }
 }
 
@@ -212,13 +299,15 @@ __global__ __launch_bounds__(kBlock) void act_dequant_kernel(const void* __restr
 // each load instruction reads whole 256-byte runs.
 // ---------------------------------------------------------------------------
 template <int GROUP, int UNROLL>
-__global__ __launch_bounds__(kBlock) void grad_quant_kernel(const f32x4* __restrict__ g,
+__global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* __restrict__ g,
                                                             int64_t n_groups,
                                                             u32* __restrict__ codes,
                                                             float* __restrict__ scales)
 {
     constexpr int VPL = GROUP / 64;   // vectors per lane: 1 (group 64) or 2 (group 128)
     constexpr int VPG = GROUP / 4;    // vectors per group
+    constexpr int kBlock = AGOQ_GQ_BLOCK;
+    constexpr bool NTL = AGOQ_GQ_NTL, NTS = AGOQ_GQ_NTS;
     const int lane16 = threadIdx.x & 15;
     const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
@@ -229,7 +318,7 @@ __global__ __launch_bounds__(kBlock) void grad_quant_kernel(const f32x4* __restr
 #pragma unroll
         for (int p = 0; p < VPL; ++p) {
             v[u][p] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (grp < n_groups) v[u][p] = g[grp * VPG + p * 16 + lane16];
+            if (grp < n_groups) v[u][p] = ld<NTL>(g + grp * VPG + p * 16 + lane16);
         }
     }
 #pragma unroll
@@ -249,9 +338,9 @@ __global__ __launch_bounds__(kBlock) void grad_quant_kernel(const f32x4* __restr
                 u32 w = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) w = push_byte(w, code_bits(v[u][p][j], inv));
-                codes[grp * VPG + p * 16 + lane16] = w;
+                st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
             }
-            if (lane16 == 0) scales[grp] = scale;
+            if (lane16 == 0) st<NTS>(scales + grp, scale);
         }
     }
 }
@@ -280,8 +369,8 @@ __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi
         for (int d = 0; d < 4; ++d)
 #pragma unroll
             for (int j = 0; j < 4; ++j) w[d] = push_byte(w[d], code_bits(acc[4 * d + j], inv));
-        out_codes[vi] = w;
-        if ((threadIdx.x & (LANES - 1)) == 0) out_scales[vi / LANES] = scale;
+        st<AGOQ_RD_NTS>(out_codes + vi, w);
+        if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS>(out_scales + vi / LANES, scale);
     }
 }
 
@@ -297,7 +386,7 @@ __device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, fl
 }
 
 template <int GROUP, int KT>
-__global__ __launch_bounds__(kBlock) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
+__global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
                                                              int64_t stride_codes,
                                                              const float* __restrict__ in_scales,
                                                              int64_t stride_scales, int K,
@@ -306,6 +395,8 @@ __global__ __launch_bounds__(kBlock) void grad_reduce_kernel(const int8_t* __res
                                                              float* __restrict__ out_scales)
 {
     constexpr int LANES = GROUP / 16;
+    constexpr int kBlock = AGOQ_RD_BLOCK;
+    constexpr bool NTC = AGOQ_RD_NTC, NTSC = AGOQ_RD_NTSC;
     const int64_t vi = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const bool valid = vi < n_vec;
     const int64_t vc = valid ? vi : 0;      // out-of-range lanes read element 0, store nothing
@@ -319,8 +410,8 @@ __global__ __launch_bounds__(kBlock) void grad_reduce_kernel(const int8_t* __res
         float s[KT > 0 ? KT : 1];
 #pragma unroll
         for (int k = 0; k < KT; ++k) {
-            c[k] = ((const u32x4*)(in_codes + (int64_t)k * stride_codes))[vc];
-            s[k] = in_scales[(int64_t)k * stride_scales + grp];
+            c[k] = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
+            s[k] = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
         }
 #pragma unroll
         for (int k = 0; k < KT; ++k) reduce_term(acc, c[k], s[k]);
@@ -331,15 +422,15 @@ __global__ __launch_bounds__(kBlock) void grad_reduce_kernel(const int8_t* __res
             float s[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                c[t] = ((const u32x4*)(in_codes + (int64_t)(k + t) * stride_codes))[vc];
-                s[t] = in_scales[(int64_t)(k + t) * stride_scales + grp];
+                c[t] = ld<NTC>((const u32x4*)(in_codes + (int64_t)(k + t) * stride_codes) + vc);
+                s[t] = ld<NTSC>(in_scales + (int64_t)(k + t) * stride_scales + grp);
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) reduce_term(acc, c[t], s[t]);
         }
         for (; k < K; ++k) {
-            const u32x4 c = ((const u32x4*)(in_codes + (int64_t)k * stride_codes))[vc];
-            const float s = in_scales[(int64_t)k * stride_scales + grp];
+            const u32x4 c = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
+            const float s = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
             reduce_term(acc, c, s);
         }
     }
@@ -369,8 +460,6 @@ inline unsigned blocks_for(int64_t items, int per_block)
     return (unsigned)((items + per_block - 1) / per_block);
 }
 
-constexpr int kActUnroll = 4;
-constexpr int kGradUnroll = 2;
 
 }  // namespace
 
@@ -384,17 +473,18 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    const dim3 grid(blocks_for(n_vec, kBlock * kActUnroll)), block(kBlock);
+    constexpr int U = AGOQ_AQ_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     if (bits == 4 && group == 128)
-        act_quant_kernel<4, 128, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+        act_quant_kernel<4, 128, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
     else if (bits == 4)
-        act_quant_kernel<4, 64, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+        act_quant_kernel<4, 64, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
     else if (group == 128)
-        act_quant_kernel<8, 128, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+        act_quant_kernel<8, 128, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
     else
-        act_quant_kernel<8, 64, kActUnroll><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+        act_quant_kernel<8, 64, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
     return launch_status();
 }
 
@@ -406,17 +496,26 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    const dim3 grid(blocks_for(n_vec, kBlock * kActUnroll)), block(kBlock);
+    constexpr int U4 = AGOQ_DQ_UNROLL4, U8 = AGOQ_DQ_UNROLL8, U8S = AGOQ_DQ_UNROLL8_SMALL;
+    // 8-bit codes: a tensor small enough to be resident in one go runs best with few, fat
+    // workgroups; a large one with more, thinner ones
+    const bool small = n_vec <= AGOQ_DQ_SMALL_VECS;
+    const int unroll = bits == 4 ? U4 : (small ? U8S : U8);
+    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
     if (bits == 4 && group == 128)
-        act_dequant_kernel<4, 128, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        act_dequant_kernel<4, 128, U4><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
     else if (bits == 4)
-        act_dequant_kernel<4, 64, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        act_dequant_kernel<4, 64, U4><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else if (group == 128 && small)
+        act_dequant_kernel<8, 128, U8S><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
     else if (group == 128)
-        act_dequant_kernel<8, 128, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        act_dequant_kernel<8, 128, U8><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else if (small)
+        act_dequant_kernel<8, 64, U8S><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
     else
-        act_dequant_kernel<8, 64, kActUnroll><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        act_dequant_kernel<8, 64, U8><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
     return launch_status();
 }
 
@@ -427,14 +526,15 @@ int agoq_grad_quant(const float* grad, int64_t numel, int group, int8_t* codes, 
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
     const int64_t n_groups = numel / group;
-    const dim3 grid(blocks_for(n_groups * 16, kBlock * kGradUnroll)), block(kBlock);
+    constexpr int U = AGOQ_GQ_UNROLL;
+    const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        grad_quant_kernel<128, kGradUnroll><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
-                                                                    (u32*)codes, scales);
+        grad_quant_kernel<128, U><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups, (u32*)codes,
+                                                          scales);
     else
-        grad_quant_kernel<64, kGradUnroll><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
-                                                                   (u32*)codes, scales);
+        grad_quant_kernel<64, U><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups, (u32*)codes,
+                                                         scales);
     return launch_status();
 }
 
@@ -451,7 +551,7 @@ int agoq_grad_reduce_requant(const int8_t* in_codes, int64_t chunk_stride_codes,
         misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
         return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 16;
-    const dim3 grid(blocks_for(n_vec, kBlock)), block(kBlock);
+    const dim3 grid(blocks_for(n_vec, AGOQ_RD_BLOCK)), block(AGOQ_RD_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* oc = (u32x4*)out_codes;
 #define AGOQ_LAUNCH_REDUCE(G, KT)                                                              \
