@@ -178,6 +178,12 @@ __device__ __forceinline__ u32 push_byte(u32 packed, u32 code)
     return __builtin_amdgcn_alignbit(code, packed, 8);
 }
 
+// Signed byte j of a word as a float: one conversion with a sign-extending byte select.
+__device__ __forceinline__ float byte_to_f32(u32 w, int j)
+{
+    return (float)(int8_t)((w >> (8 * j)) & 0xFFu);
+}
+
 __device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -279,12 +285,12 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
         float f[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            int q;
+            float q;
             if (BITS == 4)
-                q = __builtin_amdgcn_sbfe((int)c[u][0], 4 * j, 4);
+                q = (float)(int)__builtin_amdgcn_sbfe((int)c[u][0], 4 * j, 4);  // the builtin returns unsigned
             else
-                q = __builtin_amdgcn_sbfe((int)c[u][j >> 2], 8 * (j & 3), 8);
-            f[j] = __fmul_rn((float)q, s[u]);
+                q = byte_to_f32(c[u][j >> 2], j & 3);
+            f[j] = __fmul_rn(q, s[u]);
         }
         if (vi < n_vec)
             st<NTS>(y + vi, u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
@@ -380,8 +386,8 @@ __device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, fl
     for (int d = 0; d < 4; ++d)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int q = __builtin_amdgcn_sbfe((int)c[d], 8 * j, 8);
-            acc[4 * d + j] = __fmaf_rn((float)q, s, acc[4 * d + j]);
+            const float q = byte_to_f32(c[d], j);
+            acc[4 * d + j] = __fmaf_rn(q, s, acc[4 * d + j]);
         }
 }
 

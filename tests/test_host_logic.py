@@ -103,3 +103,18 @@ def test_stage_bitmaps_average_width(agoq):
     assert agoq.layer_bitmap(5) == [8, 4, 8, 4, 4] and agoq.layer_bitmap(6) == [8, 4, 8, 8, 4]
     with pytest.raises(agoq.AgoqError):
         agoq.layer_bitmap(3)
+
+
+def test_generated_isa_has_no_packed_fp32_math(tmp_path):
+    """The device code must contain no packed fp32 arithmetic (v_pk_{add,mul,fma}_f32)."""
+    import subprocess
+    from paper_2605_00539_amd import build
+    out = tmp_path / "agoq_kernels.s"
+    flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.check_call([build.HIPCC, *flags, "-S", "--cuda-device-only", "-o", str(out),
+                           build.SOURCES[0]], stderr=subprocess.DEVNULL)
+    text = out.read_text()
+    assert "act_quant_kernel" in text and "grad_reduce_kernel" in text
+    for mnemonic in ("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32"):
+        assert mnemonic not in text, mnemonic
+    assert "scratch_" not in text                       # no register spills to scratch memory
