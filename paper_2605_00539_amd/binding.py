@@ -86,6 +86,22 @@ def _stream(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
+class _on_device:
+    """Make the tensor's device current for the call; free when it already is."""
+
+    def __init__(self, device):
+        import torch
+        self.guard = None if device.index == torch.cuda.current_device() else torch.cuda.device(device)
+
+    def __enter__(self):
+        if self.guard is not None:
+            self.guard.__enter__()
+
+    def __exit__(self, *exc):
+        if self.guard is not None:
+            self.guard.__exit__(*exc)
+
+
 def _raw(ptr):
     return ctypes.c_void_p(ptr)
 
@@ -104,7 +120,7 @@ def act_quant(x, group, bits, codes=None, scales=None, stream=None):
         scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
     _dev(codes, torch.uint8, "codes")
     _dev(scales, torch.float32, "scales")
-    with torch.cuda.device(x.device):
+    with _on_device(x.device):
         _check(L.agoq_act_quant(_raw(x.data_ptr()), n, group, bits, _raw(codes.data_ptr()),
                                 _raw(scales.data_ptr()), _stream(stream)))
     return codes, scales
@@ -119,7 +135,7 @@ def act_dequant(codes, scales, numel, group, bits, out=None, stream=None):
     if out is None:
         out = torch.empty(numel, dtype=torch.bfloat16, device=codes.device)
     _dev(out, torch.bfloat16, "out")
-    with torch.cuda.device(codes.device):
+    with _on_device(codes.device):
         _check(L.agoq_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
                                   bits, _raw(out.data_ptr()), _stream(stream)))
     return out
@@ -137,7 +153,7 @@ def grad_quant(grad, group, codes=None, scales=None, stream=None):
         scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=grad.device)
     _dev(codes, torch.int8, "codes")
     _dev(scales, torch.float32, "scales")
-    with torch.cuda.device(grad.device):
+    with _on_device(grad.device):
         _check(L.agoq_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
                                  _raw(scales.data_ptr()), _stream(stream)))
     return codes, scales
@@ -161,7 +177,7 @@ def grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_s
                                  device=in_codes.device)
     _dev(out_codes, torch.int8, "out_codes")
     _dev(out_scales, torch.float32, "out_scales")
-    with torch.cuda.device(in_codes.device):
+    with _on_device(in_codes.device):
         _check(L.agoq_grad_reduce_requant(
             _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
             in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),

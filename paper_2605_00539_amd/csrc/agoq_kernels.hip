@@ -34,7 +34,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_AQ_BLOCK          // activation quantize
 #define AGOQ_AQ_BLOCK 128
 #endif
-#ifndef AGOQ_AQ_UNROLL
+#ifndef AGOQ_AQ_UNROLL         // 16-byte vectors per lane: 1, 2 or 4
 #define AGOQ_AQ_UNROLL 2
 #endif
 #ifndef AGOQ_AQ_NTL
@@ -46,17 +46,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_DQ_BLOCK          // activation dequantize
 #define AGOQ_DQ_BLOCK 512
 #endif
-#ifndef AGOQ_DQ_UNROLL4
-#define AGOQ_DQ_UNROLL4 4
-#endif
-#ifndef AGOQ_DQ_UNROLL8        // 8-bit codes, large tensors
-#define AGOQ_DQ_UNROLL8 2
-#endif
-#ifndef AGOQ_DQ_UNROLL8_SMALL  // 8-bit codes, tensors that fit one resident set of workgroups
-#define AGOQ_DQ_UNROLL8_SMALL 4
-#endif
-#ifndef AGOQ_DQ_SMALL_VECS     // "small" = at most this many 16-byte output vectors
-#define AGOQ_DQ_SMALL_VECS (4 << 20)
+#ifndef AGOQ_DQ_FORCE_UNROLL   // 0 = chosen per launch; else 1, 2 or 4
+#define AGOQ_DQ_FORCE_UNROLL 0
 #endif
 #ifndef AGOQ_DQ_NTC            // code loads
 #define AGOQ_DQ_NTC 1
@@ -466,6 +457,30 @@ inline unsigned blocks_for(int64_t items, int per_block)
     return (unsigned)((items + per_block - 1) / per_block);
 }
 
+// Compute units of the current device (cached per device ordinal).
+inline int compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
+// True when a one-shot grid of `block`-thread workgroups with `unroll` vectors per lane is
+// resident on the chip all at once (2048 threads per compute unit for these small-register
+// kernels).
+inline bool fits_one_round(int64_t n_vec, int block, int unroll)
+{
+    const int64_t capacity = (int64_t)compute_units() * (2048 / block);
+    return (n_vec + (int64_t)block * unroll - 1) / ((int64_t)block * unroll) <= capacity;
+}
 
 }  // namespace
 
@@ -479,18 +494,26 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    constexpr int U = AGOQ_AQ_UNROLL;
-    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+    const int unroll = AGOQ_AQ_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * unroll)), block(AGOQ_AQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
-    if (bits == 4 && group == 128)
-        act_quant_kernel<4, 128, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
-    else if (bits == 4)
-        act_quant_kernel<4, 64, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
-    else if (group == 128)
-        act_quant_kernel<8, 128, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
-    else
-        act_quant_kernel<8, 64, U><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+#define AGOQ_LAUNCH_AQ(B, G)                                                                     \
+    switch (unroll) {                                                                            \
+    case 4: act_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
+    case 2: act_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
+    default: act_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;  \
+    }
+    if (bits == 4 && group == 128) {
+        AGOQ_LAUNCH_AQ(4, 128)
+    } else if (bits == 4) {
+        AGOQ_LAUNCH_AQ(4, 64)
+    } else if (group == 128) {
+        AGOQ_LAUNCH_AQ(8, 128)
+    } else {
+        AGOQ_LAUNCH_AQ(8, 64)
+    }
+#undef AGOQ_LAUNCH_AQ
     return launch_status();
 }
 
@@ -502,26 +525,29 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    constexpr int U4 = AGOQ_DQ_UNROLL4, U8 = AGOQ_DQ_UNROLL8, U8S = AGOQ_DQ_UNROLL8_SMALL;
-    // 8-bit codes: a tensor small enough to be resident in one go runs best with few, fat
-    // workgroups; a large one with more, thinner ones
-    const bool small = n_vec <= AGOQ_DQ_SMALL_VECS;
-    const int unroll = bits == 4 ? U4 : (small ? U8S : U8);
+    // measured: 4-bit codes run best with four vectors per lane at every size; 8-bit codes
+    // with four when the whole grid is resident at once and with one otherwise
+    int unroll = AGOQ_DQ_FORCE_UNROLL;
+    if (unroll == 0) unroll = (bits == 4 || fits_one_round(n_vec, AGOQ_DQ_BLOCK, 4)) ? 4 : 1;
     const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
-    if (bits == 4 && group == 128)
-        act_dequant_kernel<4, 128, U4><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
-    else if (bits == 4)
-        act_dequant_kernel<4, 64, U4><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
-    else if (group == 128 && small)
-        act_dequant_kernel<8, 128, U8S><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
-    else if (group == 128)
-        act_dequant_kernel<8, 128, U8><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
-    else if (small)
-        act_dequant_kernel<8, 64, U8S><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
-    else
-        act_dequant_kernel<8, 64, U8><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+#define AGOQ_LAUNCH_DQ(B, G)                                                                      \
+    switch (unroll) {                                                                             \
+    case 4: act_dequant_kernel<B, G, 4><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
+    case 2: act_dequant_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
+    default: act_dequant_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break; \
+    }
+    if (bits == 4 && group == 128) {
+        AGOQ_LAUNCH_DQ(4, 128)
+    } else if (bits == 4) {
+        AGOQ_LAUNCH_DQ(4, 64)
+    } else if (group == 128) {
+        AGOQ_LAUNCH_DQ(8, 128)
+    } else {
+        AGOQ_LAUNCH_DQ(8, 64)
+    }
+#undef AGOQ_LAUNCH_DQ
     return launch_status();
 }
 

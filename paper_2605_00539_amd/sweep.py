@@ -1,0 +1,209 @@
+"""Per-kernel throughput on all five benchmark configurations (one GPU).
+
+    python -m paper_2605_00539_amd.sweep [--launches 200] [--reps 5]
+
+Protocol: for every (kernel, tensor shape, bits, group) case, `launches` back-to-back
+launches between two events on one stream, cycling through enough distinct input AND
+output buffers that the cycle's footprint on each side exceeds 1 GiB (the chip has a
+256 MB last-level cache in front of HBM; without rotation it absorbs re-reads and
+overwrites); median of `reps` such runs.  Reported: microseconds per launch, effective
+GB/s = algorithmic bytes / time, and the fraction of the 8 TB/s HBM peak.
+"""
+import argparse
+import json
+import sys
+
+import torch
+
+from . import binding as agoq
+
+PEAK = 8000.0
+GiB = 1 << 30
+
+
+def algo_act(n, bits, group):
+    return n * 2 + n * bits // 8 + 4 * (n // group)
+
+
+def algo_gq(n, group):
+    return 5 * n + 4 * (n // group)
+
+
+def algo_red(n, K, group):
+    return (K + 1) * (n + 4 * (n // group))
+
+
+def timed(fn, launches, reps):
+    for i in range(min(10, launches)):
+        fn(i)
+    torch.cuda.synchronize()
+    out = []
+    for _ in range(reps):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(launches):
+            fn(i)
+        e1.record()
+        e1.synchronize()
+        out.append(e0.elapsed_time(e1) * 1e3 / launches)
+    out.sort()
+    return out[len(out) // 2]
+
+
+def slots_for(bytes_each, floor=2, cap=128):
+    """Buffers needed for a 1.5 GiB rotation, at most `cap` (tiny tensors stay cache-resident
+    whatever the rotation; they measure launch latency, not bandwidth)."""
+    return min(cap, max(floor, -(-(GiB + GiB // 2) // bytes_each)))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--launches", type=int, default=200)
+    ap.add_argument("--reps", type=int, default=5)
+    args = ap.parse_args()
+    import workloads as wl
+
+    import ctypes
+    L = agoq.load_library()
+    P = ctypes.c_void_p
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    st = P(torch.cuda.current_stream().cuda_stream)
+    rows = []
+
+    def report(config, kernel, case, us, nbytes):
+        gbps = nbytes / us / 1e3
+        rows.append(dict(config=config, kernel=kernel, case=case, us=round(us, 2),
+                         algo_MB=round(nbytes / 1e6, 2), GBps=round(gbps, 1),
+                         frac=round(gbps / PEAK, 4)))
+        print("%-14s %-22s %-34s %10.2f us %10.1f MB %9.1f GB/s %6.1f%%" %
+              (config, kernel, case, us, nbytes / 1e6, gbps, 100 * gbps / PEAK), flush=True)
+
+    def act_case(config, label, rows_, cols, dist, frac, scale, seed, group_list, bits_list):
+        n = rows_ * cols
+        nx = slots_for(2 * n)
+        base = wl.act_device(rows_, cols, seed, dist, wl.n_outlier_channels(cols, frac), scale).reshape(-1)
+        xs = [base] + [base.roll(7919 * (i + 1)) for i in range(nx - 1)]
+        ys = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(nx)]
+        for group in group_list:
+            for bits in bits_list:
+                nc = slots_for(n * bits // 8)
+                cs = [torch.empty(n * bits // 8, dtype=torch.uint8, device=dev) for _ in range(nc)]
+                ss = [torch.empty(n // group, dtype=torch.float32, device=dev) for _ in range(nc)]
+                for i in range(nc):
+                    agoq.act_quant(xs[i % nx], group, bits, codes=cs[i], scales=ss[i])
+                torch.cuda.synchronize()
+                nb = algo_act(n, bits, group)
+                case = "%s [%d,%d] b%d g%d" % (label, rows_, cols, bits, group)
+                # argument tuples are marshalled once, so that the loop issues launches as
+                # fast as the host can (small tensors finish in under 10 us)
+                m = max(nx, nc)
+                qa = [(P(xs[i % nx].data_ptr()), n, group, bits, P(cs[i % nc].data_ptr()),
+                       P(ss[i % nc].data_ptr()), st) for i in range(m)]
+                da = [(P(cs[i % nc].data_ptr()), P(ss[i % nc].data_ptr()), n, group, bits,
+                       P(ys[i % nx].data_ptr()), st) for i in range(m)]
+                us = timed(lambda i: L.agoq_act_quant(*qa[i % len(qa)]), args.launches, args.reps)
+                report(config, "act_quant", case, us, nb)
+                us = timed(lambda i: L.agoq_act_dequant(*da[i % len(da)]), args.launches, args.reps)
+                report(config, "act_dequant", case, us, nb)
+                del cs, ss
+        del xs, ys, base
+
+    def grad_case(config, n, sigma, spike_frac, spike_scale, seed, K, group, share=True):
+        g = [wl.grad_device(n, seed + i, sigma, spike_frac, spike_scale) for i in range(2 if n > (1 << 26) else 8)]
+        nout = slots_for(n, floor=3)
+        ocs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nout)]
+        oss = [torch.empty(n // group, dtype=torch.float32, device=dev) for _ in range(nout)]
+        launches = max(20, min(args.launches, int(2e9 / n)))
+        us = timed(lambda i: agoq.grad_quant(g[i % len(g)], group, codes=ocs[i % nout],
+                                             scales=oss[i % nout]), launches, args.reps)
+        report(config, "grad_quant", "n=%d g%d" % (n, group), us, algo_gq(n, group))
+        nin = 1 if K * n > GiB else -(-GiB // (K * n)) + 1
+        ins = []
+        for s in range(nin):
+            codes = torch.empty((K, n), dtype=torch.int8, device=dev)
+            scales = torch.empty((K, n // group), dtype=torch.float32, device=dev)
+            for k in range(K):
+                gk = wl.grad_device(n, seed + 100 + 17 * s + k, sigma, spike_frac, spike_scale)
+                agoq.grad_quant(gk, group, codes=codes[k], scales=scales[k])
+                torch.cuda.synchronize()
+                del gk
+            ins.append((codes, scales))
+        us = timed(lambda i: agoq.grad_reduce_requant(ins[i % nin][0], ins[i % nin][1], n, group,
+                                                      out_codes=ocs[i % nout], out_scales=oss[i % nout]),
+                   launches, args.reps)
+        report(config, "grad_reduce_requant", "K=%d n=%d g%d" % (K, n, group), us, algo_red(n, K, group))
+        if share:
+            ns = n // K
+            codes, scales = ins[0]
+
+            # a shard is a strided window of the receive buffer: pass pointers and strides
+            # to the C ABI directly
+
+            def shard_raw(i):
+                k = i % K
+                off = k * ns
+                o = ocs[(i // K) % nout]
+                osc = oss[(i // K) % nout]
+                rc = L.agoq_grad_reduce_requant(P(codes.data_ptr() + off), n,
+                                                P(scales.data_ptr() + 4 * (off // group)), n // group,
+                                                K, ns, group, P(o.data_ptr() + off),
+                                                P(osc.data_ptr() + 4 * (off // group)), st)
+                assert rc == 0
+            us = timed(shard_raw, args.launches, args.reps)
+            report(config, "grad_reduce_requant", "K=%d share n=%d g%d" % (K, ns, group), us,
+                   algo_red(ns, K, group))
+        del ins, g, ocs, oss
+
+    C = wl.CONFIGS
+    # config 1: tiny (launch-latency bound; parity case, reported for completeness)
+    c = C["tiny"]
+    act_case("1-tiny", "act", c["act"]["rows"], c["act"]["cols"], "normal",
+             c["act"]["outlier_channels"] / c["act"]["cols"], c["act"]["outlier_scale"], c["seed"],
+             [c["group"]], [c["bits"]])
+    grad_case("1-tiny", c["grad"]["n"], c["grad"]["sigma"], 0.0, 1.0, 1, c["K"], c["group"], share=False)
+    # config 2: LLaMA-8B-shaped activations
+    c = C["llama8b_act"]
+    for name, sh in c["acts"].items():
+        act_case("2-8B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
+                 c["outlier_scale"], c["seed"], [c["group"]], [4, 8])
+    # config 3: LLaMA-8B-shaped gradients, K = 8
+    c = C["llama8b_grad"]
+    grad_case("3-8B-grad", c["n"], c["sigma"], c["spike_frac"], c["spike_scale"], c["seed"], c["K"], c["group"])
+    # config 4: 32B-shaped activations, both group sizes
+    c = C["llama32b_act"]
+    for name, sh in c["acts"].items():
+        act_case("4-32B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
+                 c["outlier_scale"], c["seed"], list(c["groups"]), [4, 8])
+    # config 5: stage sweep at seq 8192, K = 16
+    c = C["stage_sweep"]
+    per = {}
+    for name, cols in (("H", c["hidden"]), ("F", c["ffn"])):
+        before = len(rows)
+        act_case("5-stage", name, c["rows"], cols, c["dist"], c["outlier_frac"], c["outlier_scale"],
+                 c["seed"], [c["group"]], [4, 8])
+        for r in rows[before:]:
+            per[(name, r["kernel"], 4 if " b4 " in r["case"] else 8)] = r
+    gcfg = c["grad"]
+    grad_case("5-stage", gcfg["n"], gcfg["sigma"], gcfg["spike_frac"], gcfg["spike_scale"], c["seed"], c["K"], c["group"])
+    # whole-layer figures per stage bit map (sum of the five tensors' launches)
+    bf16_bytes = c["rows"] * (3 * c["hidden"] + 2 * c["ffn"]) * 2
+    for stage in (1, 2, 3, 4):
+        b = agoq.dbca_bits(4, stage)
+        bitmap = agoq.layer_bitmap(b)
+        stored = agoq.layer_stored_bytes(c["rows"], c["hidden"], c["ffn"], c["group"], bitmap, True)
+        for kernel in ("act_quant", "act_dequant"):
+            us = nb = 0.0
+            for slot, bits in enumerate(bitmap):
+                r = per[("F" if slot >= 3 else "H", kernel, bits)]
+                us += r["us"]
+                nb += r["algo_MB"] * 1e6
+            report("5-stage", kernel + "_layer", "stage %d (B=%d) map %s stored %d B (%.1f%% saved vs bf16)" %
+                   (stage, b, bitmap, stored, 100.0 * (1 - stored / bf16_bytes)), us, nb)
+    print(json.dumps(rows))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
