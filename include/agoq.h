@@ -110,6 +110,29 @@ int agoq_grad_reduce_requant(const int8_t *in_codes, int64_t chunk_stride_codes,
                              int64_t numel, int group, int8_t *out_codes, float *out_scales,
                              void *stream);
 
+/*
+ * Local gradient accumulation (paper: "System Overview" and "Precision-Preserved
+ * Gradient Quantization", first overflow issue: the stored 8-bit main gradient is
+ * dequantized, the new micro-batch gradient is added in high precision, and the sum is
+ * quantized back to 8 bits and written over the stored gradient).
+ *   for each element i of group g:  acc = fma(code[i], scale[g], g_new[i])   (fp32)
+ *   then the group of acc values is quantized to 8 bits as in agoq_grad_quant.
+ *   g_new         : in, numel values: fp32 (g_new_is_bf16 == 0) or bf16 (!= 0)
+ *   out_codes, out_scales : may be the same buffers as main_codes, main_scales
+ *                   (in-place update); any other overlap is undefined.
+ */
+int agoq_grad_accumulate(const int8_t *main_codes, const float *main_scales, const void *g_new,
+                         int g_new_is_bf16, int64_t numel, int group, int8_t *out_codes,
+                         float *out_scales, void *stream);
+
+/*
+ * Dequantize a stored 8-bit gradient to fp32 (paper: "Precision-Preserved Gradient
+ * Quantization": quantized gradients are dequantized before they are used in high
+ * precision).  out[i] = (float)code[i] * scale[g], one fp32 rounding.
+ */
+int agoq_grad_dequant(const int8_t *codes, const float *scales, int64_t numel, int group,
+                      float *out, void *stream);
+
 /* ---- host-only helpers: pure functions, no device access ---------------- */
 
 /* Bytes of packed codes for numel elements at `bits` per element; -1 if bits is unsupported. */

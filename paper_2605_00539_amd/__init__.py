@@ -6,12 +6,14 @@ HIP kernels of that library; there is no fallback: without the built library, or
 without a GPU, the calls raise.
 """
 from .binding import (AgoqError, act_dequant, act_quant, codes_bytes, dbca_bits,
-                      dbca_stored_microbatches, grad_quant, grad_reduce_requant,
+                      dbca_stored_microbatches, grad_accumulate, grad_dequant, grad_quant,
+                      grad_reduce_requant,
                       layer_bitmap, layer_stored_bytes, library_path, load_library,
                       num_groups, strerror, version)
 
 __all__ = [
     "AgoqError", "act_quant", "act_dequant", "grad_quant", "grad_reduce_requant",
+    "grad_accumulate", "grad_dequant",
     "codes_bytes", "num_groups", "dbca_bits", "dbca_stored_microbatches", "layer_bitmap",
     "layer_stored_bytes", "strerror", "version", "load_library", "library_path",
 ]

@@ -39,6 +39,8 @@ def load_library():
     L.agoq_act_dequant.argtypes = [_P, _P, _I64, _INT, _INT, _P, _P]
     L.agoq_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
     L.agoq_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
+    L.agoq_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
+    L.agoq_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
     L.agoq_codes_bytes.argtypes = [_I64, _INT]
     L.agoq_codes_bytes.restype = _I64
     L.agoq_num_groups.argtypes = [_I64, _INT]
@@ -183,6 +185,50 @@ def grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_s
             in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),
             _raw(out_scales.data_ptr()), _stream(stream)))
     return out_codes, out_scales
+
+
+def grad_accumulate(main_codes, main_scales, g_new, group, out_codes=None, out_scales=None,
+                    stream=None):
+    """main_codes int8 [numel], main_scales float32 [numel/group], g_new float32 or bfloat16
+    [numel].  With out_codes/out_scales left None the stored gradient is updated in place."""
+    import torch
+    L = load_library()
+    _dev(main_codes, torch.int8, "main_codes")
+    _dev(main_scales, torch.float32, "main_scales")
+    if not isinstance(g_new, torch.Tensor) or g_new.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("g_new must be a float32 or bfloat16 tensor")
+    _dev(g_new, g_new.dtype, "g_new")
+    n = main_codes.numel()
+    if g_new.numel() != n:
+        raise ValueError("g_new must have as many elements as main_codes")
+    if out_codes is None:
+        out_codes = main_codes
+    if out_scales is None:
+        out_scales = main_scales
+    _dev(out_codes, torch.int8, "out_codes")
+    _dev(out_scales, torch.float32, "out_scales")
+    with _on_device(main_codes.device):
+        _check(L.agoq_grad_accumulate(
+            _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
+            1 if g_new.dtype == torch.bfloat16 else 0, n, group, _raw(out_codes.data_ptr()),
+            _raw(out_scales.data_ptr()), _stream(stream)))
+    return out_codes, out_scales
+
+
+def grad_dequant(codes, scales, group, out=None, stream=None):
+    """int8 codes + float32 scales -> float32 tensor of the same length."""
+    import torch
+    L = load_library()
+    _dev(codes, torch.int8, "codes")
+    _dev(scales, torch.float32, "scales")
+    n = codes.numel()
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)
+    _dev(out, torch.float32, "out")
+    with _on_device(codes.device):
+        _check(L.agoq_grad_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), n, group,
+                                   _raw(out.data_ptr()), _stream(stream)))
+    return out
 
 
 # ---- host helpers ---------------------------------------------------------------

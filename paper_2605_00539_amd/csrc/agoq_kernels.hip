@@ -83,6 +83,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define AGOQ_RD_NTS 1
 #endif
 
+#ifndef AGOQ_GD_BLOCK          // gradient dequantize
+#define AGOQ_GD_BLOCK 512
+#endif
+#ifndef AGOQ_GD_UNROLL
+#define AGOQ_GD_UNROLL 1
+#endif
+#ifndef AGOQ_GD_NTS
+#define AGOQ_GD_NTS 1
+#endif
+
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
 constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
 
@@ -435,6 +445,158 @@ __global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t
 }
 
 // ---------------------------------------------------------------------------
+// Local gradient accumulation: stored int8 gradient (+ scales) plus a new
+// micro-batch gradient -> int8 (+ scales).  acc = fma(code, scale, g_new) in fp32,
+// then the group is quantized to 8 bits.  May run in place: a group is read in
+// full by the lanes that own it before any of them stores, and no other lane
+// touches it, so the output may alias the stored gradient.
+//   fp32 addend: lane layout of grad_quant_kernel (one DPP row per group).
+//   bf16 addend: lane layout of act_quant_kernel (8 elements per lane).
+// ---------------------------------------------------------------------------
+template <int GROUP, int UNROLL>
+__global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
+    const u32* main_codes, const float* main_scales, const f32x4* __restrict__ g_new,
+    int64_t n_groups, u32* out_codes, float* out_scales)
+{
+    constexpr int VPL = GROUP / 64;
+    constexpr int VPG = GROUP / 4;
+    constexpr int kBlock = AGOQ_GQ_BLOCK;
+    const int lane16 = threadIdx.x & 15;
+    const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    f32x4 v[UNROLL][VPL];
+    u32 c[UNROLL][VPL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+        s[u] = 0.0f;
+        if (grp < n_groups) s[u] = ld<true>(main_scales + grp);
+#pragma unroll
+        for (int p = 0; p < VPL; ++p) {
+            v[u][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            c[u][p] = 0;
+            if (grp < n_groups) {
+                v[u][p] = ld<true>(g_new + grp * VPG + p * 16 + lane16);
+                c[u][p] = ld<true>(main_codes + grp * VPG + p * 16 + lane16);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+        float acc[VPL][4];
+        u32 m = 0;
+#pragma unroll
+        for (int p = 0; p < VPL; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[p][j] = __fmaf_rn(byte_to_f32(c[u][p], j), s[u], v[u][p][j]);
+                m = umax(m, as_u32(acc[p][j]) & 0x7FFFFFFFu);
+            }
+        m = group_max_bits<16>(m);
+        float scale, inv;
+        scale_and_inv<127>(m, scale, inv);
+        if (grp < n_groups) {
+#pragma unroll
+            for (int p = 0; p < VPL; ++p) {
+                u32 w = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w = push_byte(w, code_bits(acc[p][j], inv));
+                st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
+            }
+            if (lane16 == 0) st<true>(out_scales + grp, scale);
+        }
+    }
+}
+
+template <int GROUP, int UNROLL>
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
+    const u32x2* main_codes, const float* main_scales, const u32x4* __restrict__ g_new,
+    int64_t n_vec, u32x2* out_codes, float* out_scales)
+{
+    constexpr int LANES = GROUP / 8;
+    constexpr int kBlock = AGOQ_AQ_BLOCK;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    u32x4 v[UNROLL];
+    u32x2 c[UNROLL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        v[u] = u32x4{0, 0, 0, 0};
+        c[u] = u32x2{0, 0};
+        s[u] = 0.0f;
+        if (vi < n_vec) {
+            v[u] = ld<true>(g_new + vi);
+            c[u] = ld<true>(main_codes + vi);
+            s[u] = ld<true>(main_scales + vi / LANES);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        float acc[8];
+        u32 m = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const u32 w = v[u][j >> 1];
+            const float g = as_f32((j & 1) ? (w & 0xFFFF0000u) : (w << 16));
+            acc[j] = __fmaf_rn(byte_to_f32(c[u][j >> 2], j & 3), s[u], g);
+            m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
+        }
+        m = group_max_bits<LANES>(m);
+        float scale, inv;
+        scale_and_inv<127>(m, scale, inv);
+        if (vi < n_vec) {
+            u32 p0 = 0, p1 = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(acc[j], inv));
+#pragma unroll
+            for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(acc[j], inv));
+            st<true>(out_codes + vi, u32x2{p0, p1});
+            if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Gradient dequantize: int8 codes + scales -> fp32 (what an optimizer step reads).
+// One lane: 4 codes (one dword) -> one 16-byte store.
+// ---------------------------------------------------------------------------
+template <int GROUP, int UNROLL>
+__global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* __restrict__ codes,
+                                                                     const float* __restrict__ scales,
+                                                                     int64_t n_vec,
+                                                                     f32x4* __restrict__ out)
+{
+    constexpr int LANES = GROUP / 4;      // lanes per group
+    constexpr int kBlock = AGOQ_GD_BLOCK;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    u32 c[UNROLL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        c[u] = 0;
+        s[u] = 0.0f;
+        if (vi < n_vec) {
+            c[u] = ld<true>(codes + vi);
+            s[u] = ld<false>(scales + vi / LANES);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        f32x4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(byte_to_f32(c[u], j), s[u]);
+        if (vi < n_vec) st<AGOQ_GD_NTS>(out + vi, o);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 
@@ -605,6 +767,63 @@ int agoq_grad_reduce_requant(const int8_t* in_codes, int64_t chunk_stride_codes,
         }
     }
 #undef AGOQ_LAUNCH_REDUCE
+    return launch_status();
+}
+
+int agoq_grad_accumulate(const int8_t* main_codes, const float* main_scales, const void* g_new,
+                         int g_new_is_bf16, int64_t numel, int group, int8_t* out_codes,
+                         float* out_scales, void* stream)
+{
+    if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(main_codes) || misaligned(main_scales) || misaligned(g_new) ||
+        misaligned(out_codes) || misaligned(out_scales))
+        return AGOQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (g_new_is_bf16) {
+        const int64_t n_vec = numel / 8;
+        constexpr int U = AGOQ_AQ_UNROLL;
+        const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+        if (group == 128)
+            grad_accumulate_bf16_kernel<128, U><<<grid, block, 0, st>>>(
+                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                (u32x2*)out_codes, out_scales);
+        else
+            grad_accumulate_bf16_kernel<64, U><<<grid, block, 0, st>>>(
+                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                (u32x2*)out_codes, out_scales);
+    } else {
+        const int64_t n_groups = numel / group;
+        constexpr int U = AGOQ_GQ_UNROLL;
+        const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
+        if (group == 128)
+            grad_accumulate_f32_kernel<128, U><<<grid, block, 0, st>>>(
+                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
+                (u32*)out_codes, out_scales);
+        else
+            grad_accumulate_f32_kernel<64, U><<<grid, block, 0, st>>>(
+                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
+                (u32*)out_codes, out_scales);
+    }
+    return launch_status();
+}
+
+int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, int group,
+                      float* out, void* stream)
+{
+    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 4;
+    constexpr int U = AGOQ_GD_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_dequant_kernel<128, U><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                            (f32x4*)out);
+    else
+        grad_dequant_kernel<64, U><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                           (f32x4*)out);
     return launch_status();
 }
 

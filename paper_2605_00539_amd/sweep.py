@@ -119,6 +119,31 @@ def main():
         us = timed(lambda i: agoq.grad_quant(g[i % len(g)], group, codes=ocs[i % nout],
                                              scales=oss[i % nout]), launches, args.reps)
         report(config, "grad_quant", "n=%d g%d" % (n, group), us, algo_gq(n, group))
+        if n > (1 << 26):
+            # local accumulation (stored int8 gradient + new micro-batch gradient -> int8) and
+            # int8 -> fp32 dequantize, on the same tensor size
+            mcs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nout)]
+            mss = [torch.empty(n // group, dtype=torch.float32, device=dev) for _ in range(nout)]
+            for i in range(nout):
+                agoq.grad_quant(g[i % len(g)], group, codes=mcs[i], scales=mss[i])
+            torch.cuda.synchronize()
+            us = timed(lambda i: agoq.grad_accumulate(mcs[i % nout], mss[i % nout], g[i % len(g)], group,
+                                                      out_codes=ocs[i % nout], out_scales=oss[i % nout]),
+                       launches, args.reps)
+            report(config, "grad_accumulate", "fp32 addend n=%d g%d" % (n, group), us,
+                   n * 6 + 8 * (n // group))
+            gb = [x.to(torch.bfloat16) for x in g]
+            us = timed(lambda i: agoq.grad_accumulate(mcs[i % nout], mss[i % nout], gb[i % len(gb)], group,
+                                                      out_codes=ocs[i % nout], out_scales=oss[i % nout]),
+                       launches, args.reps)
+            report(config, "grad_accumulate", "bf16 addend n=%d g%d" % (n, group), us,
+                   n * 4 + 8 * (n // group))
+            del gb
+            fo = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]
+            us = timed(lambda i: agoq.grad_dequant(mcs[i % nout], mss[i % nout], group, out=fo[i % 2]),
+                       launches, args.reps)
+            report(config, "grad_dequant", "n=%d g%d" % (n, group), us, n * 5 + 4 * (n // group))
+            del mcs, mss, fo
         nin = 1 if K * n > GiB else -(-GiB // (K * n)) + 1
         ins = []
         for s in range(nin):

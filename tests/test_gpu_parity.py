@@ -259,3 +259,96 @@ def test_error_codes(agoq):
         agoq.act_quant(x.float(), 128, 4)
     with pytest.raises(TypeError):
         agoq.act_quant(x.cpu(), 128, 4)
+
+
+# ---- local accumulation into the stored 8-bit gradient, and int8 -> fp32 dequantize ----
+
+@pytest.mark.parametrize("as_bf16", [False, True])
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("n_groups", [1, 17, 4 * 32 + 3, 30011])
+def test_gradient_accumulate(agoq, ref, group, n_groups, as_bf16):
+    rng = np.random.default_rng(4000 + n_groups)
+    n = n_groups * group
+    base = wl.grad_host(n, 4100 + n_groups, 1e-4, 0.001, 100.0)
+    main_c, main_s = ref.grad_quant(base, group)
+    g32 = wl.grad_host(n, 4200 + n_groups, 1e-4, 0.001, 100.0)
+    if n_groups > 8:
+        g32[group * 2: group * 3] = 0.0
+        main_c[group * 2: group * 3] = 0                      # 0 + 0: a dead group
+        g32[group * 5: group * 6] = -ref.grad_dequant(main_c, main_s, group)[group * 5: group * 6]
+    if as_bf16:
+        t = torch.from_numpy(g32).to(torch.bfloat16)
+        g_host = t.view(torch.int16).numpy().view(np.uint16)
+        g_dev = t.cuda()
+    else:
+        g_host = g32
+        g_dev = torch.from_numpy(g32).cuda()
+    want = ref.grad_accumulate(main_c, main_s, g_host, group)
+    d_c, d_s = torch.from_numpy(main_c).cuda(), torch.from_numpy(main_s).cuda()
+    out_c = torch.empty_like(d_c)
+    out_s = torch.empty_like(d_s)
+    agoq.grad_accumulate(d_c, d_s, g_dev, group, out_codes=out_c, out_scales=out_s)
+    torch.cuda.synchronize()
+    assert same_f32(out_s.cpu().numpy(), want[1])
+    assert np.array_equal(out_c.cpu().numpy(), want[0])
+    assert np.array_equal(d_c.cpu().numpy(), main_c)          # inputs untouched
+    # in place: the stored gradient is overwritten with the same result
+    agoq.grad_accumulate(d_c, d_s, g_dev, group)
+    torch.cuda.synchronize()
+    assert same_f32(d_s.cpu().numpy(), want[1])
+    assert np.array_equal(d_c.cpu().numpy(), want[0])
+
+
+def test_gradient_accumulate_over_micro_batches_tracks_the_sum(agoq, ref):
+    # eight micro-batches accumulated in place; oracle and GPU stay bit-identical, and the
+    # stored gradient stays within the quantization steps of the true fp32 sum
+    group, n = 128, 128 * 2048
+    d_c = torch.zeros(n, dtype=torch.int8, device="cuda")
+    d_s = torch.zeros(n // group, dtype=torch.float32, device="cuda")
+    h_c, h_s = np.zeros(n, np.int8), np.zeros(n // group, np.float32)
+    total = np.zeros(n, np.float64)
+    slack = np.zeros(n // group, np.float64)
+    for mb in range(8):
+        g = wl.grad_host(n, 4300 + mb, 1e-4, 0.001, 100.0)
+        total += g
+        agoq.grad_accumulate(d_c, d_s, torch.from_numpy(g).cuda(), group)
+        h_c, h_s = ref.grad_accumulate(h_c, h_s, g, group)
+        slack += 0.5 * h_s.astype(np.float64) * 1.001
+    torch.cuda.synchronize()
+    assert np.array_equal(d_c.cpu().numpy(), h_c) and same_f32(d_s.cpu().numpy(), h_s)
+    deq = agoq.grad_dequant(d_c, d_s, group)
+    torch.cuda.synchronize()
+    assert np.array_equal(deq.cpu().numpy(), ref.grad_dequant(h_c, h_s, group))
+    assert np.all(np.abs(deq.cpu().numpy().astype(np.float64) - total) <= np.repeat(slack, group) + 1e-12)
+
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("n_groups", [1, 5, 8 * 512 * 4 // 32 + 3, 70001])
+def test_gradient_dequant(agoq, ref, group, n_groups):
+    rng = np.random.default_rng(4400 + n_groups)
+    n = n_groups * group
+    codes = rng.integers(-128, 128, size=n).astype(np.int8)
+    scales = (rng.random(n_groups).astype(np.float32) + np.float32(0.5)) * \
+        (2.0 ** rng.integers(-140, 100, n_groups)).astype(np.float32)
+    scales[::53] = 0.0
+    want = ref.grad_dequant(codes, scales.astype(np.float32), group)
+    got = agoq.grad_dequant(torch.from_numpy(codes).cuda(), torch.from_numpy(scales.astype(np.float32)).cuda(), group)
+    torch.cuda.synchronize()
+    assert same_f32(got.cpu().numpy(), want)
+
+
+def test_accumulate_and_dequant_error_codes(agoq):
+    import ctypes
+    L = agoq.load_library()
+    P = ctypes.c_void_p
+    c = torch.zeros(1024, dtype=torch.int8, device="cuda")
+    s = torch.zeros(8, dtype=torch.float32, device="cuda")
+    g = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    pc, ps, pg = P(c.data_ptr()), P(s.data_ptr()), P(g.data_ptr())
+    assert L.agoq_grad_accumulate(pc, ps, None, 0, 1024, 128, pc, ps, None) == 1
+    assert L.agoq_grad_accumulate(pc, ps, pg, 0, 1024, 96, pc, ps, None) == 3
+    assert L.agoq_grad_accumulate(pc, ps, pg, 0, 1000, 128, pc, ps, None) == 4
+    assert L.agoq_grad_accumulate(pc, ps, P(g.data_ptr() + 4), 0, 512, 128, pc, ps, None) == 5
+    assert L.agoq_grad_dequant(pc, None, 1024, 128, pg, None) == 1
+    assert L.agoq_grad_dequant(pc, ps, 1024, 32, pg, None) == 3
+    assert L.agoq_grad_dequant(pc, ps, -128, 128, pg, None) == 4
