@@ -25,10 +25,14 @@
  *   - amax < 2^-100 (includes 0): scale = 0 and every code = 0;
  *   - scale = amax / qmax,  inv = qmax / amax   (two separate divisions);
  *   - code  = clamp(rint(x_j * inv), -qmax, +qmax)   (rint = ties to even);
- *   - 8-bit codes are int8; narrower codes are two's-complement fields of
- *     b bits packed little-endian into the byte stream, element j of the
- *     buffer occupying bits [j*b, j*b+b) of that stream (for b = 4: even
- *     element in the low nibble, odd element in the high nibble);
+ *   - codes are two's-complement fields of b bits.  b = 8: int8, one byte per
+ *     element.  b = 4: byte m holds element 2m in bits 0-3 and element 2m+1
+ *     in bits 4-7.  b = 5 and b = 6: two planes over the whole tensor; the
+ *     low four bits of every code form a 4-bit plane laid out exactly like
+ *     b = 4 (numel/2 bytes), and the remaining high bits follow at byte
+ *     offset numel/2: for b = 5, bit j of byte m is the high bit of element
+ *     8m+j; for b = 6, bits 2j..2j+1 of byte m are the two high bits of
+ *     element 4m+j;
  *   - dequantize: v = (float)code * scale; activations return bf16(v) with
  *     round-to-nearest-even;
  *   - reduce: acc = 0; for k = 0..K-1 in that order: acc = fmaf(code_k,
@@ -95,7 +99,7 @@ static int qmax_of_bits(int bits) { return (1 << (bits - 1)) - 1; }
 
 static int bits_supported(int bits)
 {
-    return bits == 4 || bits == 8;
+    return bits == 4 || bits == 5 || bits == 6 || bits == 8;
 }
 
 /* Quantize G fp32 values to integer codes in [-qmax, qmax]; returns scale. */
@@ -127,29 +131,54 @@ static float quantize_group(const float *x, int G, int qmax, int *q)
     return scale;
 }
 
-/* ---- bit-stream packing: element j lives in bits [j*b, j*b + b) --------- */
+/* ---- code layout: element i of a tensor of numel elements --------------- */
 
-static void put_code(uint8_t *stream, int64_t j, int bits, int q)
+static void put_code(uint8_t *codes, int64_t numel, int64_t i, int bits, int q)
 {
-    uint32_t field = (uint32_t)q & ((1u << bits) - 1u); /* two's complement */
-    int64_t bit0 = j * bits;
-    for (int t = 0; t < bits; ++t) {
-        int64_t p = bit0 + t;
-        uint8_t m = (uint8_t)(1u << (p & 7));
-        if ((field >> t) & 1u)
-            stream[p >> 3] |= m;
+    const uint32_t field = (uint32_t)q & ((1u << bits) - 1u); /* two's complement */
+    if (bits == 8) {
+        codes[i] = (uint8_t)field;
+        return;
+    }
+    /* low nibble plane (all of a 4-bit code) */
+    {
+        uint8_t *byte = codes + i / 2;
+        const uint32_t lo = field & 0xFu;
+        if (i % 2 == 0)
+            *byte = (uint8_t)((*byte & 0xF0u) | lo);
         else
-            stream[p >> 3] &= (uint8_t)~m;
+            *byte = (uint8_t)((*byte & 0x0Fu) | (lo << 4));
+    }
+    if (bits == 4)
+        return;
+    /* high plane, after the numel/2 bytes of the nibble plane */
+    {
+        uint8_t *high = codes + numel / 2;
+        const uint32_t hi = field >> 4; /* 1 bit (b = 5) or 2 bits (b = 6) */
+        if (bits == 5) {
+            uint8_t *byte = high + i / 8;
+            const int sh = (int)(i % 8);
+            *byte = (uint8_t)((*byte & ~(1u << sh)) | (hi << sh));
+        } else {
+            uint8_t *byte = high + i / 4;
+            const int sh = 2 * (int)(i % 4);
+            *byte = (uint8_t)((*byte & ~(3u << sh)) | (hi << sh));
+        }
     }
 }
 
-static int get_code(const uint8_t *stream, int64_t j, int bits)
+static int get_code(const uint8_t *codes, int64_t numel, int64_t i, int bits)
 {
-    uint32_t field = 0;
-    int64_t bit0 = j * bits;
-    for (int t = 0; t < bits; ++t) {
-        int64_t p = bit0 + t;
-        field |= (uint32_t)((stream[p >> 3] >> (p & 7)) & 1u) << t;
+    uint32_t field;
+    if (bits == 8) {
+        field = codes[i];
+    } else {
+        const uint8_t byte = codes[i / 2];
+        field = (i % 2 == 0) ? (byte & 0xFu) : (uint32_t)(byte >> 4);
+        if (bits == 5)
+            field |= (uint32_t)((codes[numel / 2 + i / 8] >> (i % 8)) & 1u) << 4;
+        else if (bits == 6)
+            field |= (uint32_t)((codes[numel / 2 + i / 4] >> (2 * (i % 4))) & 3u) << 4;
     }
     if (field & (1u << (bits - 1))) /* sign bit of the field */
         return (int)field - (1 << bits);
@@ -166,7 +195,7 @@ static int check_shape(int64_t numel, int group, int bits)
         return REF_ERR_GROUP;
     if (numel <= 0 || numel % group != 0)
         return REF_ERR_SHAPE;
-    if (((int64_t)group * bits) % 8 != 0) /* a group is a whole number of bytes */
+    if (group % 8 != 0 && bits != 8) /* every plane of a group is a whole number of bytes */
         return REF_ERR_GROUP;
     return REF_OK;
 }
@@ -184,7 +213,6 @@ int agoq_ref_act_quant(const uint16_t *x, int64_t numel, int group, int bits,
         return rc;
     const int qmax = qmax_of_bits(bits);
     const int64_t n_groups = numel / group;
-    const int64_t group_bytes = (int64_t)group * bits / 8;
 #pragma omp parallel for schedule(static)
     for (int64_t g = 0; g < n_groups; ++g) {
         float xf[4096];
@@ -193,9 +221,9 @@ int agoq_ref_act_quant(const uint16_t *x, int64_t numel, int group, int bits,
         for (int j = 0; j < group; ++j)
             xf[j] = bf16_bits_to_f32(xg[j]);
         scales[g] = quantize_group(xf, group, qmax, q);
-        uint8_t *cg = codes + g * group_bytes; /* groups start on byte boundaries */
+        /* a group's bytes in every plane belong to that group alone */
         for (int j = 0; j < group; ++j)
-            put_code(cg, j, bits, q[j]);
+            put_code(codes, numel, g * group + j, bits, q[j]);
     }
     return REF_OK;
 }
@@ -209,13 +237,11 @@ int agoq_ref_act_dequant(const uint8_t *codes, const float *scales, int64_t nume
     if (rc)
         return rc;
     const int64_t n_groups = numel / group;
-    const int64_t group_bytes = (int64_t)group * bits / 8;
 #pragma omp parallel for schedule(static)
     for (int64_t g = 0; g < n_groups; ++g) {
-        const uint8_t *cg = codes + g * group_bytes;
         const float s = scales[g];
         for (int j = 0; j < group; ++j) {
-            float v = (float)get_code(cg, j, bits) * s;
+            float v = (float)get_code(codes, numel, g * group + j, bits) * s;
             y[g * group + j] = f32_to_bf16_bits(v);
         }
     }

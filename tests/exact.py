@@ -99,3 +99,46 @@ def unpack_nibbles(codes: np.ndarray) -> np.ndarray:
     out[0::2] = lo
     out[1::2] = hi
     return np.where(out >= 8, out - 16, out).astype(np.int32)
+
+
+def unpack_codes(codes: np.ndarray, numel: int, bits: int) -> np.ndarray:
+    """Code bytes -> signed integers, from the stated layout: int8 for 8 bits; nibbles for 4;
+    for 5 and 6 bits a nibble plane (numel/2 bytes) followed by the plane of high bits."""
+    c = np.asarray(codes, np.uint8)
+    if bits == 8:
+        return c.view(np.int8).astype(np.int32)
+    lo = np.empty(numel, np.int32)
+    lo[0::2] = c[: numel // 2] & 0xF
+    lo[1::2] = c[: numel // 2] >> 4
+    if bits == 4:
+        field = lo
+    elif bits == 5:
+        hb = c[numel // 2: numel // 2 + numel // 8]
+        hi = ((hb[:, None] >> np.arange(8)) & 1).reshape(-1).astype(np.int32)
+        field = lo | (hi << 4)
+    elif bits == 6:
+        hb = c[numel // 2: numel // 2 + numel // 4]
+        hi = ((hb[:, None] >> (2 * np.arange(4))) & 3).reshape(-1).astype(np.int32)
+        field = lo | (hi << 4)
+    else:
+        raise ValueError(bits)
+    return np.where(field >= (1 << (bits - 1)), field - (1 << bits), field).astype(np.int32)
+
+
+def pack_codes(q: np.ndarray, bits: int) -> np.ndarray:
+    """Signed integers -> code bytes (inverse of unpack_codes), for building dequantize inputs."""
+    q = np.asarray(q, np.int64).reshape(-1)
+    n = q.size
+    u = (q & ((1 << bits) - 1)).astype(np.uint8)
+    if bits == 8:
+        return u
+    lo = u & 0xF
+    nib = (lo[0::2] | (lo[1::2] << 4)).astype(np.uint8)
+    if bits == 4:
+        return nib
+    hi = (u >> 4).astype(np.uint8)
+    if bits == 5:
+        high = (hi.reshape(-1, 8) << np.arange(8, dtype=np.uint8)).sum(axis=1).astype(np.uint8)
+    else:
+        high = (hi.reshape(-1, 4) << (2 * np.arange(4, dtype=np.uint8))).sum(axis=1).astype(np.uint8)
+    return np.concatenate([nib, high])

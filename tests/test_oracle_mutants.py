@@ -24,7 +24,15 @@ MUTANTS = [
     ("absmax_without_abs", "float a = fabsf(x[j]);", "float a = x[j];"),
     ("no_tiny_group_rule", "static const float REF_AMAX_MIN = 0x1p-100f;",
      "static const float REF_AMAX_MIN = 0.0f;"),
-    ("nibbles_swapped", "put_code(cg, j, bits, q[j]);", "put_code(cg, j ^ 1, bits, q[j]);"),
+    ("nibbles_swapped", "put_code(codes, numel, g * group + j, bits, q[j]);",
+     "put_code(codes, numel, (g * group + j) ^ 1, bits, q[j]);"),
+    ("high_plane_at_wrong_offset", "uint8_t *high = codes + numel / 2;", "uint8_t *high = codes + numel / 4;"),
+    ("five_bit_high_bits_reversed", "const int sh = (int)(i % 8);", "const int sh = 7 - (int)(i % 8);"),
+    ("six_bit_fields_reversed", "const int sh = 2 * (int)(i % 4);", "const int sh = 6 - 2 * (int)(i % 4);"),
+    ("decode_five_bit_ignores_high_plane", "field |= (uint32_t)((codes[numel / 2 + i / 8] >> (i % 8)) & 1u) << 4;",
+     "field |= 0u;"),
+    ("decode_six_bit_one_high_bit", "field |= (uint32_t)((codes[numel / 2 + i / 4] >> (2 * (i % 4))) & 3u) << 4;",
+     "field |= (uint32_t)((codes[numel / 2 + i / 4] >> (2 * (i % 4))) & 1u) << 4;"),
     ("decode_without_sign_extension", "return (int)field - (1 << bits);", "return (int)field;"),
     ("bf16_by_truncation", "u += 0x7FFFu + lsb;", "u += 0u * lsb;"),
     ("bf16_ties_up", "u += 0x7FFFu + lsb;", "u += 0x8000u + 0u * lsb;"),

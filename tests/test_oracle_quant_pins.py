@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from exact import (all_finite_bf16_bits, bf16_bits_to_f64, bf16_rne_from_fraction,
-                   f32_fraction, fraction_to_f32, rint_half_even_f64, unpack_nibbles)
+                   f32_fraction, fraction_to_f32, pack_codes, rint_half_even_f64, unpack_codes)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -24,10 +24,12 @@ def bf16_bits(x):
     return t.view(torch.int16).numpy().view(np.uint16)
 
 
+ALL_BITS = [4, 5, 6, 8]
+
+
 def codes_to_int(codes, bits):
-    if bits == 8:
-        return np.asarray(codes, np.uint8).view(np.int8).astype(np.int32)
-    return unpack_nibbles(codes)
+    codes = np.asarray(codes, np.uint8)
+    return unpack_codes(codes, codes.size * 8 // bits, bits)
 
 
 # ---------------------------------------------------------------------------
@@ -48,7 +50,7 @@ PLANTED_AMAX_BITS = [
 ]
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 @pytest.mark.parametrize("amax_bits", PLANTED_AMAX_BITS)
 def test_codes_and_scale_exact_all_bf16_patterns(ref, bits, amax_bits):
     G = 128
@@ -111,13 +113,13 @@ def load_tie_fixture():
     return rows
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 def test_ties_round_to_even(ref, bits):
     qmax = (1 << (bits - 1)) - 1
     # keep the rows that fit the grid and that bf16 (8 significant bits) can hold
     rows = [(t, q) for t, q in load_tie_fixture()
             if abs(t) <= qmax and bf16_bits_to_f64(bf16_bits(np.float32([t])))[0] == t]
-    assert len(rows) >= 15
+    assert len(rows) >= 15 or bits == 4
     for e in (0, -3, 5):  # scale = 2^e, so x = t * 2^e and t = x * inv exactly
         G = 128
         x = np.zeros(G, np.float32)
@@ -177,6 +179,31 @@ def test_nibble_packing_fixture(ref):
     assert np.array_equal(c8.view(np.int8).astype(np.float32), x8)
 
 
+def load_plane_fixture(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                key, rest = line.split(":")
+                out[key.strip()] = rest.split()
+    return out
+
+
+@pytest.mark.parametrize("bits,name", [(5, "plane_packing_5bit.txt"), (6, "plane_packing_6bit.txt")])
+def test_plane_packing_fixtures(ref, bits, name):
+    # two groups of 8 on a grid of step 1 (amax = qmax, so scale = 1 and code = value);
+    # expected bytes written by hand: nibble plane first, plane of high bits after it
+    fx = load_plane_fixture(name)
+    vals = np.array([float(v) for v in fx["values"]], np.float32)
+    want = [int(b, 16) for b in fx["nibble_plane"]] + [int(b, 16) for b in fx["high_plane"]]
+    codes, scales = ref.act_quant(bf16_bits(vals), 8, bits)
+    assert np.all(scales == 1.0)
+    assert list(codes) == want
+    y = ref.act_dequant(np.array(want, np.uint8), scales, vals.size, 8, bits)
+    assert np.array_equal(bf16_bits_to_f64(y), vals.astype(np.float64))
+
+
 def test_dequant_unpacks_what_quant_packed(ref):
     # decode side of the layout, including the code -8 / -128 that quant never emits
     codes = np.array([0x8F, 0x10, 0x7E, 0x98], np.uint8)   # elems: -1,-8, 0,1, -2,7, -8,-7
@@ -193,7 +220,7 @@ def test_dequant_unpacks_what_quant_packed(ref):
 # closed forms and invariants
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 @pytest.mark.parametrize("G", [64, 128])
 def test_values_on_the_grid_are_reconstructed_exactly(ref, bits, G):
     qmax = (1 << (bits - 1)) - 1
@@ -212,16 +239,16 @@ def test_values_on_the_grid_are_reconstructed_exactly(ref, bits, G):
     assert np.array_equal(y, xb.reshape(-1))
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 def test_zero_groups(ref, bits):
     G = 128
     x = np.zeros((3, G), np.uint16)
     x[1] = bf16_bits(np.random.default_rng(0).standard_normal(G).astype(np.float32))
     x[2, 5] = 0x8000                      # a lone negative zero
     codes, scales = ref.act_quant(x, G, bits)
-    gb = G * bits // 8
     assert scales[0] == 0.0 and scales[2] == 0.0 and scales[1] > 0.0
-    assert not codes[:gb].any() and not codes[2 * gb:].any()
+    q = codes_to_int(codes, bits).reshape(3, G)
+    assert not q[0].any() and not q[2].any() and q[1].any()
     y = ref.act_dequant(codes, scales, 3 * G, G, bits).reshape(3, G)
     assert not y[0].any() and not y[2].any()   # +0.0 bit pattern
 
@@ -240,7 +267,7 @@ def test_tiny_amax_threshold(ref):
     assert codes[G + 3] == 127
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 def test_sign_symmetry(ref, bits):
     rng = np.random.default_rng(3)
     x = bf16_bits(rng.standard_normal(128 * 50).astype(np.float32) * 3.0)
@@ -250,7 +277,7 @@ def test_sign_symmetry(ref, bits):
     assert np.array_equal(codes_to_int(c1, bits), -codes_to_int(c2, bits))
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 @pytest.mark.parametrize("G", [64, 128])
 def test_round_trip_error_bound_and_extreme_code(ref, bits, G):
     qmax = (1 << (bits - 1)) - 1
@@ -348,24 +375,20 @@ def test_bf16_rounding_against_torch_and_rationals(ref):
     assert ref.bf16_to_f32(0x3F80) == 1.0 and ref.bf16_to_f32(0xC049) == -3.140625
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", ALL_BITS)
 def test_dequant_every_code_times_scale_exact(ref, bits):
     lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
     rng = np.random.default_rng(37)
     n_codes = hi - lo + 1
-    G = 256 if bits == 8 else 16
-    assert n_codes == G
+    G = n_codes
+    assert G in (16, 32, 64, 256)
     scales = np.concatenate([
         rng.standard_normal(500).astype(np.float32) ** 2 *
         (10.0 ** rng.integers(-30, 30, 500)).astype(np.float32),
         np.array([1.0, 2.0 ** -107, 2.0 ** -126, 1e-42, 0.0, 2.0e36], np.float32)])
     scales = scales.astype(np.float32)
     q = np.tile(np.arange(lo, hi + 1, dtype=np.int32), (scales.size, 1))
-    if bits == 8:
-        codes = q.astype(np.int8).view(np.uint8).reshape(-1)
-    else:
-        u = (q & 0xF).astype(np.uint8)
-        codes = (u[:, 0::2] | (u[:, 1::2] << 4)).reshape(-1)
+    codes = pack_codes(q, bits)
     y = ref.act_dequant(codes, scales, q.size, G, bits).reshape(scales.size, G)
     prod = (q.astype(np.float64) * scales.astype(np.float64)[:, None]).astype(np.float32)
     want = torch.from_numpy(prod).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
