@@ -29,10 +29,15 @@
  *                           code  = rint(x * inv)   (ties to even; |code| <= qmax)
  *     and dequantization is value = (float)code * scale.
  *   - Inputs must be finite; NaN/Inf give unspecified codes (never a fault).
- *   - Code layout: 8-bit codes are int8, one per element.  4-bit codes are
- *     two's-complement nibbles, byte m holding element 2m in bits 0-3 and
- *     element 2m+1 in bits 4-7.  Scales are fp32, one per group, in group
- *     order.
+ *   - Code layout: codes are two's-complement fields of `bits` bits.  8-bit
+ *     codes are int8, one per element.  4-bit codes: byte m holds element 2m
+ *     in bits 0-3 and element 2m+1 in bits 4-7.  5- and 6-bit codes occupy
+ *     two planes over the whole tensor: the low four bits of every code form
+ *     a plane laid out exactly like 4-bit codes (numel/2 bytes); the high
+ *     bits follow at byte offset numel/2: for 5 bits, bit j of byte m is the
+ *     high bit of element 8m+j; for 6 bits, bits 2j..2j+1 of byte m are the
+ *     two high bits of element 4m+j.  Scales are fp32, one per group, in
+ *     group order.
  */
 #ifndef AGOQ_H
 #define AGOQ_H
@@ -46,7 +51,7 @@ extern "C" {
 enum {
     AGOQ_OK = 0,
     AGOQ_ERR_NULL = 1,  /* a required pointer is NULL */
-    AGOQ_ERR_BITS = 2,  /* bits is not 4 or 8 */
+    AGOQ_ERR_BITS = 2,  /* bits is not 4, 5, 6 or 8 */
     AGOQ_ERR_GROUP = 3, /* group is not 64 or 128 */
     AGOQ_ERR_SHAPE = 4, /* numel <= 0, numel % group != 0, or a stride below its extent */
     AGOQ_ERR_ALIGN = 5, /* a pointer (or a chunk stride) breaks 16-byte alignment */
@@ -61,7 +66,7 @@ enum {
  * block-wise quantization with block size 128; "Dynamic Bit-width
  * Compensation", later pipeline stages use wider codes).
  *   x_bf16 : in,  numel bf16 values
- *   bits   : 4 or 8, the width the bit map assigns to this tensor
+ *   bits   : 4, 5, 6 or 8, the width the bit map assigns to this tensor
  *   codes  : out, numel*bits/8 bytes
  *   scales : out, numel/group fp32
  */
@@ -160,13 +165,16 @@ int agoq_dbca_bits(int n_stages, int stage_1based, int *bits_out);
  * RMSNorms, the input of the attention output projection, and the two inputs
  * of SiLU & Multiply; attention's own tensors stay in bf16).  The slots of
  * bits_out are, in order: norm1 input, out-proj input, norm2 input, gate, up.
- * With only 4- and 8-bit codes a stage's target width B (4..8, from
- * agoq_dbca_bits) is realized as a mix: B=4 all 4-bit; B=5 both norm inputs
- * 8-bit; B=6 and B=7 norm inputs and gate 8-bit; B=8 all 8-bit.
+ * agoq_layer_bitmap_native gives every stored tensor the stage's own width
+ * B (4..8, from agoq_dbca_bits; there are no 7-bit codes, B=7 is stored at 6).
+ * agoq_layer_bitmap realizes B with 4- and 8-bit codes only, as a mix: B=4 all
+ * 4-bit; B=5 both norm inputs 8-bit; B=6 and B=7 norm inputs and gate 8-bit;
+ * B=8 all 8-bit.
  */
 enum { AGOQ_SLOT_NORM1_IN = 0, AGOQ_SLOT_OPROJ_IN = 1, AGOQ_SLOT_NORM2_IN = 2,
        AGOQ_SLOT_GATE = 3, AGOQ_SLOT_UP = 4, AGOQ_LAYER_SLOTS = 5 };
 int agoq_layer_bitmap(int target_bits, int bits_out[AGOQ_LAYER_SLOTS]);
+int agoq_layer_bitmap_native(int target_bits, int bits_out[AGOQ_LAYER_SLOTS]);
 
 /*
  * Bytes that one layer's five stored tensors occupy under a bit map

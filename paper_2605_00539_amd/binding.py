@@ -48,6 +48,7 @@ def load_library():
     L.agoq_dbca_stored_microbatches.argtypes = [_INT, _INT]
     L.agoq_dbca_bits.argtypes = [_INT, _INT, ctypes.POINTER(_INT)]
     L.agoq_layer_bitmap.argtypes = [_INT, ctypes.POINTER(_INT * _SLOTS)]
+    L.agoq_layer_bitmap_native.argtypes = [_INT, ctypes.POINTER(_INT * _SLOTS)]
     L.agoq_layer_stored_bytes.argtypes = [_I64, _I64, _I64, _INT, ctypes.POINTER(_INT * _SLOTS), _INT]
     L.agoq_layer_stored_bytes.restype = _I64
     L.agoq_strerror.argtypes = [_INT]
@@ -251,9 +252,12 @@ def dbca_bits(n_stages, stage):
     return out.value
 
 
-def layer_bitmap(target_bits):
+def layer_bitmap(target_bits, native=False):
+    """Bits for (norm1 input, out-proj input, norm2 input, gate, up).  native=True: every
+    tensor at the stage's own width; else a mix of 4- and 8-bit codes."""
     arr = (_INT * _SLOTS)()
-    _check(load_library().agoq_layer_bitmap(target_bits, ctypes.byref(arr)))
+    fn = load_library().agoq_layer_bitmap_native if native else load_library().agoq_layer_bitmap
+    _check(fn(target_bits, ctypes.byref(arr)))
     return list(arr)
 
 

@@ -9,7 +9,7 @@ extern "C" {
 
 int64_t agoq_codes_bytes(int64_t numel, int bits)
 {
-    if (numel < 0 || (bits != 4 && bits != 8)) return -1;
+    if (numel < 0 || (bits != 4 && bits != 5 && bits != 6 && bits != 8)) return -1;
     return numel * bits / 8;
 }
 
@@ -56,6 +56,15 @@ int agoq_layer_bitmap(int target_bits, int bits_out[AGOQ_LAYER_SLOTS])
     return AGOQ_OK;
 }
 
+int agoq_layer_bitmap_native(int target_bits, int bits_out[AGOQ_LAYER_SLOTS])
+{
+    if (!bits_out) return AGOQ_ERR_NULL;
+    if (target_bits < 4 || target_bits > 8) return AGOQ_ERR_BITS;
+    const int b = target_bits == 7 ? 6 : target_bits;   // no 7-bit codes: stay under the budget
+    for (int s = 0; s < AGOQ_LAYER_SLOTS; ++s) bits_out[s] = b;
+    return AGOQ_OK;
+}
+
 int64_t agoq_layer_stored_bytes(int64_t tokens, int64_t hidden, int64_t ffn, int group,
                                 const int bits[AGOQ_LAYER_SLOTS], int with_scales)
 {
@@ -78,7 +87,7 @@ const char* agoq_strerror(int status)
     switch (status) {
     case AGOQ_OK: return "ok";
     case AGOQ_ERR_NULL: return "null pointer";
-    case AGOQ_ERR_BITS: return "unsupported bit-width (4 or 8)";
+    case AGOQ_ERR_BITS: return "unsupported bit-width (4, 5, 6 or 8)";
     case AGOQ_ERR_GROUP: return "unsupported group size (64 or 128)";
     case AGOQ_ERR_SHAPE: return "numel must be a positive multiple of group; strides must cover the extents";
     case AGOQ_ERR_ALIGN: return "pointers and chunk strides must be 16-byte aligned";

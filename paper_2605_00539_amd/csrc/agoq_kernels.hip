@@ -195,9 +195,11 @@ __device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
 }
 
 // ---------------------------------------------------------------------------
-// Activation quantize: bf16 -> 4- or 8-bit codes + fp32 scale per group.
+// Activation quantize: bf16 -> 4-, 5-, 6- or 8-bit codes + fp32 scale per group.
 // One lane owns 8 consecutive elements (one 16-byte load) of a group;
-// GROUP/8 consecutive lanes own a group.
+// GROUP/8 consecutive lanes own a group.  5- and 6-bit codes go to two planes:
+// the low nibbles exactly where 4-bit codes would go, the remaining high bits
+// (one byte or two bytes per lane) to a second plane that starts n_vec*4 bytes in.
 // ---------------------------------------------------------------------------
 template <int BITS, int GROUP, int UNROLL>
 __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
@@ -238,6 +240,20 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
 #pragma unroll
                 for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
                 st<NTS>((u32*)codes + vi, p);
+            } else if (BITS == 5 || BITS == 6) {
+                u32 p = 0, h = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const u32 c = code_bits(f[j], inv);
+                    p = push_nibble(p, c);
+                    h = __builtin_amdgcn_alignbit(c >> 4, h, BITS - 4);  // bits 4.. of the code
+                }
+                st<NTS>((u32*)codes + vi, p);
+                uint8_t* high = (uint8_t*)codes + n_vec * 4;
+                if (BITS == 5)
+                    st<NTS>(high + vi, (uint8_t)(h >> 24));
+                else
+                    st<NTS>((uint16_t*)high + vi, (uint16_t)(h >> 16));
             } else {
                 u32 p0 = 0, p1 = 0;
 #pragma unroll
@@ -265,7 +281,7 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
     constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
-    u32x2 c[UNROLL];
+    u32x2 c[UNROLL];    // 8-bit: both words are codes; 5/6-bit: [0] nibbles, [1] high bits
     float s[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -273,10 +289,14 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
         c[u] = u32x2{0, 0};
         s[u] = 0.0f;
         if (vi < n_vec) {
-            if (BITS == 4)
-                c[u][0] = ld<NTC>((const u32*)codes + vi);
-            else
+            if (BITS == 8) {
                 c[u] = ld<NTC>((const u32x2*)codes + vi);
+            } else {
+                c[u][0] = ld<NTC>((const u32*)codes + vi);
+                const uint8_t* high = (const uint8_t*)codes + n_vec * 4;
+                if (BITS == 5) c[u][1] = ld<NTC>(high + vi);
+                if (BITS == 6) c[u][1] = ld<NTC>((const uint16_t*)high + vi);
+            }
             s[u] = ld<NTSC>(scales + vi / LANES);
         }
     }
@@ -287,10 +307,16 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             float q;
-            if (BITS == 4)
+            if (BITS == 4) {
                 q = (float)(int)__builtin_amdgcn_sbfe((int)c[u][0], 4 * j, 4);  // the builtin returns unsigned
-            else
+            } else if (BITS == 8) {
                 q = byte_to_f32(c[u][j >> 2], j & 3);
+            } else {
+                // signed high field * 16 + unsigned low nibble
+                const int hi = (int)__builtin_amdgcn_sbfe((int)c[u][1], (BITS - 4) * j, BITS - 4);
+                const u32 lo = __builtin_amdgcn_ubfe(c[u][0], 4 * j, 4);
+                q = (float)(int)(((u32)hi << 4) | lo);
+            }
             f[j] = __fmul_rn(q, s[u]);
         }
         if (vi < n_vec)
@@ -652,7 +678,7 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
                    float* scales, void* stream)
 {
     if (!x_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
-    if (bits != 4 && bits != 8) return AGOQ_ERR_BITS;
+    if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
@@ -666,14 +692,20 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     case 2: act_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
     default: act_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;  \
     }
-    if (bits == 4 && group == 128) {
-        AGOQ_LAUNCH_AQ(4, 128)
-    } else if (bits == 4) {
-        AGOQ_LAUNCH_AQ(4, 64)
-    } else if (group == 128) {
-        AGOQ_LAUNCH_AQ(8, 128)
+    if (group == 128) {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_AQ(4, 128) break;
+        case 5: AGOQ_LAUNCH_AQ(5, 128) break;
+        case 6: AGOQ_LAUNCH_AQ(6, 128) break;
+        default: AGOQ_LAUNCH_AQ(8, 128) break;
+        }
     } else {
-        AGOQ_LAUNCH_AQ(8, 64)
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_AQ(4, 64) break;
+        case 5: AGOQ_LAUNCH_AQ(5, 64) break;
+        case 6: AGOQ_LAUNCH_AQ(6, 64) break;
+        default: AGOQ_LAUNCH_AQ(8, 64) break;
+        }
     }
 #undef AGOQ_LAUNCH_AQ
     return launch_status();
@@ -683,14 +715,14 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
                      void* y_bf16, void* stream)
 {
     if (!codes || !scales || !y_bf16) return AGOQ_ERR_NULL;
-    if (bits != 4 && bits != 8) return AGOQ_ERR_BITS;
+    if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
     // measured: 4-bit codes run best with four vectors per lane at every size; 8-bit codes
     // with four when the whole grid is resident at once and with one otherwise
     int unroll = AGOQ_DQ_FORCE_UNROLL;
-    if (unroll == 0) unroll = (bits == 4 || fits_one_round(n_vec, AGOQ_DQ_BLOCK, 4)) ? 4 : 1;
+    if (unroll == 0) unroll = (bits != 8 || fits_one_round(n_vec, AGOQ_DQ_BLOCK, 4)) ? 4 : 1;
     const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
@@ -700,14 +732,20 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     case 2: act_dequant_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
     default: act_dequant_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break; \
     }
-    if (bits == 4 && group == 128) {
-        AGOQ_LAUNCH_DQ(4, 128)
-    } else if (bits == 4) {
-        AGOQ_LAUNCH_DQ(4, 64)
-    } else if (group == 128) {
-        AGOQ_LAUNCH_DQ(8, 128)
+    if (group == 128) {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_DQ(4, 128) break;
+        case 5: AGOQ_LAUNCH_DQ(5, 128) break;
+        case 6: AGOQ_LAUNCH_DQ(6, 128) break;
+        default: AGOQ_LAUNCH_DQ(8, 128) break;
+        }
     } else {
-        AGOQ_LAUNCH_DQ(8, 64)
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_DQ(4, 64) break;
+        case 5: AGOQ_LAUNCH_DQ(5, 64) break;
+        case 6: AGOQ_LAUNCH_DQ(6, 64) break;
+        default: AGOQ_LAUNCH_DQ(8, 64) break;
+        }
     }
 #undef AGOQ_LAUNCH_DQ
     return launch_status();

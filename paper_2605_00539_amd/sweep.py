@@ -207,25 +207,28 @@ def main():
     for name, cols in (("H", c["hidden"]), ("F", c["ffn"])):
         before = len(rows)
         act_case("5-stage", name, c["rows"], cols, c["dist"], c["outlier_frac"], c["outlier_scale"],
-                 c["seed"], [c["group"]], [4, 8])
+                 c["seed"], [c["group"]], [4, 5, 6, 8])
         for r in rows[before:]:
-            per[(name, r["kernel"], 4 if " b4 " in r["case"] else 8)] = r
+            per[(name, r["kernel"], int(r["case"].split(" b")[1].split()[0]))] = r
     gcfg = c["grad"]
     grad_case("5-stage", gcfg["n"], gcfg["sigma"], gcfg["spike_frac"], gcfg["spike_scale"], c["seed"], c["K"], c["group"])
     # whole-layer figures per stage bit map (sum of the five tensors' launches)
     bf16_bytes = c["rows"] * (3 * c["hidden"] + 2 * c["ffn"]) * 2
     for stage in (1, 2, 3, 4):
         b = agoq.dbca_bits(4, stage)
-        bitmap = agoq.layer_bitmap(b)
-        stored = agoq.layer_stored_bytes(c["rows"], c["hidden"], c["ffn"], c["group"], bitmap, True)
-        for kernel in ("act_quant", "act_dequant"):
-            us = nb = 0.0
-            for slot, bits in enumerate(bitmap):
-                r = per[("F" if slot >= 3 else "H", kernel, bits)]
-                us += r["us"]
-                nb += r["algo_MB"] * 1e6
-            report("5-stage", kernel + "_layer", "stage %d (B=%d) map %s stored %d B (%.1f%% saved vs bf16)" %
-                   (stage, b, bitmap, stored, 100.0 * (1 - stored / bf16_bytes)), us, nb)
+        for native in (True, False):
+            bitmap = agoq.layer_bitmap(b, native=native)
+            if not native and bitmap == agoq.layer_bitmap(b, native=True):
+                continue
+            stored = agoq.layer_stored_bytes(c["rows"], c["hidden"], c["ffn"], c["group"], bitmap, True)
+            for kernel in ("act_quant", "act_dequant"):
+                us = nb = 0.0
+                for slot, bits in enumerate(bitmap):
+                    r = per[("F" if slot >= 3 else "H", kernel, bits)]
+                    us += r["us"]
+                    nb += r["algo_MB"] * 1e6
+                report("5-stage", kernel + "_layer", "stage %d (B=%d) map %s stored %d B (%.1f%% saved vs bf16)" %
+                       (stage, b, bitmap, stored, 100.0 * (1 - stored / bf16_bytes)), us, nb)
     print(json.dumps(rows))
     return 0
 

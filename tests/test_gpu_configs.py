@@ -83,10 +83,11 @@ def test_stage_sweep_layer_activations(agoq, ref):
     rows, hidden, ffn, group = cfg["rows"], cfg["hidden"], cfg["ffn"], cfg["group"]
     shapes = [hidden, hidden, hidden, ffn, ffn]          # norm1-in, oproj-in, norm2-in, gate, up
     maps = {b: agoq.layer_bitmap(b) for b in (agoq.dbca_bits(4, s) for s in (1, 2, 3, 4))}
+    native = {b: agoq.layer_bitmap(b, native=True) for b in maps}
     assert sorted(maps) == [4, 5, 6, 8]
     for slot, cols in enumerate(shapes):
         x = act_tensor(cfg, rows, cols, cfg["seed"] + slot)
-        for bits in sorted({m[slot] for m in maps.values()}):
+        for bits in sorted({m[slot] for m in maps.values()} | {m[slot] for m in native.values()}):
             check_act_full(agoq, ref, x, group, bits)
         del x
     # bytes saved against bf16, closed form (codes + scales)
@@ -94,6 +95,8 @@ def test_stage_sweep_layer_activations(agoq, ref):
     stored = {b: agoq.layer_stored_bytes(rows, hidden, ffn, group, m, True) for b, m in maps.items()}
     assert bf16_bytes == 671088640
     assert stored == {4: 178257920, 5: 211812352, 6: 270532608, 8: 346030080}
+    stored_native = {b: agoq.layer_stored_bytes(rows, hidden, ffn, group, m, True) for b, m in native.items()}
+    assert stored_native == {b: bf16_bytes // 16 * b + 4 * (bf16_bytes // 2 // group) for b in (4, 5, 6, 8)}
 
 
 # ---- configs 3 and 5: one decoder layer's gradients, K = 8 and K = 16 ----------------

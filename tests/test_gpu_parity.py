@@ -82,7 +82,7 @@ def test_tiny_gradient_quant_and_reduce(agoq, ref):
 
 # ---- sizes that span several blocks and leave a ragged tail -------------------
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 5, 6, 8])
 @pytest.mark.parametrize("group", [64, 128])
 @pytest.mark.parametrize("n_groups", [1, 3, 64, 65, 8 * 64 + 5, 3 * 8192 // 64 + 7, 40013])
 def test_activation_sizes(agoq, ref, bits, group, n_groups):
@@ -93,7 +93,7 @@ def test_activation_sizes(agoq, ref, bits, group, n_groups):
     check_act(agoq, ref, xb, group, bits)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 5, 6, 8])
 @pytest.mark.parametrize("group", [64, 128])
 def test_every_bf16_pattern(agoq, ref, bits, group):
     # all finite bf16 patterns (denormals included), shuffled, plus sorted runs so that
@@ -111,7 +111,7 @@ def test_every_bf16_pattern(agoq, ref, bits, group):
     check_act(agoq, ref, x, group, bits)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 5, 6, 8])
 def test_zero_and_tiny_groups(agoq, ref, bits):
     group = 128
     x = np.zeros((6, group), np.uint16)
@@ -125,11 +125,10 @@ def test_zero_and_tiny_groups(agoq, ref, bits):
     torch.cuda.synchronize()
     s = scales.cpu().numpy()
     assert s[0] == 0 and s[1] == 0 and s[2] == 0 and s[4] == 0 and s[3] > 0 and s[5] > 0
-    gb = group * bits // 8
-    assert not codes.cpu().numpy()[: 3 * gb].any()
+    assert not codes.cpu().numpy()[: 3 * group // 2 if bits != 8 else 3 * group].any()
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 5, 6, 8])
 @pytest.mark.parametrize("group", [64, 128])
 def test_dequant_arbitrary_codes_and_scales(agoq, ref, bits, group):
     # any byte is a legal code (incl. -8 / -128); scales span denormals to large values
@@ -234,7 +233,7 @@ def test_error_codes(agoq):
     P = ctypes.c_void_p
     px, pc, ps = P(x.data_ptr()), P(codes.data_ptr()), P(scales.data_ptr())
     assert L.agoq_act_quant(None, 1024, 128, 4, pc, ps, None) == 1
-    assert L.agoq_act_quant(px, 1024, 128, 5, pc, ps, None) == 2
+    assert L.agoq_act_quant(px, 1024, 128, 7, pc, ps, None) == 2
     assert L.agoq_act_quant(px, 1024, 32, 4, pc, ps, None) == 3
     assert L.agoq_act_quant(px, 1000, 128, 4, pc, ps, None) == 4
     assert L.agoq_act_quant(px, 0, 128, 4, pc, ps, None) == 4
@@ -254,7 +253,7 @@ def test_error_codes(agoq):
     torch.cuda.synchronize()
     assert bool((codes == 7).all()) and bool((scales == 3.0).all())
     with pytest.raises(agoq.AgoqError):
-        agoq.act_quant(x, 128, 6)
+        agoq.act_quant(x, 128, 7)
     with pytest.raises(TypeError):
         agoq.act_quant(x.float(), 128, 4)
     with pytest.raises(TypeError):

@@ -38,7 +38,8 @@ def test_library_exports_every_declared_symbol(agoq):
 def test_size_helpers(agoq):
     assert agoq.codes_bytes(1 << 20, 4) == 1 << 19
     assert agoq.codes_bytes(1 << 20, 8) == 1 << 20
-    assert agoq.codes_bytes(128, 5) == -1
+    assert agoq.codes_bytes(128, 5) == 80 and agoq.codes_bytes(128, 6) == 96
+    assert agoq.codes_bytes(128, 7) == -1 and agoq.codes_bytes(128, 3) == -1
     assert agoq.num_groups(4096 * 14336, 128) == 4096 * 14336 // 128
     assert agoq.num_groups(100, 64) == -1
     assert agoq.strerror(0) == "ok" and "group" in agoq.strerror(3)
@@ -103,6 +104,18 @@ def test_stage_bitmaps_average_width(agoq):
     assert agoq.layer_bitmap(5) == [8, 4, 8, 4, 4] and agoq.layer_bitmap(6) == [8, 4, 8, 8, 4]
     with pytest.raises(agoq.AgoqError):
         agoq.layer_bitmap(3)
+    # native maps: every tensor at the stage's own width, stored bytes scale with it
+    for b, stored_b in ((4, 4), (5, 5), (6, 6), (7, 6), (8, 8)):
+        bits = agoq.layer_bitmap(b, native=True)
+        assert bits == [stored_b] * 5
+        codes_only = agoq.layer_stored_bytes(8192, 4096, 14336, 128, bits, False)
+        assert codes_only == 8192 * (3 * 4096 + 2 * 14336) * stored_b // 8
+    # the paper's budget argument: stage i holds N_i micro-batches at B_i bits; none exceeds stage 1
+    n1 = agoq.dbca_stored_microbatches(4, 1)
+    for stage in (1, 2, 3, 4):
+        b = agoq.layer_bitmap(agoq.dbca_bits(4, stage), native=True)[0]
+        ni = agoq.dbca_stored_microbatches(4, stage)
+        assert (b - 0.5) * ni <= 4 * n1
 
 
 def test_generated_isa_has_no_packed_fp32_math(tmp_path):
