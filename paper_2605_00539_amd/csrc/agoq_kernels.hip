@@ -150,13 +150,8 @@ __device__ __forceinline__ void scale_and_inv(u32 amax_bits, float& scale, float
     const float amax = as_f32(amax_bits);
     const bool live = amax_bits >= kAmaxMinBits;
     const float den = live ? amax : 1.0f;
-#ifdef AGOQ_EXP_NODIV   // timing experiment only: wrong arithmetic
-    const float s = amax * (1.0f / (float)QMAX);
-    const float r = (float)QMAX * __builtin_amdgcn_rcpf(den);
-#else
     const float s = __fdiv_rn(amax, (float)QMAX);
     const float r = __fdiv_rn((float)QMAX, den);
-#endif
     scale = live ? s : 0.0f;
     inv = live ? r : 0.0f;
 }
