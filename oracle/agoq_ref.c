@@ -40,7 +40,8 @@
  *
  * Parity status of each function:
  *   act_quant / act_dequant / grad_quant / grad_reduce_requant /
- *   grad_accumulate / grad_dequant / dbca_bits:  pinned by tests/test_oracle_*.py
+ *   grad_accumulate / grad_dequant / act_dequant_rmsnorm / act_dequant_silu_mul /
+ *   dbca_bits:  pinned by tests/test_oracle_*.py
  *   (exact-arithmetic brute force over all bf16 patterns, closed forms on
  *   power-of-two scales, tie cases, byte-level packing fixtures, the
  *   round-trip bound, library cross-checks and the values the paper prints
@@ -244,6 +245,83 @@ int agoq_ref_act_dequant(const uint8_t *codes, const float *scales, int64_t nume
             float v = (float)get_code(codes, numel, g * group + j, bits) * s;
             y[g * group + j] = f32_to_bf16_bits(v);
         }
+    }
+    return REF_OK;
+}
+
+/* ---- dequantize fused with the recomputation of the layer's forward ------ */
+
+/*
+ * Case-1 recomputation for RMSNorm ("Error Analysis of Activation Quantization /
+ * RMSNorm"; Eq. (rmsnorm)): only the quantized input X is stored; r and the
+ * normalized output are recomputed from the dequantized X' in the backward pass.
+ *   x'_ij = bf16(code_ij * scale)                      (exactly act_dequant's output)
+ *   r_i   = sqrt( (1/d) * sum_j x'_ij^2 + eps )        (d = cols), in binary64
+ *   y_ij  = bf16( gamma_j * x'_ij / r_i )
+ * This is the plain definition in binary64; the GPU computes in binary32, so parity
+ * for y is "equal, or one bf16 step apart where the exact value sits at a rounding
+ * boundary", and relative 2e-6 for r.
+ */
+int agoq_ref_act_dequant_rmsnorm(const uint8_t *codes, const float *scales, int64_t rows,
+                                 int64_t cols, int group, int bits, const float *gamma,
+                                 float eps, uint16_t *y, float *r_out)
+{
+    if (!codes || !scales || !gamma || !y || !r_out)
+        return REF_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || cols % group != 0)
+        return REF_ERR_SHAPE;
+    const int64_t numel = rows * cols;
+    int rc = check_shape(numel, group, bits);
+    if (rc)
+        return rc;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double ss = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            const int64_t e = i * cols + j;
+            float v = (float)get_code(codes, numel, e, bits) * scales[e / group];
+            double x = (double)bf16_bits_to_f32(f32_to_bf16_bits(v));
+            ss += x * x;
+        }
+        const double r = sqrt(ss / (double)cols + (double)eps);
+        r_out[i] = (float)r;
+        for (int64_t j = 0; j < cols; ++j) {
+            const int64_t e = i * cols + j;
+            float v = (float)get_code(codes, numel, e, bits) * scales[e / group];
+            double x = (double)bf16_bits_to_f32(f32_to_bf16_bits(v));
+            y[e] = f32_to_bf16_bits((float)((double)gamma[j] * x / r));
+        }
+    }
+    return REF_OK;
+}
+
+/*
+ * Case-1 recomputation for SiLU & Multiply (appendix "SiLU & Multiply": z = x * y *
+ * sigma(y)): the stored inputs are the gate (through SiLU) and the up projection; the
+ * input of the second FFN GEMM is recomputed from their dequantized values.
+ *   g' = bf16(code_g * scale_g), u' = bf16(code_u * scale_u)
+ *   z  = bf16( u' * g' / (1 + exp(-g')) )              in binary64
+ */
+int agoq_ref_act_dequant_silu_mul(const uint8_t *gate_codes, const float *gate_scales,
+                                  int gate_bits, const uint8_t *up_codes,
+                                  const float *up_scales, int up_bits, int64_t numel, int group,
+                                  uint16_t *z)
+{
+    if (!gate_codes || !gate_scales || !up_codes || !up_scales || !z)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, gate_bits);
+    if (rc)
+        return rc;
+    rc = check_shape(numel, group, up_bits);
+    if (rc)
+        return rc;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < numel; ++e) {
+        float gv = (float)get_code(gate_codes, numel, e, gate_bits) * gate_scales[e / group];
+        float uv = (float)get_code(up_codes, numel, e, up_bits) * up_scales[e / group];
+        double g = (double)bf16_bits_to_f32(f32_to_bf16_bits(gv));
+        double u = (double)bf16_bits_to_f32(f32_to_bf16_bits(uv));
+        z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-g))));
     }
     return REF_OK;
 }

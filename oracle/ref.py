@@ -12,7 +12,7 @@ import numpy as np
 from . import build as _build
 
 __all__ = [
-    "lib", "act_quant", "act_dequant", "grad_quant", "grad_dequant",
+    "lib", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
     "grad_reduce_requant", "grad_reduce_f64", "grad_accumulate", "dbca_bits",
     "dbca_stored_microbatches", "bf16_to_f32", "f32_to_bf16", "max_threads",
     "set_threads", "OracleError", "Oracle",
@@ -38,6 +38,8 @@ def _bind(path):
     L.agoq_ref_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P]
     L.agoq_ref_grad_reduce_f64.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P]
     L.agoq_ref_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P]
+    L.agoq_ref_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _INT, _P, ctypes.c_float, _P, _P]
+    L.agoq_ref_act_dequant_silu_mul.argtypes = [_P, _P, _INT, _P, _P, _INT, _I64, _INT, _P]
     L.agoq_ref_dbca_bits.argtypes = [_INT, _INT, ctypes.POINTER(_INT)]
     L.agoq_ref_dbca_stored_microbatches.argtypes = [_INT, _INT]
     L.agoq_ref_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -103,6 +105,29 @@ class Oracle:
         _check(self.lib.agoq_ref_act_dequant(_ptr(codes), _ptr(scales), numel, group, bits,
                                              _ptr(y)))
         return y
+
+    def act_dequant_rmsnorm(self, codes, scales, rows, cols, group, bits, gamma, eps):
+        """Returns (y bf16 bits [rows*cols], r float32 [rows])."""
+        codes = _c(codes, np.uint8).reshape(-1)
+        scales = _c(scales, np.float32).reshape(-1)
+        gamma = _c(gamma, np.float32).reshape(-1)
+        y = np.zeros(rows * cols, np.uint16)
+        r = np.zeros(rows, np.float32)
+        _check(self.lib.agoq_ref_act_dequant_rmsnorm(_ptr(codes), _ptr(scales), rows, cols, group,
+                                                     bits, _ptr(gamma), float(eps), _ptr(y), _ptr(r)))
+        return y, r
+
+    def act_dequant_silu_mul(self, gate_codes, gate_scales, gate_bits, up_codes, up_scales, up_bits,
+                             numel, group):
+        gate_codes = _c(gate_codes, np.uint8).reshape(-1)
+        up_codes = _c(up_codes, np.uint8).reshape(-1)
+        gate_scales = _c(gate_scales, np.float32).reshape(-1)
+        up_scales = _c(up_scales, np.float32).reshape(-1)
+        z = np.zeros(numel, np.uint16)
+        _check(self.lib.agoq_ref_act_dequant_silu_mul(
+            _ptr(gate_codes), _ptr(gate_scales), gate_bits, _ptr(up_codes), _ptr(up_scales),
+            up_bits, numel, group, _ptr(z)))
+        return z
 
     def grad_quant(self, g, group):
         g = _c(g, np.float32).reshape(-1)
@@ -184,6 +209,8 @@ _default = Oracle()
 lib = _default.lib
 act_quant = _default.act_quant
 act_dequant = _default.act_dequant
+act_dequant_rmsnorm = _default.act_dequant_rmsnorm
+act_dequant_silu_mul = _default.act_dequant_silu_mul
 grad_quant = _default.grad_quant
 grad_dequant = _default.grad_dequant
 grad_reduce_requant = _default.grad_reduce_requant

@@ -9,6 +9,7 @@ import pytest
 
 import test_oracle_quant_pins as quant_pins
 import test_oracle_reduce_pins as reduce_pins
+import test_oracle_recompute_pins as recompute_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "agoq_ref.c")
@@ -47,6 +48,18 @@ MUTANTS = [
      "acc[j] = (float)main_codes[i] * s + add;"),
     ("accumulate_drops_new_gradient", "acc[j] = fmaf((float)main_codes[i], s, add);",
      "acc[j] = fmaf((float)main_codes[i], s, 0.0f * add);"),
+    ("rmsnorm_sum_instead_of_mean", "const double r = sqrt(ss / (double)cols + (double)eps);",
+     "const double r = sqrt(ss + (double)eps);"),
+    ("rmsnorm_eps_dropped", "const double r = sqrt(ss / (double)cols + (double)eps);",
+     "const double r = sqrt(ss / (double)cols);"),
+    ("rmsnorm_gamma_of_wrong_column", "y[e] = f32_to_bf16_bits((float)((double)gamma[j] * x / r));",
+     "y[e] = f32_to_bf16_bits((float)((double)gamma[0] * x / r));"),
+    ("rmsnorm_skips_bf16_rounding_of_input", "double x = (double)bf16_bits_to_f32(f32_to_bf16_bits(v));\n            ss += x * x;",
+     "double x = (double)v;\n            ss += x * x;"),
+    ("silu_sigmoid_of_minus_gate", "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-g))));",
+     "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(g))));"),
+    ("silu_applied_to_up", "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-g))));",
+     "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-u))));"),
     ("dbca_printed_index", "return 3 * n_stages - 2 * stage + 1;", "return n_stages + 2 * stage - 1;"),
     ("dbca_floor_instead_of_round", "int r = (int)floor(b + 0.5);", "int r = (int)floor(b);"),
     ("dbca_no_cap", "if (r > 8)\n        r = 8;", ""),
@@ -58,7 +71,7 @@ MUTANTS = [
 def pin_tests():
     """Every pin test of the two pin modules, expanded over its parametrisation."""
     cases = []
-    for mod in (quant_pins, reduce_pins):
+    for mod in (quant_pins, reduce_pins, recompute_pins):
         for name, fn in inspect.getmembers(mod, inspect.isfunction):
             if not name.startswith("test_") or "ref" not in inspect.signature(fn).parameters:
                 continue
