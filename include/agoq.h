@@ -86,6 +86,37 @@ int agoq_act_dequant(const void *codes, const float *scales, int64_t numel, int 
                      void *y_bf16, void *stream);
 
 /*
+ * Dequantize a stored RMSNorm input and recompute the layer's forward from it (paper:
+ * "Error Analysis of Activation Quantization / RMSNorm", Case 1, with Eq. (rmsnorm):
+ * only the quantized input is stored; r and the normalized output are recomputed in the
+ * backward pass).  For each row i of the [rows, cols] tensor:
+ *     x' = bf16(code * scale)                 (what agoq_act_dequant would write)
+ *     r_i = sqrt(mean_j x'_ij^2 + eps),   y_ij = bf16(gamma_j * x'_ij / r_i)
+ * computed in fp32 (results are within one bf16 step of the exact value, r within 2e-6
+ * relative).  Nothing but y and r is written: the dequantized tensor never goes to memory.
+ *   cols   : multiple of group, at most 16384
+ *   gamma  : in, cols fp32
+ *   y_bf16 : out, rows*cols bf16 (the recomputed input of the next GEMM)
+ *   r_out  : out, rows fp32 (for the norm's own backward)
+ */
+int agoq_act_dequant_rmsnorm(const void *codes, const float *scales, int64_t rows, int64_t cols,
+                             int group, int bits, const float *gamma, float eps, void *y_bf16,
+                             float *r_out, void *stream);
+
+/*
+ * Dequantize the two stored inputs of SiLU & Multiply and recompute its output (paper:
+ * appendix "SiLU & Multiply", z = x * y * sigma(y), Case 1: only the quantized inputs are
+ * stored and the input of the second FFN GEMM is recomputed in the backward pass).
+ *     g' = bf16(gate code * scale), u' = bf16(up code * scale), z = bf16(u' * g' * sigmoid(g'))
+ * computed in fp32 (within one bf16 step of the exact value; magnitudes below 2^-100 may
+ * come out as zero).  The two tensors may have
+ * different code widths (4, 5, 6 or 8 each) and share numel and group.
+ */
+int agoq_act_dequant_silu_mul(const void *gate_codes, const float *gate_scales, int gate_bits,
+                              const void *up_codes, const float *up_scales, int up_bits,
+                              int64_t numel, int group, void *z_bf16, void *stream);
+
+/*
  * Store a gradient as 8-bit block-wise codes (paper: "Precision-Preserved
  * Gradient Quantization": the main gradient is kept in 8 bits).
  *   grad   : in,  numel fp32

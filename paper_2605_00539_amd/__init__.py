@@ -5,7 +5,7 @@ include/agoq.h (same names without the prefix).  Every step of the method runs i
 HIP kernels of that library; there is no fallback: without the built library, or
 without a GPU, the calls raise.
 """
-from .binding import (AgoqError, act_dequant, act_quant, codes_bytes, dbca_bits,
+from .binding import (AgoqError, act_dequant, act_dequant_rmsnorm, act_dequant_silu_mul, act_quant, codes_bytes, dbca_bits,
                       dbca_stored_microbatches, grad_accumulate, grad_dequant, grad_quant,
                       grad_reduce_requant,
                       layer_bitmap, layer_stored_bytes, library_path, load_library,
@@ -13,7 +13,7 @@ from .binding import (AgoqError, act_dequant, act_quant, codes_bytes, dbca_bits,
 
 __all__ = [
     "AgoqError", "act_quant", "act_dequant", "grad_quant", "grad_reduce_requant",
-    "grad_accumulate", "grad_dequant",
+    "grad_accumulate", "grad_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul",
     "codes_bytes", "num_groups", "dbca_bits", "dbca_stored_microbatches", "layer_bitmap",
     "layer_stored_bytes", "strerror", "version", "load_library", "library_path",
 ]

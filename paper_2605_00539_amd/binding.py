@@ -39,6 +39,8 @@ def load_library():
     L.agoq_act_dequant.argtypes = [_P, _P, _I64, _INT, _INT, _P, _P]
     L.agoq_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
     L.agoq_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
+    L.agoq_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _INT, _P, ctypes.c_float, _P, _P, _P]
+    L.agoq_act_dequant_silu_mul.argtypes = [_P, _P, _INT, _P, _P, _INT, _I64, _INT, _P, _P]
     L.agoq_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
     L.agoq_codes_bytes.argtypes = [_I64, _INT]
@@ -141,6 +143,50 @@ def act_dequant(codes, scales, numel, group, bits, out=None, stream=None):
     with _on_device(codes.device):
         _check(L.agoq_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
                                   bits, _raw(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, gamma, eps, out=None, r_out=None,
+                        stream=None):
+    """Stored RMSNorm input -> (y bf16 [rows, cols] = gamma * x' / r, r float32 [rows])."""
+    import torch
+    L = load_library()
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    _dev(gamma, torch.float32, "gamma")
+    if gamma.numel() != cols:
+        raise ValueError("gamma must have cols elements")
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.bfloat16, device=codes.device)
+    if r_out is None:
+        r_out = torch.empty(rows, dtype=torch.float32, device=codes.device)
+    _dev(out, torch.bfloat16, "out")
+    _dev(r_out, torch.float32, "r_out")
+    with _on_device(codes.device):
+        _check(L.agoq_act_dequant_rmsnorm(
+            _raw(codes.data_ptr()), _raw(scales.data_ptr()), rows, cols, group, bits,
+            _raw(gamma.data_ptr()), float(eps), _raw(out.data_ptr()), _raw(r_out.data_ptr()),
+            _stream(stream)))
+    return out, r_out
+
+
+def act_dequant_silu_mul(gate_codes, gate_scales, gate_bits, up_codes, up_scales, up_bits, numel,
+                         group, out=None, stream=None):
+    """Stored gate and up tensors -> z bf16 [numel] = up' * gate' * sigmoid(gate')."""
+    import torch
+    L = load_library()
+    _dev(gate_codes, torch.uint8, "gate_codes")
+    _dev(gate_scales, torch.float32, "gate_scales")
+    _dev(up_codes, torch.uint8, "up_codes")
+    _dev(up_scales, torch.float32, "up_scales")
+    if out is None:
+        out = torch.empty(numel, dtype=torch.bfloat16, device=gate_codes.device)
+    _dev(out, torch.bfloat16, "out")
+    with _on_device(gate_codes.device):
+        _check(L.agoq_act_dequant_silu_mul(
+            _raw(gate_codes.data_ptr()), _raw(gate_scales.data_ptr()), gate_bits,
+            _raw(up_codes.data_ptr()), _raw(up_scales.data_ptr()), up_bits, numel, group,
+            _raw(out.data_ptr()), _stream(stream)))
     return out
 
 

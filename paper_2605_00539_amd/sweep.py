@@ -80,7 +80,7 @@ def main():
         print("%-14s %-22s %-34s %10.2f us %10.1f MB %9.1f GB/s %6.1f%%" %
               (config, kernel, case, us, nbytes / 1e6, gbps, 100 * gbps / PEAK), flush=True)
 
-    def act_case(config, label, rows_, cols, dist, frac, scale, seed, group_list, bits_list):
+    def act_case(config, label, rows_, cols, dist, frac, scale, seed, group_list, bits_list, fused=False):
         n = rows_ * cols
         nx = slots_for(2 * n)
         base = wl.act_device(rows_, cols, seed, dist, wl.n_outlier_channels(cols, frac), scale).reshape(-1)
@@ -107,6 +107,21 @@ def main():
                 report(config, "act_quant", case, us, nb)
                 us = timed(lambda i: L.agoq_act_dequant(*da[i % len(da)]), args.launches, args.reps)
                 report(config, "act_dequant", case, us, nb)
+                if fused and cols <= 16384:
+                    # dequantize fused with the RMSNorm recompute (same bytes as a plain dequantize)
+                    gamma = torch.ones(cols, dtype=torch.float32, device=dev)
+                    rs = [torch.empty(rows_, dtype=torch.float32, device=dev) for _ in range(4)]
+                    na = [(P(cs[i % nc].data_ptr()), P(ss[i % nc].data_ptr()), rows_, cols, group, bits,
+                           P(gamma.data_ptr()), ctypes.c_float(1e-5), P(ys[i % nx].data_ptr()),
+                           P(rs[i % 4].data_ptr()), st) for i in range(m)]
+                    us = timed(lambda i: L.agoq_act_dequant_rmsnorm(*na[i % len(na)]), args.launches, args.reps)
+                    report(config, "act_dequant_rmsnorm", case, us, nb + 4 * rows_)
+                    # SiLU & Multiply recompute from two stored tensors of this shape and width
+                    sa = [(P(cs[i % nc].data_ptr()), P(ss[i % nc].data_ptr()), bits,
+                           P(cs[(i + 1) % nc].data_ptr()), P(ss[(i + 1) % nc].data_ptr()), bits, n, group,
+                           P(ys[i % nx].data_ptr()), st) for i in range(m)]
+                    us = timed(lambda i: L.agoq_act_dequant_silu_mul(*sa[i % len(sa)]), args.launches, args.reps)
+                    report(config, "act_dequant_silu_mul", case, us, 2 * (n * bits // 8 + 4 * (n // group)) + 2 * n)
                 del cs, ss
         del xs, ys, base
 
@@ -207,7 +222,7 @@ def main():
     for name, cols in (("H", c["hidden"]), ("F", c["ffn"])):
         before = len(rows)
         act_case("5-stage", name, c["rows"], cols, c["dist"], c["outlier_frac"], c["outlier_scale"],
-                 c["seed"], [c["group"]], [4, 5, 6, 8])
+                 c["seed"], [c["group"]], [4, 5, 6, 8], fused=True)
         for r in rows[before:]:
             per[(name, r["kernel"], int(r["case"].split(" b")[1].split()[0]))] = r
     gcfg = c["grad"]
