@@ -469,6 +469,218 @@ int agoq_ref_grad_accumulate(const int8_t *main_codes, const float *main_scales,
     return REF_OK;
 }
 
+/* ======================================================================= */
+/* Floating-point code books: the formats the paper names ("block-wise FP4  */
+/* quantization" for activations, "FP8" for gradients), read as E2M1 and     */
+/* OCP E4M3 (no infinities), block-wise abs-max scaled like the integer      */
+/* grids above:                                                              */
+/*     scale = amax / vmax,  inv = vmax / amax,  code = nearest(x * inv)     */
+/* with vmax = 6 (E2M1) or 448 (E4M3), nearest = round to the nearest        */
+/* representable value, ties to the code with an even mantissa, the sign bit */
+/* of the code being the sign bit of x * inv.  Groups with amax < 2^-100     */
+/* store scale 0 and all-zero codes.                                          */
+/* ======================================================================= */
+
+/* magnitude of E2M1 code index 0..7: exponent field e = idx >> 1, mantissa m = idx & 1;
+   e == 0: m * 0.5 (subnormal);  else (1 + m/2) * 2^(e-1) */
+static float e2m1_magnitude(int idx)
+{
+    const int e = idx >> 1, m = idx & 1;
+    if (e == 0)
+        return 0.5f * (float)m;
+    return ldexpf(1.0f + 0.5f * (float)m, e - 1);
+}
+
+/* magnitude of E4M3 code index 0..126 (index 127 is NaN): e = idx >> 3, m = idx & 7, bias 7;
+   e == 0: m * 2^-9;  else (1 + m/8) * 2^(e-7) */
+static float e4m3_magnitude(int idx)
+{
+    const int e = idx >> 3, m = idx & 7;
+    if (e == 0)
+        return ldexpf((float)m, -9);
+    return ldexpf(1.0f + (float)m / 8.0f, e - 7);
+}
+
+/* index of the representable magnitude nearest to a >= 0 among n_values (increasing),
+   ties to the even index, beyond the last value: the last value (saturation) */
+static int nearest_index(float a, int n_values, float (*magnitude)(int))
+{
+    int best = 0;
+    double best_d = fabs((double)a - (double)magnitude(0));
+    for (int i = 1; i < n_values; ++i) {
+        const double d = fabs((double)a - (double)magnitude(i));
+        if (d < best_d || (d == best_d && (i % 2 == 0))) {
+            best = i;
+            best_d = d;
+        }
+    }
+    return best;
+}
+
+static uint8_t e2m1_encode(float t)
+{
+    const int idx = nearest_index(fabsf(t), 8, e2m1_magnitude);
+    return (uint8_t)((signbit(t) ? 8 : 0) | idx);
+}
+
+static float e2m1_decode(uint8_t code)
+{
+    const float v = e2m1_magnitude(code & 7);
+    return (code & 8) ? -v : v;
+}
+
+static uint8_t e4m3_encode(float t)
+{
+    const int idx = nearest_index(fabsf(t), 127, e4m3_magnitude);
+    return (uint8_t)((signbit(t) ? 0x80 : 0) | idx);
+}
+
+static float e4m3_decode(uint8_t code)
+{
+    const float v = e4m3_magnitude(code & 0x7F); /* 0x7F itself (NaN) is never produced */
+    return (code & 0x80) ? -v : v;
+}
+
+uint8_t agoq_ref_e2m1_encode(float t) { return e2m1_encode(t); }
+float agoq_ref_e2m1_decode(uint8_t c) { return e2m1_decode(c); }
+uint8_t agoq_ref_e4m3_encode(float t) { return e4m3_encode(t); }
+float agoq_ref_e4m3_decode(uint8_t c) { return e4m3_decode(c); }
+
+/* scale, inv of a group for a code book with largest magnitude vmax; returns 0 for a dead group */
+static int fp_group_scale(const float *x, int G, float vmax, float *scale, float *inv)
+{
+    float amax = 0.0f;
+    for (int j = 0; j < G; ++j) {
+        const float mag = fabsf(x[j]);
+        if (mag > amax)
+            amax = mag;
+    }
+    if (amax < REF_AMAX_MIN) {
+        *scale = 0.0f;
+        *inv = 0.0f;
+        return 0;
+    }
+    *scale = amax / vmax;
+    *inv = vmax / amax;
+    return 1;
+}
+
+/* activations: bf16 -> E2M1 codes (nibbles, even element low) + fp32 scales */
+int agoq_ref_fp4_act_quant(const uint16_t *x, int64_t numel, int group, uint8_t *codes,
+                           float *scales)
+{
+    if (!x || !codes || !scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 4);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float xf[4096];
+        for (int j = 0; j < group; ++j)
+            xf[j] = bf16_bits_to_f32(x[g * group + j]);
+        float scale, inv;
+        const int live = fp_group_scale(xf, group, 6.0f, &scale, &inv);
+        scales[g] = scale;
+        for (int j = 0; j < group; j += 2) {
+            const uint8_t lo = live ? e2m1_encode(xf[j] * inv) : 0;
+            const uint8_t hi = live ? e2m1_encode(xf[j + 1] * inv) : 0;
+            codes[(g * group + j) / 2] = (uint8_t)(lo | (hi << 4));
+        }
+    }
+    return REF_OK;
+}
+
+int agoq_ref_fp4_act_dequant(const uint8_t *codes, const float *scales, int64_t numel, int group,
+                             uint16_t *y)
+{
+    if (!codes || !scales || !y)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 4);
+    if (rc)
+        return rc;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < numel; ++e) {
+        const uint8_t byte = codes[e / 2];
+        const uint8_t code = (e % 2 == 0) ? (byte & 0xF) : (uint8_t)(byte >> 4);
+        y[e] = f32_to_bf16_bits(e2m1_decode(code) * scales[e / group]);
+    }
+    return REF_OK;
+}
+
+/* gradients: fp32 -> E4M3 codes (one byte each) + fp32 scales */
+int agoq_ref_fp8_grad_quant(const float *grad, int64_t numel, int group, uint8_t *codes,
+                            float *scales)
+{
+    if (!grad || !codes || !scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float scale, inv;
+        const int live = fp_group_scale(grad + g * group, group, 448.0f, &scale, &inv);
+        scales[g] = scale;
+        for (int j = 0; j < group; ++j)
+            codes[g * group + j] = live ? e4m3_encode(grad[g * group + j] * inv) : 0;
+    }
+    return REF_OK;
+}
+
+int agoq_ref_fp8_grad_dequant(const uint8_t *codes, const float *scales, int64_t numel, int group,
+                              float *out)
+{
+    if (!codes || !scales || !out)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < numel; ++e)
+        out[e] = e4m3_decode(codes[e]) * scales[e / group];
+    return REF_OK;
+}
+
+/* local step of the All-Reduce on E4M3 chunks: fp32 fma chain in chunk order, requantize */
+int agoq_ref_fp8_grad_reduce_requant(const uint8_t *in_codes, int64_t stride_codes,
+                                     const float *in_scales, int64_t stride_scales, int K,
+                                     int64_t numel, int group, uint8_t *out_codes,
+                                     float *out_scales)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    if (K < 1 || K > 64)
+        return REF_ERR_K;
+    const int64_t n_groups = numel / group;
+    if (stride_codes < numel || stride_scales < n_groups)
+        return REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float acc[4096];
+        for (int j = 0; j < group; ++j) {
+            const int64_t e = g * group + j;
+            float a = 0.0f;
+            for (int k = 0; k < K; ++k) {
+                const float v = e4m3_decode(in_codes[k * stride_codes + e]);
+                a = fmaf(v, in_scales[k * stride_scales + g], a);
+            }
+            acc[j] = a;
+        }
+        float scale, inv;
+        const int live = fp_group_scale(acc, group, 448.0f, &scale, &inv);
+        out_scales[g] = scale;
+        for (int j = 0; j < group; ++j)
+            out_codes[g * group + j] = live ? e4m3_encode(acc[j] * inv) : 0;
+    }
+    return REF_OK;
+}
+
 /* ---- Dynamic Bit-width Compensation (Eq. "dynamic") --------------------- */
 
 /*

@@ -12,7 +12,8 @@ import numpy as np
 from . import build as _build
 
 __all__ = [
-    "lib", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
+    "lib", "fp4_act_quant", "fp4_act_dequant", "fp8_grad_quant", "fp8_grad_dequant",
+    "fp8_grad_reduce_requant", "e2m1_encode", "e2m1_decode", "e4m3_encode", "e4m3_decode", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
     "grad_reduce_requant", "grad_reduce_f64", "grad_accumulate", "dbca_bits",
     "dbca_stored_microbatches", "bf16_to_f32", "f32_to_bf16", "max_threads",
     "set_threads", "OracleError", "Oracle",
@@ -40,6 +41,18 @@ def _bind(path):
     L.agoq_ref_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P]
     L.agoq_ref_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _INT, _P, ctypes.c_float, _P, _P]
     L.agoq_ref_act_dequant_silu_mul.argtypes = [_P, _P, _INT, _P, _P, _INT, _I64, _INT, _P]
+    L.agoq_ref_fp4_act_quant.argtypes = [_P, _I64, _INT, _P, _P]
+    L.agoq_ref_fp4_act_dequant.argtypes = [_P, _P, _I64, _INT, _P]
+    L.agoq_ref_fp8_grad_quant.argtypes = [_P, _I64, _INT, _P, _P]
+    L.agoq_ref_fp8_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P]
+    L.agoq_ref_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P]
+    for name in ("e2m1", "e4m3"):
+        enc = getattr(L, "agoq_ref_%s_encode" % name)
+        enc.argtypes = [ctypes.c_float]
+        enc.restype = ctypes.c_uint8
+        dec = getattr(L, "agoq_ref_%s_decode" % name)
+        dec.argtypes = [ctypes.c_uint8]
+        dec.restype = ctypes.c_float
     L.agoq_ref_dbca_bits.argtypes = [_INT, _INT, ctypes.POINTER(_INT)]
     L.agoq_ref_dbca_stored_microbatches.argtypes = [_INT, _INT]
     L.agoq_ref_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -129,6 +142,61 @@ class Oracle:
             up_bits, numel, group, _ptr(z)))
         return z
 
+    # ---- floating-point code books (E2M1 activations, E4M3 gradients) ----
+
+    def fp4_act_quant(self, x_bf16_bits, group):
+        x = _c(x_bf16_bits, np.uint16).reshape(-1)
+        codes = np.zeros(x.size // 2, np.uint8)
+        scales = np.zeros(x.size // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_fp4_act_quant(_ptr(x), x.size, group, _ptr(codes), _ptr(scales)))
+        return codes, scales
+
+    def fp4_act_dequant(self, codes, scales, numel, group):
+        codes = _c(codes, np.uint8).reshape(-1)
+        scales = _c(scales, np.float32).reshape(-1)
+        y = np.zeros(numel, np.uint16)
+        _check(self.lib.agoq_ref_fp4_act_dequant(_ptr(codes), _ptr(scales), numel, group, _ptr(y)))
+        return y
+
+    def fp8_grad_quant(self, g, group):
+        g = _c(g, np.float32).reshape(-1)
+        codes = np.zeros(g.size, np.uint8)
+        scales = np.zeros(g.size // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_fp8_grad_quant(_ptr(g), g.size, group, _ptr(codes), _ptr(scales)))
+        return codes, scales
+
+    def fp8_grad_dequant(self, codes, scales, group):
+        codes = _c(codes, np.uint8).reshape(-1)
+        scales = _c(scales, np.float32).reshape(-1)
+        out = np.zeros(codes.size, np.float32)
+        _check(self.lib.agoq_ref_fp8_grad_dequant(_ptr(codes), _ptr(scales), codes.size, group, _ptr(out)))
+        return out
+
+    def fp8_grad_reduce_requant(self, in_codes, in_scales, numel, group):
+        in_codes = _c(in_codes, np.uint8)
+        in_scales = _c(in_scales, np.float32)
+        if in_codes.ndim != 2 or in_scales.ndim != 2 or in_codes.shape[0] != in_scales.shape[0]:
+            raise ValueError("expected codes [K, stride_c] and scales [K, stride_s]")
+        K = in_codes.shape[0]
+        out_codes = np.zeros(numel, np.uint8)
+        out_scales = np.zeros(numel // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_fp8_grad_reduce_requant(
+            _ptr(in_codes), in_codes.shape[1], _ptr(in_scales), in_scales.shape[1], K, numel,
+            group, _ptr(out_codes), _ptr(out_scales)))
+        return out_codes, out_scales
+
+    def e2m1_encode(self, t):
+        return self.lib.agoq_ref_e2m1_encode(float(t))
+
+    def e2m1_decode(self, c):
+        return self.lib.agoq_ref_e2m1_decode(int(c))
+
+    def e4m3_encode(self, t):
+        return self.lib.agoq_ref_e4m3_encode(float(t))
+
+    def e4m3_decode(self, c):
+        return self.lib.agoq_ref_e4m3_decode(int(c))
+
     def grad_quant(self, g, group):
         g = _c(g, np.float32).reshape(-1)
         codes = np.zeros(g.size, np.int8)
@@ -212,6 +280,15 @@ act_dequant = _default.act_dequant
 act_dequant_rmsnorm = _default.act_dequant_rmsnorm
 act_dequant_silu_mul = _default.act_dequant_silu_mul
 grad_quant = _default.grad_quant
+fp4_act_quant = _default.fp4_act_quant
+fp4_act_dequant = _default.fp4_act_dequant
+fp8_grad_quant = _default.fp8_grad_quant
+fp8_grad_dequant = _default.fp8_grad_dequant
+fp8_grad_reduce_requant = _default.fp8_grad_reduce_requant
+e2m1_encode = _default.e2m1_encode
+e2m1_decode = _default.e2m1_decode
+e4m3_encode = _default.e4m3_encode
+e4m3_decode = _default.e4m3_decode
 grad_dequant = _default.grad_dequant
 grad_reduce_requant = _default.grad_reduce_requant
 grad_reduce_f64 = _default.grad_reduce_f64

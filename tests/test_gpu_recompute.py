@@ -1,7 +1,9 @@
 """GPU parity for dequantize fused with the Case-1 recompute (RMSNorm, SiLU & Multiply).
 
-The oracle is the plain binary64 definition; the kernels compute in binary32.  Bar
-(derived in the design doc): the bf16 outputs are equal, or one bf16 step apart where the exact
+The oracle is the plain binary64 definition; the kernels compute in binary32, whose result
+before the final rounding is within ~1e-5 relative of the exact one (cols * 2^-24 for the sum
+of squares at worst, a few 1e-6 for exp), far below bf16's half step of 2^-9.  Bar: the bf16
+outputs are equal, or one bf16 step apart where the exact
 value sits within ~1e-5 relative of a rounding boundary (at most 0.5 % of the elements);
 values whose exact magnitude is below 2^-100 (SiLU of a gate below about -70) only need to
 come out below 2^-100 as well; r agrees to 2e-6 relative.

@@ -10,6 +10,7 @@ import pytest
 import test_oracle_quant_pins as quant_pins
 import test_oracle_reduce_pins as reduce_pins
 import test_oracle_recompute_pins as recompute_pins
+import test_oracle_fp_pins as fp_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "agoq_ref.c")
@@ -60,6 +61,27 @@ MUTANTS = [
      "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(g))));"),
     ("silu_applied_to_up", "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-g))));",
      "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-u))));"),
+    ("fp_absmax_without_abs", "const float mag = fabsf(x[j]);", "const float mag = x[j];"),
+    ("fp_ties_to_odd", "if (d < best_d || (d == best_d && (i % 2 == 0))) {",
+     "if (d < best_d || (d == best_d && (i % 2 == 1))) {"),
+    ("fp_ties_keep_lower", "if (d < best_d || (d == best_d && (i % 2 == 0))) {", "if (d < best_d) {"),
+    ("e2m1_subnormal_step", "return 0.5f * (float)m;", "return 0.25f * (float)m;"),
+    ("e2m1_exponent_bias", "return ldexpf(1.0f + 0.5f * (float)m, e - 1);", "return ldexpf(1.0f + 0.5f * (float)m, e);"),
+    ("e4m3_exponent_bias", "return ldexpf(1.0f + (float)m / 8.0f, e - 7);", "return ldexpf(1.0f + (float)m / 8.0f, e - 8);"),
+    ("e4m3_subnormal_scale", "return ldexpf((float)m, -9);", "return ldexpf((float)m, -10);"),
+    ("fp_sign_dropped", "return (uint8_t)((signbit(t) ? 8 : 0) | idx);", "return (uint8_t)idx;"),
+    ("fp8_sign_from_comparison", "return (uint8_t)((signbit(t) ? 0x80 : 0) | idx);",
+     "return (uint8_t)((t < 0.0f ? 0x80 : 0) | idx);"),
+    ("fp4_vmax_is_8", "const int live = fp_group_scale(xf, group, 6.0f, &scale, &inv);",
+     "const int live = fp_group_scale(xf, group, 8.0f, &scale, &inv);"),
+    ("fp4_dead_group_keeps_signs", "const uint8_t lo = live ? e2m1_encode(xf[j] * inv) : 0;",
+     "const uint8_t lo = e2m1_encode(xf[j] * inv);"),
+    ("fp4_nibbles_swapped", "codes[(g * group + j) / 2] = (uint8_t)(lo | (hi << 4));",
+     "codes[(g * group + j) / 2] = (uint8_t)(hi | (lo << 4));"),
+    ("fp8_reduce_two_roundings", "a = fmaf(v, in_scales[k * stride_scales + g], a);",
+     "a = a + v * in_scales[k * stride_scales + g];"),
+    ("fp8_reduce_ignores_stride", "const float v = e4m3_decode(in_codes[k * stride_codes + e]);",
+     "const float v = e4m3_decode(in_codes[k * numel + e]);"),
     ("dbca_printed_index", "return 3 * n_stages - 2 * stage + 1;", "return n_stages + 2 * stage - 1;"),
     ("dbca_floor_instead_of_round", "int r = (int)floor(b + 0.5);", "int r = (int)floor(b);"),
     ("dbca_no_cap", "if (r > 8)\n        r = 8;", ""),
@@ -71,7 +93,7 @@ MUTANTS = [
 def pin_tests():
     """Every pin test of the two pin modules, expanded over its parametrisation."""
     cases = []
-    for mod in (quant_pins, reduce_pins, recompute_pins):
+    for mod in (quant_pins, reduce_pins, recompute_pins, fp_pins):
         for name, fn in inspect.getmembers(mod, inspect.isfunction):
             if not name.startswith("test_") or "ref" not in inspect.signature(fn).parameters:
                 continue
