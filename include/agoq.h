@@ -169,6 +169,34 @@ int agoq_grad_accumulate(const int8_t *main_codes, const float *main_scales, con
 int agoq_grad_dequant(const int8_t *codes, const float *scales, int64_t numel, int group,
                       float *out, void *stream);
 
+/* ---- the same path with floating-point code books ------------------------
+ *
+ * The paper words its formats as "block-wise FP4 quantization" (activations) and "FP8"
+ * (gradients).  These entry points are the calls above with the integer grid replaced by
+ * a floating-point code book, everything else unchanged (groups, fp32 scales, layouts,
+ * error codes, the 2^-100 rule, fixed summation order):
+ *     scale = amax / vmax,  inv = vmax / amax,  code = nearest(x * inv)
+ *   FP4 = E2M1 (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6; vmax = 6), one nibble per element,
+ *         sign in bit 3, even element in bits 0-3 of the byte;
+ *   FP8 = OCP E4M3 (no infinities; vmax = 448), one byte per element, sign in bit 7.
+ * nearest = round to the nearest representable value, ties to the even mantissa; the
+ * code's sign bit is the sign bit of x * inv (negative values that round to zero give
+ * -0), except that a group stored as zeros has all-zero codes.  The NaN code of E4M3 is
+ * never produced; on input it decodes as NaN.
+ */
+int agoq_fp4_act_quant(const void *x_bf16, int64_t numel, int group, void *codes, float *scales,
+                       void *stream);
+int agoq_fp4_act_dequant(const void *codes, const float *scales, int64_t numel, int group,
+                         void *y_bf16, void *stream);
+int agoq_fp8_grad_quant(const float *grad, int64_t numel, int group, uint8_t *codes, float *scales,
+                        void *stream);
+int agoq_fp8_grad_dequant(const uint8_t *codes, const float *scales, int64_t numel, int group,
+                          float *out, void *stream);
+int agoq_fp8_grad_reduce_requant(const uint8_t *in_codes, int64_t chunk_stride_codes,
+                                 const float *in_scales, int64_t chunk_stride_scales, int K,
+                                 int64_t numel, int group, uint8_t *out_codes, float *out_scales,
+                                 void *stream);
+
 /* ---- host-only helpers: pure functions, no device access ---------------- */
 
 /* Bytes of packed codes for numel elements at `bits` per element; -1 if bits is unsupported. */

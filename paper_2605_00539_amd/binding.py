@@ -43,6 +43,11 @@ def load_library():
     L.agoq_act_dequant_silu_mul.argtypes = [_P, _P, _INT, _P, _P, _INT, _I64, _INT, _P, _P]
     L.agoq_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
+    L.agoq_fp4_act_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
+    L.agoq_fp4_act_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
+    L.agoq_fp8_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
+    L.agoq_fp8_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
+    L.agoq_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_codes_bytes.argtypes = [_I64, _INT]
     L.agoq_codes_bytes.restype = _I64
     L.agoq_num_groups.argtypes = [_I64, _INT]
@@ -276,6 +281,95 @@ def grad_dequant(codes, scales, group, out=None, stream=None):
         _check(L.agoq_grad_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), n, group,
                                    _raw(out.data_ptr()), _stream(stream)))
     return out
+
+
+# ---- floating-point code books (E2M1 activations, E4M3 gradients) -----------------
+
+def fp4_act_quant(x, group, codes=None, scales=None, stream=None):
+    import torch
+    L = load_library()
+    x = _dev(x, torch.bfloat16, "x")
+    n = x.numel()
+    if codes is None:
+        codes = torch.empty(max(n // 2, 1), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    with _on_device(x.device):
+        _check(L.agoq_fp4_act_quant(_raw(x.data_ptr()), n, group, _raw(codes.data_ptr()),
+                                    _raw(scales.data_ptr()), _stream(stream)))
+    return codes, scales
+
+
+def fp4_act_dequant(codes, scales, numel, group, out=None, stream=None):
+    import torch
+    L = load_library()
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    if out is None:
+        out = torch.empty(numel, dtype=torch.bfloat16, device=codes.device)
+    _dev(out, torch.bfloat16, "out")
+    with _on_device(codes.device):
+        _check(L.agoq_fp4_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
+                                      _raw(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def fp8_grad_quant(grad, group, codes=None, scales=None, stream=None):
+    import torch
+    L = load_library()
+    grad = _dev(grad, torch.float32, "grad")
+    n = grad.numel()
+    if codes is None:
+        codes = torch.empty(max(n, 1), dtype=torch.uint8, device=grad.device)
+    if scales is None:
+        scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=grad.device)
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    with _on_device(grad.device):
+        _check(L.agoq_fp8_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
+                                     _raw(scales.data_ptr()), _stream(stream)))
+    return codes, scales
+
+
+def fp8_grad_dequant(codes, scales, group, out=None, stream=None):
+    import torch
+    L = load_library()
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float32, "scales")
+    n = codes.numel()
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)
+    _dev(out, torch.float32, "out")
+    with _on_device(codes.device):
+        _check(L.agoq_fp8_grad_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), n, group,
+                                       _raw(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def fp8_grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_scales=None,
+                            stream=None):
+    import torch
+    L = load_library()
+    _dev(in_codes, torch.uint8, "in_codes")
+    _dev(in_scales, torch.float32, "in_scales")
+    if in_codes.dim() != 2 or in_scales.dim() != 2 or in_codes.shape[0] != in_scales.shape[0]:
+        raise ValueError("expected in_codes [K, stride_c] and in_scales [K, stride_s]")
+    K = in_codes.shape[0]
+    if out_codes is None:
+        out_codes = torch.empty(max(numel, 1), dtype=torch.uint8, device=in_codes.device)
+    if out_scales is None:
+        out_scales = torch.empty(max(numel // max(group, 1), 1), dtype=torch.float32,
+                                 device=in_codes.device)
+    _dev(out_codes, torch.uint8, "out_codes")
+    _dev(out_scales, torch.float32, "out_scales")
+    with _on_device(in_codes.device):
+        _check(L.agoq_fp8_grad_reduce_requant(
+            _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
+            in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),
+            _raw(out_scales.data_ptr()), _stream(stream)))
+    return out_codes, out_scales
 
 
 # ---- host helpers ---------------------------------------------------------------

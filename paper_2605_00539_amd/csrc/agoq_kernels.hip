@@ -180,6 +180,69 @@ __device__ __forceinline__ float byte_to_f32(u32 w, int j)
     return (float)(int8_t)((w >> (8 * j)) & 0xFFu);
 }
 
+// ---- floating-point code books (E2M1 nibbles, OCP E4M3 bytes) ----------------------
+// gfx950's conversion instructions round to nearest, ties to the even mantissa, saturate
+// at the largest magnitude and keep the sign of a zero -- the semantics of the code books
+// here.  fp4 conversions take a power-of-two scale operand; it is always 1.
+
+// Four fp32 values times inv -> one word of 8-bit codes, element 0 in the low byte.
+template <bool FP>
+__device__ __forceinline__ u32 encode4_bytes(float x0, float x1, float x2, float x3, float inv)
+{
+    if (FP) {
+        int w = 0;
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(__fmul_rn(x0, inv), __fmul_rn(x1, inv), w, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(__fmul_rn(x2, inv), __fmul_rn(x3, inv), w, true);
+        return (u32)w;
+    }
+    u32 w = 0;
+    w = push_byte(w, code_bits(x0, inv));
+    w = push_byte(w, code_bits(x1, inv));
+    w = push_byte(w, code_bits(x2, inv));
+    w = push_byte(w, code_bits(x3, inv));
+    return w;
+}
+
+// The four 8-bit codes of a word as fp32 values.
+template <bool FP>
+__device__ __forceinline__ void decode4_bytes(u32 w, float (&q)[4])
+{
+    if (FP) {
+        q[0] = __builtin_amdgcn_cvt_f32_fp8((int)w, 0);
+        q[1] = __builtin_amdgcn_cvt_f32_fp8((int)w, 1);
+        q[2] = __builtin_amdgcn_cvt_f32_fp8((int)w, 2);
+        q[3] = __builtin_amdgcn_cvt_f32_fp8((int)w, 3);
+    } else {
+        q[0] = byte_to_f32(w, 0);
+        q[1] = byte_to_f32(w, 1);
+        q[2] = byte_to_f32(w, 2);
+        q[3] = byte_to_f32(w, 3);
+    }
+}
+
+// Eight fp32 values times inv -> one word of E2M1 nibbles, element 0 in bits 0-3.
+__device__ __forceinline__ u32 encode8_e2m1(const float (&f)[8], float inv)
+{
+    u32 p = 0;
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[0], inv), __fmul_rn(f[1], inv), 1.0f, 0);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[2], inv), __fmul_rn(f[3], inv), 1.0f, 1);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[4], inv), __fmul_rn(f[5], inv), 1.0f, 2);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[6], inv), __fmul_rn(f[7], inv), 1.0f, 3);
+    return p;
+}
+
+// The eight E2M1 nibbles of a word as fp32 values.
+__device__ __forceinline__ void decode8_e2m1(u32 w, float (&q)[8])
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 0);
+    const f32x2 b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 1);
+    const f32x2 c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 2);
+    const f32x2 d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 3);
+    q[0] = a[0]; q[1] = a[1]; q[2] = b[0]; q[3] = b[1];
+    q[4] = c[0]; q[5] = c[1]; q[6] = d[0]; q[7] = d[1];
+}
+
 __device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -196,13 +259,14 @@ __device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
 // the low nibbles exactly where 4-bit codes would go, the remaining high bits
 // (one byte or two bytes per lane) to a second plane that starts n_vec*4 bytes in.
 // ---------------------------------------------------------------------------
-template <int BITS, int GROUP, int UNROLL>
+template <int BITS, int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
                                                            int64_t n_vec, void* __restrict__ codes,
                                                            float* __restrict__ scales)
 {
+    static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
     constexpr int LANES = GROUP / 8;
-    constexpr int QMAX = (1 << (BITS - 1)) - 1;
+    constexpr int QMAX = FP ? 6 : (1 << (BITS - 1)) - 1;   // largest code magnitude
     constexpr int kBlock = AGOQ_AQ_BLOCK;
     constexpr bool NTL = AGOQ_AQ_NTL, NTS = AGOQ_AQ_NTS;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
@@ -230,7 +294,10 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
         float scale, inv;
         scale_and_inv<QMAX>(m, scale, inv);
         if (vi < n_vec) {
-            if (BITS == 4) {
+            if (FP) {
+                const u32 p = encode8_e2m1(f, inv);
+                st<NTS>((u32*)codes + vi, scale != 0.0f ? p : 0u);   // dead group: no signed zeros
+            } else if (BITS == 4) {
                 u32 p = 0;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
@@ -266,7 +333,7 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
 // Activation dequantize: codes + scales -> bf16.  One lane produces 8 elements
 // (one 16-byte store).
 // ---------------------------------------------------------------------------
-template <int BITS, int GROUP, int UNROLL>
+template <int BITS, int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
                                                              const float* __restrict__ scales,
                                                              int64_t n_vec, u32x4* __restrict__ y)
@@ -299,10 +366,14 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         float f[8];
+        float fpq[8];
+        if (FP) decode8_e2m1(c[u][0], fpq);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             float q;
-            if (BITS == 4) {
+            if (FP) {
+                q = fpq[j];
+            } else if (BITS == 4) {
                 q = (float)(int)__builtin_amdgcn_sbfe((int)c[u][0], 4 * j, 4);  // the builtin returns unsigned
             } else if (BITS == 8) {
                 q = byte_to_f32(c[u][j >> 2], j & 3);
@@ -326,7 +397,7 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
 // vector p of lane l being elements [p*64 + 4l, p*64 + 4l + 4) of the group, so
 // each load instruction reads whole 256-byte runs.
 // ---------------------------------------------------------------------------
-template <int GROUP, int UNROLL>
+template <int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* __restrict__ g,
                                                             int64_t n_groups,
                                                             u32* __restrict__ codes,
@@ -359,13 +430,12 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* 
             for (int j = 0; j < 4; ++j) m = umax(m, as_u32(v[u][p][j]) & 0x7FFFFFFFu);
         m = group_max_bits<16>(m);
         float scale, inv;
-        scale_and_inv<127>(m, scale, inv);
+        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (grp < n_groups) {
 #pragma unroll
             for (int p = 0; p < VPL; ++p) {
-                u32 w = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) w = push_byte(w, code_bits(v[u][p][j], inv));
+                u32 w = encode4_bytes<FP>(v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3], inv);
+                if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
                 st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
             }
             if (lane16 == 0) st<NTS>(scales + grp, scale);
@@ -379,7 +449,7 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* 
 // a group.  acc = fma(code_k, scale_k, acc) for k = 0..K-1 in that order.
 // KT > 0: K known at compile time (all loads hoisted); KT == 0: run-time K.
 // ---------------------------------------------------------------------------
-template <int GROUP>
+template <int GROUP, bool FP = false>
 __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi,
                                               bool valid, u32x4* __restrict__ out_codes,
                                               float* __restrict__ out_scales)
@@ -390,30 +460,31 @@ __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi
     for (int j = 0; j < 16; ++j) m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
     m = group_max_bits<LANES>(m);
     float scale, inv;
-    scale_and_inv<127>(m, scale, inv);
+    scale_and_inv<FP ? 448 : 127>(m, scale, inv);
     if (valid) {
         u32x4 w = {0, 0, 0, 0};
 #pragma unroll
         for (int d = 0; d < 4; ++d)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) w[d] = push_byte(w[d], code_bits(acc[4 * d + j], inv));
+            w[d] = encode4_bytes<FP>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv);
+        if (FP && scale == 0.0f) w = u32x4{0, 0, 0, 0};       // dead group: no signed zeros
         st<AGOQ_RD_NTS>(out_codes + vi, w);
         if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS>(out_scales + vi / LANES, scale);
     }
 }
 
+template <bool FP = false>
 __device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, float s)
 {
 #pragma unroll
-    for (int d = 0; d < 4; ++d)
+    for (int d = 0; d < 4; ++d) {
+        float q[4];
+        decode4_bytes<FP>(c[d], q);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float q = byte_to_f32(c[d], j);
-            acc[4 * d + j] = __fmaf_rn(q, s, acc[4 * d + j]);
-        }
+        for (int j = 0; j < 4; ++j) acc[4 * d + j] = __fmaf_rn(q[j], s, acc[4 * d + j]);
+    }
 }
 
-template <int GROUP, int KT>
+template <int GROUP, int KT, bool FP = false>
 __global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
                                                              int64_t stride_codes,
                                                              const float* __restrict__ in_scales,
@@ -442,7 +513,7 @@ __global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t
             s[k] = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
         }
 #pragma unroll
-        for (int k = 0; k < KT; ++k) reduce_term(acc, c[k], s[k]);
+        for (int k = 0; k < KT; ++k) reduce_term<FP>(acc, c[k], s[k]);
     } else {
         int k = 0;
         for (; k + 4 <= K; k += 4) {
@@ -454,15 +525,15 @@ __global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t
                 s[t] = ld<NTSC>(in_scales + (int64_t)(k + t) * stride_scales + grp);
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) reduce_term(acc, c[t], s[t]);
+            for (int t = 0; t < 4; ++t) reduce_term<FP>(acc, c[t], s[t]);
         }
         for (; k < K; ++k) {
             const u32x4 c = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
             const float s = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
-            reduce_term(acc, c, s);
+            reduce_term<FP>(acc, c, s);
         }
     }
-    reduce_finish<GROUP>(acc, vi, valid, out_codes, out_scales);
+    reduce_finish<GROUP, FP>(acc, vi, valid, out_codes, out_scales);
 }
 
 // ---------------------------------------------------------------------------
@@ -586,7 +657,7 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
 // Gradient dequantize: int8 codes + scales -> fp32 (what an optimizer step reads).
 // One lane: 4 codes (one dword) -> one 16-byte store.
 // ---------------------------------------------------------------------------
-template <int GROUP, int UNROLL>
+template <int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* __restrict__ codes,
                                                                      const float* __restrict__ scales,
                                                                      int64_t n_vec,
@@ -611,8 +682,10 @@ __global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* 
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         f32x4 o;
+        float q[4];
+        decode4_bytes<FP>(c[u], q);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(byte_to_f32(c[u], j), s[u]);
+        for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(q[j], s[u]);
         if (vi < n_vec) st<AGOQ_GD_NTS>(out + vi, o);
     }
 }
@@ -1186,6 +1259,121 @@ int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, 
     }
 #undef AGOQ_SILU_UP
 #undef AGOQ_LAUNCH_SILU
+    return launch_status();
+}
+
+// ---- floating-point code books ---------------------------------------------------------
+
+int agoq_fp4_act_quant(const void* x_bf16, int64_t numel, int group, void* codes, float* scales,
+                       void* stream)
+{
+    if (!x_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    constexpr int U = AGOQ_AQ_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4* x = (const u32x4*)x_bf16;
+    if (group == 128)
+        act_quant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    else
+        act_quant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    return launch_status();
+}
+
+int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, int group,
+                         void* y_bf16, void* stream)
+{
+    if (!codes || !scales || !y_bf16) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    constexpr int U = 4;
+    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * U)), block(AGOQ_DQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* y = (u32x4*)y_bf16;
+    if (group == 128)
+        act_dequant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else
+        act_dequant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    return launch_status();
+}
+
+int agoq_fp8_grad_quant(const float* grad, int64_t numel, int group, uint8_t* codes, float* scales,
+                        void* stream)
+{
+    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_groups = numel / group;
+    constexpr int U = AGOQ_GQ_UNROLL;
+    const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_quant_kernel<128, U, true><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
+                                                                (u32*)codes, scales);
+    else
+        grad_quant_kernel<64, U, true><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
+                                                               (u32*)codes, scales);
+    return launch_status();
+}
+
+int agoq_fp8_grad_dequant(const uint8_t* codes, const float* scales, int64_t numel, int group,
+                          float* out, void* stream)
+{
+    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 4;
+    constexpr int U = AGOQ_GD_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_dequant_kernel<128, U, true><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                                  (f32x4*)out);
+    else
+        grad_dequant_kernel<64, U, true><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                                 (f32x4*)out);
+    return launch_status();
+}
+
+int agoq_fp8_grad_reduce_requant(const uint8_t* in_codes, int64_t chunk_stride_codes,
+                                 const float* in_scales, int64_t chunk_stride_scales, int K,
+                                 int64_t numel, int group, uint8_t* out_codes, float* out_scales,
+                                 void* stream)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (K < 1 || K > 64) return AGOQ_ERR_K;
+    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
+    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
+        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
+        return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 16;
+    const dim3 grid(blocks_for(n_vec, AGOQ_RD_BLOCK)), block(AGOQ_RD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* oc = (u32x4*)out_codes;
+    const int8_t* ic = (const int8_t*)in_codes;
+#define AGOQ_LAUNCH_REDUCE_FP(G, KT)                                                           \
+    grad_reduce_kernel<G, KT, true><<<grid, block, 0, st>>>(ic, chunk_stride_codes, in_scales, \
+                                                            chunk_stride_scales, K, n_vec, oc, out_scales)
+    if (group == 128) {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE_FP(128, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE_FP(128, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE_FP(128, 16); break;
+        default: AGOQ_LAUNCH_REDUCE_FP(128, 0); break;
+        }
+    } else {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE_FP(64, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE_FP(64, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE_FP(64, 16); break;
+        default: AGOQ_LAUNCH_REDUCE_FP(64, 0); break;
+        }
+    }
+#undef AGOQ_LAUNCH_REDUCE_FP
     return launch_status();
 }
 

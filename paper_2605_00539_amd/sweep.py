@@ -80,7 +80,7 @@ def main():
         print("%-14s %-22s %-34s %10.2f us %10.1f MB %9.1f GB/s %6.1f%%" %
               (config, kernel, case, us, nbytes / 1e6, gbps, 100 * gbps / PEAK), flush=True)
 
-    def act_case(config, label, rows_, cols, dist, frac, scale, seed, group_list, bits_list, fused=False):
+    def act_case(config, label, rows_, cols, dist, frac, scale, seed, group_list, bits_list, fused=False, fp=False):
         n = rows_ * cols
         nx = slots_for(2 * n)
         base = wl.act_device(rows_, cols, seed, dist, wl.n_outlier_channels(cols, frac), scale).reshape(-1)
@@ -107,6 +107,17 @@ def main():
                 report(config, "act_quant", case, us, nb)
                 us = timed(lambda i: L.agoq_act_dequant(*da[i % len(da)]), args.launches, args.reps)
                 report(config, "act_dequant", case, us, nb)
+                if fp and bits == 4:
+                    us = timed(lambda i: L.agoq_fp4_act_quant(qa[i % len(qa)][0], n, group, qa[i % len(qa)][4],
+                                                              qa[i % len(qa)][5], st), args.launches, args.reps)
+                    report(config, "fp4_act_quant", case.replace(" b4 ", " e2m1 "), us, nb)
+                    us = timed(lambda i: L.agoq_fp4_act_dequant(da[i % len(da)][0], da[i % len(da)][1], n, group,
+                                                                da[i % len(da)][5], st), args.launches, args.reps)
+                    report(config, "fp4_act_dequant", case.replace(" b4 ", " e2m1 "), us, nb)
+                    # leave int4 codes behind for the cases that follow
+                    for i in range(nc):
+                        agoq.act_quant(xs[i % nx], group, bits, codes=cs[i], scales=ss[i])
+                    torch.cuda.synchronize()
                 if fused and cols <= 16384:
                     # dequantize fused with the RMSNorm recompute (same bytes as a plain dequantize)
                     gamma = torch.ones(cols, dtype=torch.float32, device=dev)
@@ -125,7 +136,7 @@ def main():
                 del cs, ss
         del xs, ys, base
 
-    def grad_case(config, n, sigma, spike_frac, spike_scale, seed, K, group, share=True):
+    def grad_case(config, n, sigma, spike_frac, spike_scale, seed, K, group, share=True, fp8=False):
         g = [wl.grad_device(n, seed + i, sigma, spike_frac, spike_scale) for i in range(2 if n > (1 << 26) else 8)]
         nout = slots_for(n, floor=3)
         ocs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nout)]
@@ -159,6 +170,25 @@ def main():
                        launches, args.reps)
             report(config, "grad_dequant", "n=%d g%d" % (n, group), us, n * 5 + 4 * (n // group))
             del mcs, mss, fo
+        if fp8:
+            ucs = [t.view(torch.uint8) for t in ocs]
+            us = timed(lambda i: agoq.fp8_grad_quant(g[i % len(g)], group, codes=ucs[i % nout],
+                                                     scales=oss[i % nout]), launches, args.reps)
+            report(config, "fp8_grad_quant", "n=%d g%d" % (n, group), us, algo_gq(n, group))
+            fcodes = torch.empty((K, n), dtype=torch.uint8, device=dev)
+            fscales = torch.empty((K, n // group), dtype=torch.float32, device=dev)
+            for k in range(K):
+                gk = wl.grad_device(n, seed + 300 + k, sigma, spike_frac, spike_scale)
+                agoq.fp8_grad_quant(gk, group, codes=fcodes[k], scales=fscales[k])
+                torch.cuda.synchronize()
+                del gk
+            us = timed(lambda i: agoq.fp8_grad_reduce_requant(fcodes, fscales, n, group, out_codes=ucs[i % nout],
+                                                              out_scales=oss[i % nout]), launches, args.reps)
+            report(config, "fp8_grad_reduce_requant", "K=%d n=%d g%d" % (K, n, group), us, algo_red(n, K, group))
+            fo = torch.empty(n, dtype=torch.float32, device=dev)
+            us = timed(lambda i: agoq.fp8_grad_dequant(fcodes[i % K], fscales[i % K], group, out=fo), launches, args.reps)
+            report(config, "fp8_grad_dequant", "n=%d g%d" % (n, group), us, algo_gq(n, group))
+            del fcodes, fscales, fo
         nin = 1 if K * n > GiB else -(-GiB // (K * n)) + 1
         ins = []
         for s in range(nin):
@@ -207,10 +237,11 @@ def main():
     c = C["llama8b_act"]
     for name, sh in c["acts"].items():
         act_case("2-8B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
-                 c["outlier_scale"], c["seed"], [c["group"]], [4, 8])
+                 c["outlier_scale"], c["seed"], [c["group"]], [4, 8], fp=True)
     # config 3: LLaMA-8B-shaped gradients, K = 8
     c = C["llama8b_grad"]
-    grad_case("3-8B-grad", c["n"], c["sigma"], c["spike_frac"], c["spike_scale"], c["seed"], c["K"], c["group"])
+    grad_case("3-8B-grad", c["n"], c["sigma"], c["spike_frac"], c["spike_scale"], c["seed"], c["K"], c["group"],
+              fp8=True)
     # config 4: 32B-shaped activations, both group sizes
     c = C["llama32b_act"]
     for name, sh in c["acts"].items():
