@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagoq.so")
-SOURCES = [os.path.join(CSRC, "agoq_kernels.hip"), os.path.join(CSRC, "agoq_host.cpp")]
+SOURCES = [os.path.join(CSRC, name) for name in
+           ("agoq_act.hip", "agoq_grad.hip", "agoq_recompute.hip", "agoq_host.cpp")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
@@ -23,16 +24,31 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC, *FLAGS, "-o", tmp, *SOURCES]
+def _run(cmd):
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass does not know the packed-fp32 feature and says so once per file: noise
     out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    return out
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source to an object (in parallel), then link libagoq.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    objs = [os.path.join(objdir, os.path.basename(src) + ".%d.o" % os.getpid()) for src in SOURCES]
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        outs = list(pool.map(lambda so: _run([HIPCC, *compile_flags, "-c", "-o", so[1], so[0]]),
+                             zip(SOURCES, objs)))
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    outs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]))
+    for o in objs:
+        os.remove(o)
+    if verbose and any(o.strip() for o in outs):
+        print("\n".join(o for o in outs if o.strip()))
     os.replace(tmp, LIB)
     return LIB
 

@@ -1,0 +1,246 @@
+// Activation storage kernels: bf16 -> packed codes + fp32 scales (quantize), and back
+// (dequantize), for 4-, 5-, 6- and 8-bit integer codes and the E2M1 code book.
+#include "agoq_device.hpp"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// Activation quantize: bf16 -> 4-, 5-, 6- or 8-bit codes + fp32 scale per group.
+// One lane owns 8 consecutive elements (one 16-byte load) of a group;
+// GROUP/8 consecutive lanes own a group.  5- and 6-bit codes go to two planes:
+// the low nibbles exactly where 4-bit codes would go, the remaining high bits
+// (one byte or two bytes per lane) to a second plane that starts n_vec*4 bytes in.
+// ---------------------------------------------------------------------------
+template <int BITS, int GROUP, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
+                                                           int64_t n_vec, void* __restrict__ codes,
+                                                           float* __restrict__ scales)
+{
+    static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
+    constexpr int LANES = GROUP / 8;
+    constexpr int QMAX = FP ? 6 : (1 << (BITS - 1)) - 1;   // largest code magnitude
+    constexpr int kBlock = AGOQ_AQ_BLOCK;
+    constexpr bool NTL = AGOQ_AQ_NTL, NTS = AGOQ_AQ_NTS;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    u32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        v[u] = u32x4{0, 0, 0, 0};
+        if (vi < n_vec) v[u] = ld<NTL>(x + vi);
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        float f[8];
+        u32 m = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32 w = v[u][j];
+            f[2 * j] = as_f32(w << 16);
+            f[2 * j + 1] = as_f32(w & 0xFFFF0000u);
+            m = umax(m, umax((w << 16) & 0x7FFFFFFFu, w & 0x7FFF0000u));
+        }
+        m = group_max_bits<LANES>(m);
+        float scale, inv;
+        scale_and_inv<QMAX>(m, scale, inv);
+        if (vi < n_vec) {
+            if (FP) {
+                const u32 p = encode8_e2m1(f, inv);
+                st<NTS>((u32*)codes + vi, scale != 0.0f ? p : 0u);   // dead group: no signed zeros
+            } else if (BITS == 4) {
+                u32 p = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
+                st<NTS>((u32*)codes + vi, p);
+            } else if (BITS == 5 || BITS == 6) {
+                u32 p = 0, h = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const u32 c = code_bits(f[j], inv);
+                    p = push_nibble(p, c);
+                    h = __builtin_amdgcn_alignbit(c >> 4, h, BITS - 4);  // bits 4.. of the code
+                }
+                st<NTS>((u32*)codes + vi, p);
+                uint8_t* high = (uint8_t*)codes + n_vec * 4;
+                if (BITS == 5)
+                    st<NTS>(high + vi, (uint8_t)(h >> 24));
+                else
+                    st<NTS>((uint16_t*)high + vi, (uint16_t)(h >> 16));
+            } else {
+                u32 p0 = 0, p1 = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
+#pragma unroll
+                for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
+                st<NTS>((u32x2*)codes + vi, u32x2{p0, p1});
+            }
+            if ((threadIdx.x & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Activation dequantize: codes + scales -> bf16.  One lane produces 8 elements
+// (one 16-byte store).
+// ---------------------------------------------------------------------------
+template <int BITS, int GROUP, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
+                                                             const float* __restrict__ scales,
+                                                             int64_t n_vec, u32x4* __restrict__ y)
+{
+    static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
+    constexpr int LANES = GROUP / 8;
+    constexpr int kBlock = AGOQ_DQ_BLOCK;
+    constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    u32 lo[UNROLL], hi[UNROLL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        lo[u] = hi[u] = 0;
+        s[u] = 0.0f;
+        if (vi < n_vec) {
+            load_codes8<BITS, NTC>(codes, n_vec, vi, lo[u], hi[u]);
+            s[u] = ld<NTSC>(scales + vi / LANES);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        float q[8], f[8];
+        if (FP) {
+            decode8_e2m1(lo[u], q);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = decode8<BITS>(lo[u], hi[u], j);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = __fmul_rn(q[j], s[u]);
+        if (vi < n_vec)
+            st<NTS>(y + vi, u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                                  pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])});
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void* codes,
+                   float* scales, void* stream)
+{
+    if (!x_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
+    if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    const int unroll = AGOQ_AQ_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * unroll)), block(AGOQ_AQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4* x = (const u32x4*)x_bf16;
+#define AGOQ_LAUNCH_AQ(B, G)                                                                     \
+    switch (unroll) {                                                                            \
+    case 4: act_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
+    case 2: act_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
+    default: act_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;  \
+    }
+    if (group == 128) {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_AQ(4, 128) break;
+        case 5: AGOQ_LAUNCH_AQ(5, 128) break;
+        case 6: AGOQ_LAUNCH_AQ(6, 128) break;
+        default: AGOQ_LAUNCH_AQ(8, 128) break;
+        }
+    } else {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_AQ(4, 64) break;
+        case 5: AGOQ_LAUNCH_AQ(5, 64) break;
+        case 6: AGOQ_LAUNCH_AQ(6, 64) break;
+        default: AGOQ_LAUNCH_AQ(8, 64) break;
+        }
+    }
+#undef AGOQ_LAUNCH_AQ
+    return launch_status();
+}
+
+int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int group, int bits,
+                     void* y_bf16, void* stream)
+{
+    if (!codes || !scales || !y_bf16) return AGOQ_ERR_NULL;
+    if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    // measured: 4-bit codes run best with four vectors per lane at every size; 8-bit codes
+    // with four when the whole grid is resident at once and with one otherwise
+    int unroll = AGOQ_DQ_FORCE_UNROLL;
+    if (unroll == 0) unroll = (bits != 8 || fits_one_round(n_vec, AGOQ_DQ_BLOCK, 4)) ? 4 : 1;
+    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* y = (u32x4*)y_bf16;
+#define AGOQ_LAUNCH_DQ(B, G)                                                                      \
+    switch (unroll) {                                                                             \
+    case 4: act_dequant_kernel<B, G, 4><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
+    case 2: act_dequant_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
+    default: act_dequant_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break; \
+    }
+    if (group == 128) {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_DQ(4, 128) break;
+        case 5: AGOQ_LAUNCH_DQ(5, 128) break;
+        case 6: AGOQ_LAUNCH_DQ(6, 128) break;
+        default: AGOQ_LAUNCH_DQ(8, 128) break;
+        }
+    } else {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_DQ(4, 64) break;
+        case 5: AGOQ_LAUNCH_DQ(5, 64) break;
+        case 6: AGOQ_LAUNCH_DQ(6, 64) break;
+        default: AGOQ_LAUNCH_DQ(8, 64) break;
+        }
+    }
+#undef AGOQ_LAUNCH_DQ
+    return launch_status();
+}
+
+int agoq_fp4_act_quant(const void* x_bf16, int64_t numel, int group, void* codes, float* scales,
+                       void* stream)
+{
+    if (!x_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    constexpr int U = AGOQ_AQ_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4* x = (const u32x4*)x_bf16;
+    if (group == 128)
+        act_quant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    else
+        act_quant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    return launch_status();
+}
+
+int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, int group,
+                         void* y_bf16, void* stream)
+{
+    if (!codes || !scales || !y_bf16) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    constexpr int U = 4;
+    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * U)), block(AGOQ_DQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* y = (u32x4*)y_bf16;
+    if (group == 128)
+        act_dequant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    else
+        act_dequant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,362 @@
+#ifndef AGOQ_DEVICE_HPP
+#define AGOQ_DEVICE_HPP
+// Device and host helpers shared by the kernel files of the AGoQ quantization hot path
+// for gfx950 (MI355X): tuning constants, cache-hinted loads and stores, the cross-lane
+// abs-max, the group scale, and the encoders / decoders of every code width.
+//
+// Every kernel here is a streaming pass: read a tensor once, write its encoded
+// (or decoded) form once.  The bound is HBM bandwidth, so the design goals are
+//   * 16-byte loads, several in flight per lane, issued before any use;
+//   * one quantization group per DPP row (16 lanes) or half row, so the
+//     abs-max reduction is a few cross-lane VALU ops and never touches LDS;
+//   * codes packed in registers and stored as whole dwords / 16-byte vectors.
+// No MFMA: nothing on this path is a contraction.
+//
+// Arithmetic contract (identical for all kernels): IEEE binary32, round to
+// nearest even, no contraction.  scale = amax / qmax and inv = qmax / amax are
+// true divisions; code = rint(x * inv).  rint is realised by adding 1.5 * 2^23:
+// for |t| <= 2^22 the sum lies in [2^23, 2^24) where the spacing of binary32 is
+// exactly 1, so the addition itself rounds t to the nearest integer, ties to
+// even, and the low mantissa bits hold the integer in two's complement.
+// Because |x| <= amax, |x * inv| <= qmax * (1 + 2^-22), whose nearest integer
+// is at most qmax: the codes need no clamp.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "agoq.h"
+namespace {
+
+typedef uint32_t u32;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- launch shapes and cache hints, per kernel (measured on MI355X) ------------------
+// Each macro can be overridden on the compiler command line for tuning sweeps.
+#ifndef AGOQ_AQ_BLOCK          // activation quantize
+#define AGOQ_AQ_BLOCK 128
+#endif
+#ifndef AGOQ_AQ_UNROLL         // 16-byte vectors per lane: 1, 2 or 4
+#define AGOQ_AQ_UNROLL 2
+#endif
+#ifndef AGOQ_AQ_NTL
+#define AGOQ_AQ_NTL 1
+#endif
+#ifndef AGOQ_AQ_NTS
+#define AGOQ_AQ_NTS 1
+#endif
+#ifndef AGOQ_DQ_BLOCK          // activation dequantize
+#define AGOQ_DQ_BLOCK 512
+#endif
+#ifndef AGOQ_DQ_FORCE_UNROLL   // 0 = chosen per launch; else 1, 2 or 4
+#define AGOQ_DQ_FORCE_UNROLL 0
+#endif
+#ifndef AGOQ_DQ_NTC            // code loads
+#define AGOQ_DQ_NTC 1
+#endif
+#ifndef AGOQ_DQ_NTSC           // scale loads
+#define AGOQ_DQ_NTSC 0
+#endif
+#ifndef AGOQ_DQ_NTS
+#define AGOQ_DQ_NTS 1
+#endif
+#ifndef AGOQ_GQ_BLOCK          // gradient quantize
+#define AGOQ_GQ_BLOCK 256
+#endif
+#ifndef AGOQ_GQ_UNROLL
+#define AGOQ_GQ_UNROLL 1
+#endif
+#ifndef AGOQ_GQ_NTL
+#define AGOQ_GQ_NTL 1
+#endif
+#ifndef AGOQ_GQ_NTS
+#define AGOQ_GQ_NTS 1
+#endif
+#ifndef AGOQ_RD_BLOCK          // reduce + requantize
+#define AGOQ_RD_BLOCK 512
+#endif
+#ifndef AGOQ_RD_NTC
+#define AGOQ_RD_NTC 1
+#endif
+#ifndef AGOQ_RD_NTSC
+#define AGOQ_RD_NTSC 1
+#endif
+#ifndef AGOQ_RD_NTS
+#define AGOQ_RD_NTS 1
+#endif
+
+#ifndef AGOQ_GD_BLOCK          // gradient dequantize
+#define AGOQ_GD_BLOCK 512
+#endif
+#ifndef AGOQ_GD_UNROLL
+#define AGOQ_GD_UNROLL 1
+#endif
+#ifndef AGOQ_GD_NTS
+#define AGOQ_GD_NTS 1
+#endif
+
+constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
+constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
+
+__device__ __forceinline__ float as_f32(u32 u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ u32 as_u32(float f) { return __builtin_bit_cast(u32, f); }
+
+// Streaming loads and stores: every byte is touched once, so the caches may drop it early.
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* p, T v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// DPP controls (row = 16 lanes)
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i within 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i within 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ u32 dpp_max_u32(u32 v)
+{
+    u32 o = (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+    return v > o ? v : o;
+}
+
+// Maximum over the LANES consecutive lanes (4, 8 or 16, aligned) that share a group.
+// Operates on magnitude bit patterns: for non-negative finite floats the unsigned
+// integer order of the bits is the order of the values.
+template <int LANES>
+__device__ __forceinline__ u32 group_max_bits(u32 m)
+{
+    m = dpp_max_u32<kDppXor1>(m);
+    m = dpp_max_u32<kDppXor2>(m);
+    if (LANES >= 8) m = dpp_max_u32<kDppHalfMirror>(m);
+    if (LANES >= 16) m = dpp_max_u32<kDppMirror>(m);
+    return m;
+}
+
+__device__ __forceinline__ u32 umax(u32 a, u32 b) { return a > b ? a : b; }
+
+// scale and inv of a group from the bits of its abs-max.
+template <int QMAX>
+__device__ __forceinline__ void scale_and_inv(u32 amax_bits, float& scale, float& inv)
+{
+    const float amax = as_f32(amax_bits);
+    const bool live = amax_bits >= kAmaxMinBits;
+    const float den = live ? amax : 1.0f;
+    const float s = __fdiv_rn(amax, (float)QMAX);
+    const float r = __fdiv_rn((float)QMAX, den);
+    scale = live ? s : 0.0f;
+    inv = live ? r : 0.0f;
+}
+
+// round(x * inv) as the low bits of the returned word (two's complement).
+__device__ __forceinline__ u32 code_bits(float x, float inv)
+{
+    return as_u32(__fadd_rn(__fmul_rn(x, inv), kRoundMagic));
+}
+
+__device__ __forceinline__ u32 push_nibble(u32 packed, u32 code)
+{
+    // shifts the pair {code, packed} right by 4: the new nibble enters at the top, so
+    // after eight pushes the first element sits in bits 0-3
+    return __builtin_amdgcn_alignbit(code, packed, 4);
+}
+
+__device__ __forceinline__ u32 push_byte(u32 packed, u32 code)
+{
+    return __builtin_amdgcn_alignbit(code, packed, 8);
+}
+
+// Signed byte j of a word as a float: one conversion with a sign-extending byte select.
+__device__ __forceinline__ float byte_to_f32(u32 w, int j)
+{
+    return (float)(int8_t)((w >> (8 * j)) & 0xFFu);
+}
+
+// ---- floating-point code books (E2M1 nibbles, OCP E4M3 bytes) ----------------------
+// gfx950's conversion instructions round to nearest, ties to the even mantissa, saturate
+// at the largest magnitude and keep the sign of a zero -- the semantics of the code books
+// here.  fp4 conversions take a power-of-two scale operand; it is always 1.
+
+// Four fp32 values times inv -> one word of 8-bit codes, element 0 in the low byte.
+template <bool FP>
+__device__ __forceinline__ u32 encode4_bytes(float x0, float x1, float x2, float x3, float inv)
+{
+    if (FP) {
+        int w = 0;
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(__fmul_rn(x0, inv), __fmul_rn(x1, inv), w, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(__fmul_rn(x2, inv), __fmul_rn(x3, inv), w, true);
+        return (u32)w;
+    }
+    u32 w = 0;
+    w = push_byte(w, code_bits(x0, inv));
+    w = push_byte(w, code_bits(x1, inv));
+    w = push_byte(w, code_bits(x2, inv));
+    w = push_byte(w, code_bits(x3, inv));
+    return w;
+}
+
+// The four 8-bit codes of a word as fp32 values.
+template <bool FP>
+__device__ __forceinline__ void decode4_bytes(u32 w, float (&q)[4])
+{
+    if (FP) {
+        q[0] = __builtin_amdgcn_cvt_f32_fp8((int)w, 0);
+        q[1] = __builtin_amdgcn_cvt_f32_fp8((int)w, 1);
+        q[2] = __builtin_amdgcn_cvt_f32_fp8((int)w, 2);
+        q[3] = __builtin_amdgcn_cvt_f32_fp8((int)w, 3);
+    } else {
+        q[0] = byte_to_f32(w, 0);
+        q[1] = byte_to_f32(w, 1);
+        q[2] = byte_to_f32(w, 2);
+        q[3] = byte_to_f32(w, 3);
+    }
+}
+
+// Eight fp32 values times inv -> one word of E2M1 nibbles, element 0 in bits 0-3.
+__device__ __forceinline__ u32 encode8_e2m1(const float (&f)[8], float inv)
+{
+    u32 p = 0;
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[0], inv), __fmul_rn(f[1], inv), 1.0f, 0);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[2], inv), __fmul_rn(f[3], inv), 1.0f, 1);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[4], inv), __fmul_rn(f[5], inv), 1.0f, 2);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __fmul_rn(f[6], inv), __fmul_rn(f[7], inv), 1.0f, 3);
+    return p;
+}
+
+// The eight E2M1 nibbles of a word as fp32 values.
+__device__ __forceinline__ void decode8_e2m1(u32 w, float (&q)[8])
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 0);
+    const f32x2 b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 1);
+    const f32x2 c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 2);
+    const f32x2 d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 3);
+    q[0] = a[0]; q[1] = a[1]; q[2] = b[0]; q[3] = b[1];
+    q[4] = c[0]; q[5] = c[1]; q[6] = d[0]; q[7] = d[1];
+}
+
+__device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);   // round to nearest even
+    return __builtin_bit_cast(u32, h);
+}
+
+
+// The stored codes of the 8 elements a lane owns.  4/5/6-bit: lo = the nibble word,
+// hi = the lane's field of high bits.  8-bit: lo, hi = the two code words.
+template <int BITS, bool NT>
+__device__ __forceinline__ void load_codes8(const void* codes, int64_t n_vec, int64_t vi, u32& lo,
+                                            u32& hi)
+{
+    if (BITS == 8) {
+        const u32x2 c = ld<NT>((const u32x2*)codes + vi);
+        lo = c[0];
+        hi = c[1];
+    } else {
+        lo = ld<NT>((const u32*)codes + vi);
+        hi = 0;
+        const uint8_t* high = (const uint8_t*)codes + n_vec * 4;
+        if (BITS == 5) hi = ld<NT>(high + vi);
+        if (BITS == 6) hi = ld<NT>((const uint16_t*)high + vi);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ float decode8(u32 lo, u32 hi, int j)
+{
+    if (BITS == 4) return (float)(int)__builtin_amdgcn_sbfe((int)lo, 4 * j, 4);
+    if (BITS == 8) return byte_to_f32(j < 4 ? lo : hi, j & 3);
+    const int h = (int)__builtin_amdgcn_sbfe((int)hi, (BITS - 4) * j, BITS - 4);
+    return (float)(int)(((u32)h << 4) | __builtin_amdgcn_ubfe(lo, 4 * j, 4));
+}
+
+// x' = bf16(code * scale) for the lane's 8 elements, returned as fp32 values.
+template <int BITS>
+__device__ __forceinline__ void dequant8_bf16(u32 lo, u32 hi, float scale, float (&x)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+        const u32 w = pack_bf16x2(__fmul_rn(decode8<BITS>(lo, hi, j), scale),
+                                  __fmul_rn(decode8<BITS>(lo, hi, j + 1), scale));
+        x[j] = as_f32(w << 16);
+        x[j + 1] = as_f32(w & 0xFFFF0000u);
+    }
+}
+
+// Sum over the wavefront, result in every lane: DPP within rows of 16, then the
+// row-swap and half-swap lane permutes.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += as_f32((u32)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), kDppXor1, 0xF, 0xF, false));
+    v += as_f32((u32)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), kDppXor2, 0xF, 0xF, false));
+    v += as_f32((u32)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), kDppHalfMirror, 0xF, 0xF, false));
+    v += as_f32((u32)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), kDppMirror, 0xF, 0xF, false));
+    auto a = __builtin_amdgcn_permlane16_swap(as_u32(v), as_u32(v), false, false);
+    v = as_f32(a[0]) + as_f32(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return as_f32(b[0]) + as_f32(b[1]);
+}
+
+// ---- host side ------------------------------------------------------------------------
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline int check_common(int64_t numel, int group)
+{
+    if (group != 64 && group != 128) return AGOQ_ERR_GROUP;
+    if (numel <= 0 || numel % group != 0) return AGOQ_ERR_SHAPE;
+    return AGOQ_OK;
+}
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? AGOQ_OK : AGOQ_ERR_HIP;
+}
+
+inline unsigned blocks_for(int64_t items, int per_block)
+{
+    return (unsigned)((items + per_block - 1) / per_block);
+}
+
+// Compute units of the current device (cached per device ordinal).
+inline int compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
+// True when a one-shot grid of `block`-thread workgroups with `unroll` vectors per lane is
+// resident on the chip all at once (2048 threads per compute unit for these small-register
+// kernels).
+inline bool fits_one_round(int64_t n_vec, int block, int unroll)
+{
+    const int64_t capacity = (int64_t)compute_units() * (2048 / block);
+    return (n_vec + (int64_t)block * unroll - 1) / ((int64_t)block * unroll) <= capacity;
+}
+
+}  // namespace
+
+#endif  // AGOQ_DEVICE_HPP

@@ -1,0 +1,502 @@
+// Gradient kernels: 8-bit store, dequantize, local accumulation, and the local
+// dequantize -> fp32 sum -> requantize step of the 8-bit All-Reduce, for int8 codes and
+// the E4M3 code book.
+#include "agoq_device.hpp"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// Gradient quantize: fp32 -> int8 codes + fp32 scale per group.
+// 16 lanes (one DPP row) own a group; a lane holds VPL 16-byte vectors of it,
+// vector p of lane l being elements [p*64 + 4l, p*64 + 4l + 4) of the group, so
+// each load instruction reads whole 256-byte runs.
+// ---------------------------------------------------------------------------
+template <int GROUP, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* __restrict__ g,
+                                                            int64_t n_groups,
+                                                            u32* __restrict__ codes,
+                                                            float* __restrict__ scales)
+{
+    constexpr int VPL = GROUP / 64;   // vectors per lane: 1 (group 64) or 2 (group 128)
+    constexpr int VPG = GROUP / 4;    // vectors per group
+    constexpr int kBlock = AGOQ_GQ_BLOCK;
+    constexpr bool NTL = AGOQ_GQ_NTL, NTS = AGOQ_GQ_NTS;
+    const int lane16 = threadIdx.x & 15;
+    const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    f32x4 v[UNROLL][VPL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+#pragma unroll
+        for (int p = 0; p < VPL; ++p) {
+            v[u][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (grp < n_groups) v[u][p] = ld<NTL>(g + grp * VPG + p * 16 + lane16);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+        u32 m = 0;
+#pragma unroll
+        for (int p = 0; p < VPL; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) m = umax(m, as_u32(v[u][p][j]) & 0x7FFFFFFFu);
+        m = group_max_bits<16>(m);
+        float scale, inv;
+        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
+        if (grp < n_groups) {
+#pragma unroll
+            for (int p = 0; p < VPL; ++p) {
+                u32 w = encode4_bytes<FP>(v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3], inv);
+                if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
+                st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
+            }
+            if (lane16 == 0) st<NTS>(scales + grp, scale);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Local reduce of K int8 chunks + requantize.  One lane owns 16 consecutive
+// elements (one 16-byte load per chunk, one 16-byte store); GROUP/16 lanes own
+// a group.  acc = fma(code_k, scale_k, acc) for k = 0..K-1 in that order.
+// KT > 0: K known at compile time (all loads hoisted); KT == 0: run-time K.
+// ---------------------------------------------------------------------------
+template <int GROUP, bool FP = false>
+__device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi,
+                                              bool valid, u32x4* __restrict__ out_codes,
+                                              float* __restrict__ out_scales)
+{
+    constexpr int LANES = GROUP / 16;
+    u32 m = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
+    m = group_max_bits<LANES>(m);
+    float scale, inv;
+    scale_and_inv<FP ? 448 : 127>(m, scale, inv);
+    if (valid) {
+        u32x4 w = {0, 0, 0, 0};
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            w[d] = encode4_bytes<FP>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv);
+        if (FP && scale == 0.0f) w = u32x4{0, 0, 0, 0};       // dead group: no signed zeros
+        st<AGOQ_RD_NTS>(out_codes + vi, w);
+        if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS>(out_scales + vi / LANES, scale);
+    }
+}
+
+template <bool FP = false>
+__device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, float s)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float q[4];
+        decode4_bytes<FP>(c[d], q);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[4 * d + j] = __fmaf_rn(q[j], s, acc[4 * d + j]);
+    }
+}
+
+template <int GROUP, int KT, bool FP = false>
+__global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
+                                                             int64_t stride_codes,
+                                                             const float* __restrict__ in_scales,
+                                                             int64_t stride_scales, int K,
+                                                             int64_t n_vec,
+                                                             u32x4* __restrict__ out_codes,
+                                                             float* __restrict__ out_scales)
+{
+    constexpr int LANES = GROUP / 16;
+    constexpr int kBlock = AGOQ_RD_BLOCK;
+    constexpr bool NTC = AGOQ_RD_NTC, NTSC = AGOQ_RD_NTSC;
+    const int64_t vi = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool valid = vi < n_vec;
+    const int64_t vc = valid ? vi : 0;      // out-of-range lanes read element 0, store nothing
+    const int64_t grp = vc / LANES;
+    float acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+
+    if (KT > 0) {
+        u32x4 c[KT > 0 ? KT : 1];
+        float s[KT > 0 ? KT : 1];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            c[k] = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
+            s[k] = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
+        }
+#pragma unroll
+        for (int k = 0; k < KT; ++k) reduce_term<FP>(acc, c[k], s[k]);
+    } else {
+        int k = 0;
+        for (; k + 4 <= K; k += 4) {
+            u32x4 c[4];
+            float s[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                c[t] = ld<NTC>((const u32x4*)(in_codes + (int64_t)(k + t) * stride_codes) + vc);
+                s[t] = ld<NTSC>(in_scales + (int64_t)(k + t) * stride_scales + grp);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) reduce_term<FP>(acc, c[t], s[t]);
+        }
+        for (; k < K; ++k) {
+            const u32x4 c = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
+            const float s = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
+            reduce_term<FP>(acc, c, s);
+        }
+    }
+    reduce_finish<GROUP, FP>(acc, vi, valid, out_codes, out_scales);
+}
+
+// ---------------------------------------------------------------------------
+// Local gradient accumulation: stored int8 gradient (+ scales) plus a new
+// micro-batch gradient -> int8 (+ scales).  acc = fma(code, scale, g_new) in fp32,
+// then the group is quantized to 8 bits.  May run in place: a group is read in
+// full by the lanes that own it before any of them stores, and no other lane
+// touches it, so the output may alias the stored gradient.
+//   fp32 addend: lane layout of grad_quant_kernel (one DPP row per group).
+//   bf16 addend: lane layout of act_quant_kernel (8 elements per lane).
+// ---------------------------------------------------------------------------
+template <int GROUP, int UNROLL>
+__global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
+    const u32* main_codes, const float* main_scales, const f32x4* __restrict__ g_new,
+    int64_t n_groups, u32* out_codes, float* out_scales)
+{
+    constexpr int VPL = GROUP / 64;
+    constexpr int VPG = GROUP / 4;
+    constexpr int kBlock = AGOQ_GQ_BLOCK;
+    const int lane16 = threadIdx.x & 15;
+    const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    f32x4 v[UNROLL][VPL];
+    u32 c[UNROLL][VPL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+        s[u] = 0.0f;
+        if (grp < n_groups) s[u] = ld<true>(main_scales + grp);
+#pragma unroll
+        for (int p = 0; p < VPL; ++p) {
+            v[u][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            c[u][p] = 0;
+            if (grp < n_groups) {
+                v[u][p] = ld<true>(g_new + grp * VPG + p * 16 + lane16);
+                c[u][p] = ld<true>(main_codes + grp * VPG + p * 16 + lane16);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
+        float acc[VPL][4];
+        u32 m = 0;
+#pragma unroll
+        for (int p = 0; p < VPL; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[p][j] = __fmaf_rn(byte_to_f32(c[u][p], j), s[u], v[u][p][j]);
+                m = umax(m, as_u32(acc[p][j]) & 0x7FFFFFFFu);
+            }
+        m = group_max_bits<16>(m);
+        float scale, inv;
+        scale_and_inv<127>(m, scale, inv);
+        if (grp < n_groups) {
+#pragma unroll
+            for (int p = 0; p < VPL; ++p) {
+                u32 w = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w = push_byte(w, code_bits(acc[p][j], inv));
+                st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
+            }
+            if (lane16 == 0) st<true>(out_scales + grp, scale);
+        }
+    }
+}
+
+template <int GROUP, int UNROLL>
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
+    const u32x2* main_codes, const float* main_scales, const u32x4* __restrict__ g_new,
+    int64_t n_vec, u32x2* out_codes, float* out_scales)
+{
+    constexpr int LANES = GROUP / 8;
+    constexpr int kBlock = AGOQ_AQ_BLOCK;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+
+    u32x4 v[UNROLL];
+    u32x2 c[UNROLL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        v[u] = u32x4{0, 0, 0, 0};
+        c[u] = u32x2{0, 0};
+        s[u] = 0.0f;
+        if (vi < n_vec) {
+            v[u] = ld<true>(g_new + vi);
+            c[u] = ld<true>(main_codes + vi);
+            s[u] = ld<true>(main_scales + vi / LANES);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        float acc[8];
+        u32 m = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const u32 w = v[u][j >> 1];
+            const float g = as_f32((j & 1) ? (w & 0xFFFF0000u) : (w << 16));
+            acc[j] = __fmaf_rn(byte_to_f32(c[u][j >> 2], j & 3), s[u], g);
+            m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
+        }
+        m = group_max_bits<LANES>(m);
+        float scale, inv;
+        scale_and_inv<127>(m, scale, inv);
+        if (vi < n_vec) {
+            u32 p0 = 0, p1 = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(acc[j], inv));
+#pragma unroll
+            for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(acc[j], inv));
+            st<true>(out_codes + vi, u32x2{p0, p1});
+            if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Gradient dequantize: int8 codes + scales -> fp32 (what an optimizer step reads).
+// One lane: 4 codes (one dword) -> one 16-byte store.
+// ---------------------------------------------------------------------------
+template <int GROUP, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* __restrict__ codes,
+                                                                     const float* __restrict__ scales,
+                                                                     int64_t n_vec,
+                                                                     f32x4* __restrict__ out)
+{
+    constexpr int LANES = GROUP / 4;      // lanes per group
+    constexpr int kBlock = AGOQ_GD_BLOCK;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    u32 c[UNROLL];
+    float s[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        c[u] = 0;
+        s[u] = 0.0f;
+        if (vi < n_vec) {
+            c[u] = ld<true>(codes + vi);
+            s[u] = ld<false>(scales + vi / LANES);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        f32x4 o;
+        float q[4];
+        decode4_bytes<FP>(c[u], q);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(q[j], s[u]);
+        if (vi < n_vec) st<AGOQ_GD_NTS>(out + vi, o);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int agoq_grad_quant(const float* grad, int64_t numel, int group, int8_t* codes, float* scales,
+                    void* stream)
+{
+    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_groups = numel / group;
+    constexpr int U = AGOQ_GQ_UNROLL;
+    const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_quant_kernel<128, U><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups, (u32*)codes,
+                                                          scales);
+    else
+        grad_quant_kernel<64, U><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups, (u32*)codes,
+                                                         scales);
+    return launch_status();
+}
+
+int agoq_grad_reduce_requant(const int8_t* in_codes, int64_t chunk_stride_codes,
+                             const float* in_scales, int64_t chunk_stride_scales, int K,
+                             int64_t numel, int group, int8_t* out_codes, float* out_scales,
+                             void* stream)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (K < 1 || K > 64) return AGOQ_ERR_K;
+    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
+    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
+        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
+        return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 16;
+    const dim3 grid(blocks_for(n_vec, AGOQ_RD_BLOCK)), block(AGOQ_RD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* oc = (u32x4*)out_codes;
+#define AGOQ_LAUNCH_REDUCE(G, KT)                                                              \
+    grad_reduce_kernel<G, KT><<<grid, block, 0, st>>>(in_codes, chunk_stride_codes, in_scales, \
+                                                      chunk_stride_scales, K, n_vec, oc, out_scales)
+    if (group == 128) {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE(128, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE(128, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE(128, 16); break;
+        default: AGOQ_LAUNCH_REDUCE(128, 0); break;
+        }
+    } else {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE(64, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE(64, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE(64, 16); break;
+        default: AGOQ_LAUNCH_REDUCE(64, 0); break;
+        }
+    }
+#undef AGOQ_LAUNCH_REDUCE
+    return launch_status();
+}
+
+int agoq_grad_accumulate(const int8_t* main_codes, const float* main_scales, const void* g_new,
+                         int g_new_is_bf16, int64_t numel, int group, int8_t* out_codes,
+                         float* out_scales, void* stream)
+{
+    if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(main_codes) || misaligned(main_scales) || misaligned(g_new) ||
+        misaligned(out_codes) || misaligned(out_scales))
+        return AGOQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (g_new_is_bf16) {
+        const int64_t n_vec = numel / 8;
+        constexpr int U = AGOQ_AQ_UNROLL;
+        const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+        if (group == 128)
+            grad_accumulate_bf16_kernel<128, U><<<grid, block, 0, st>>>(
+                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                (u32x2*)out_codes, out_scales);
+        else
+            grad_accumulate_bf16_kernel<64, U><<<grid, block, 0, st>>>(
+                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                (u32x2*)out_codes, out_scales);
+    } else {
+        const int64_t n_groups = numel / group;
+        constexpr int U = AGOQ_GQ_UNROLL;
+        const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
+        if (group == 128)
+            grad_accumulate_f32_kernel<128, U><<<grid, block, 0, st>>>(
+                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
+                (u32*)out_codes, out_scales);
+        else
+            grad_accumulate_f32_kernel<64, U><<<grid, block, 0, st>>>(
+                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
+                (u32*)out_codes, out_scales);
+    }
+    return launch_status();
+}
+
+int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, int group,
+                      float* out, void* stream)
+{
+    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 4;
+    constexpr int U = AGOQ_GD_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_dequant_kernel<128, U><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                            (f32x4*)out);
+    else
+        grad_dequant_kernel<64, U><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                           (f32x4*)out);
+    return launch_status();
+}
+
+int agoq_fp8_grad_quant(const float* grad, int64_t numel, int group, uint8_t* codes, float* scales,
+                        void* stream)
+{
+    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_groups = numel / group;
+    constexpr int U = AGOQ_GQ_UNROLL;
+    const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_quant_kernel<128, U, true><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
+                                                                (u32*)codes, scales);
+    else
+        grad_quant_kernel<64, U, true><<<grid, block, 0, st>>>((const f32x4*)grad, n_groups,
+                                                               (u32*)codes, scales);
+    return launch_status();
+}
+
+int agoq_fp8_grad_dequant(const uint8_t* codes, const float* scales, int64_t numel, int group,
+                          float* out, void* stream)
+{
+    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 4;
+    constexpr int U = AGOQ_GD_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        grad_dequant_kernel<128, U, true><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                                  (f32x4*)out);
+    else
+        grad_dequant_kernel<64, U, true><<<grid, block, 0, st>>>((const u32*)codes, scales, n_vec,
+                                                                 (f32x4*)out);
+    return launch_status();
+}
+
+int agoq_fp8_grad_reduce_requant(const uint8_t* in_codes, int64_t chunk_stride_codes,
+                                 const float* in_scales, int64_t chunk_stride_scales, int K,
+                                 int64_t numel, int group, uint8_t* out_codes, float* out_scales,
+                                 void* stream)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (K < 1 || K > 64) return AGOQ_ERR_K;
+    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
+    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
+        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
+        return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 16;
+    const dim3 grid(blocks_for(n_vec, AGOQ_RD_BLOCK)), block(AGOQ_RD_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    u32x4* oc = (u32x4*)out_codes;
+    const int8_t* ic = (const int8_t*)in_codes;
+#define AGOQ_LAUNCH_REDUCE_FP(G, KT)                                                           \
+    grad_reduce_kernel<G, KT, true><<<grid, block, 0, st>>>(ic, chunk_stride_codes, in_scales, \
+                                                            chunk_stride_scales, K, n_vec, oc, out_scales)
+    if (group == 128) {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE_FP(128, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE_FP(128, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE_FP(128, 16); break;
+        default: AGOQ_LAUNCH_REDUCE_FP(128, 0); break;
+        }
+    } else {
+        switch (K) {
+        case 4: AGOQ_LAUNCH_REDUCE_FP(64, 4); break;
+        case 8: AGOQ_LAUNCH_REDUCE_FP(64, 8); break;
+        case 16: AGOQ_LAUNCH_REDUCE_FP(64, 16); break;
+        default: AGOQ_LAUNCH_REDUCE_FP(64, 0); break;
+        }
+    }
+#undef AGOQ_LAUNCH_REDUCE_FP
+    return launch_status();
+}
+
+}  // extern "C"

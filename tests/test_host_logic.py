@@ -122,12 +122,16 @@ def test_generated_isa_has_no_packed_fp32_math(tmp_path):
     """The device code must contain no packed fp32 arithmetic (v_pk_{add,mul,fma}_f32)."""
     import subprocess
     from paper_2605_00539_amd import build
-    out = tmp_path / "agoq_kernels.s"
     flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
-    subprocess.check_call([build.HIPCC, *flags, "-S", "--cuda-device-only", "-o", str(out),
-                           build.SOURCES[0]], stderr=subprocess.DEVNULL)
-    text = out.read_text()
-    assert "act_quant_kernel" in text and "grad_reduce_kernel" in text
+    text = ""
+    for src in build.SOURCES:
+        if not src.endswith(".hip"):
+            continue
+        out = tmp_path / (os.path.basename(src) + ".s")
+        subprocess.check_call([build.HIPCC, *flags, "-S", "--cuda-device-only", "-o", str(out), src],
+                              stderr=subprocess.DEVNULL)
+        text += out.read_text()
+    assert "act_quant_kernel" in text and "grad_reduce_kernel" in text and "rmsnorm" in text
     for mnemonic in ("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32"):
         assert mnemonic not in text, mnemonic
     assert "scratch_" not in text                       # no register spills to scratch memory
