@@ -326,6 +326,52 @@ int agoq_ref_act_dequant_silu_mul(const uint8_t *gate_codes, const float *gate_s
     return REF_OK;
 }
 
+/*
+ * The forward side of the same two layers, for the fused "compute the layer and store its
+ * quantized input in one pass" kernels: plain binary64 definitions on the ORIGINAL bf16
+ * inputs (the stored codes are act_quant's, unchanged).
+ *   rmsnorm_fwd : r_i = sqrt(mean_j x_ij^2 + eps),  y_ij = bf16(gamma_j * x_ij / r_i)
+ *   silu_mul_fwd: z = bf16(u * g / (1 + exp(-g)))
+ */
+int agoq_ref_rmsnorm_fwd(const uint16_t *x, int64_t rows, int64_t cols, const float *gamma,
+                         float eps, uint16_t *y, float *r_out)
+{
+    if (!x || !gamma || !y || !r_out)
+        return REF_ERR_NULL;
+    if (rows <= 0 || cols <= 0)
+        return REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double sumsq = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            const double v = (double)bf16_bits_to_f32(x[i * cols + j]);
+            sumsq += v * v;
+        }
+        const double rms = sqrt(sumsq / (double)cols + (double)eps);
+        r_out[i] = (float)rms;
+        for (int64_t j = 0; j < cols; ++j) {
+            const double v = (double)bf16_bits_to_f32(x[i * cols + j]);
+            y[i * cols + j] = f32_to_bf16_bits((float)((double)gamma[j] * v / rms));
+        }
+    }
+    return REF_OK;
+}
+
+int agoq_ref_silu_mul_fwd(const uint16_t *gate, const uint16_t *up, int64_t numel, uint16_t *z)
+{
+    if (!gate || !up || !z)
+        return REF_ERR_NULL;
+    if (numel <= 0)
+        return REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < numel; ++e) {
+        const double gate_v = (double)bf16_bits_to_f32(gate[e]);
+        const double up_v = (double)bf16_bits_to_f32(up[e]);
+        z[e] = f32_to_bf16_bits((float)(up_v * gate_v / (1.0 + exp(-gate_v))));
+    }
+    return REF_OK;
+}
+
 /* ---- gradients ---------------------------------------------------------- */
 
 int agoq_ref_grad_quant(const float *grad, int64_t numel, int group, int8_t *codes,

@@ -12,7 +12,7 @@ import numpy as np
 from . import build as _build
 
 __all__ = [
-    "lib", "fp4_act_quant", "fp4_act_dequant", "fp8_grad_quant", "fp8_grad_dequant",
+    "lib", "rmsnorm_fwd", "silu_mul_fwd", "fp4_act_quant", "fp4_act_dequant", "fp8_grad_quant", "fp8_grad_dequant",
     "fp8_grad_reduce_requant", "e2m1_encode", "e2m1_decode", "e4m3_encode", "e4m3_decode", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
     "grad_reduce_requant", "grad_reduce_f64", "grad_accumulate", "dbca_bits",
     "dbca_stored_microbatches", "bf16_to_f32", "f32_to_bf16", "max_threads",
@@ -41,6 +41,8 @@ def _bind(path):
     L.agoq_ref_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P]
     L.agoq_ref_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _INT, _P, ctypes.c_float, _P, _P]
     L.agoq_ref_act_dequant_silu_mul.argtypes = [_P, _P, _INT, _P, _P, _INT, _I64, _INT, _P]
+    L.agoq_ref_rmsnorm_fwd.argtypes = [_P, _I64, _I64, _P, ctypes.c_float, _P, _P]
+    L.agoq_ref_silu_mul_fwd.argtypes = [_P, _P, _I64, _P]
     L.agoq_ref_fp4_act_quant.argtypes = [_P, _I64, _INT, _P, _P]
     L.agoq_ref_fp4_act_dequant.argtypes = [_P, _P, _I64, _INT, _P]
     L.agoq_ref_fp8_grad_quant.argtypes = [_P, _I64, _INT, _P, _P]
@@ -140,6 +142,21 @@ class Oracle:
         _check(self.lib.agoq_ref_act_dequant_silu_mul(
             _ptr(gate_codes), _ptr(gate_scales), gate_bits, _ptr(up_codes), _ptr(up_scales),
             up_bits, numel, group, _ptr(z)))
+        return z
+
+    def rmsnorm_fwd(self, x_bf16_bits, rows, cols, gamma, eps):
+        x = _c(x_bf16_bits, np.uint16).reshape(-1)
+        gamma = _c(gamma, np.float32).reshape(-1)
+        y = np.zeros(rows * cols, np.uint16)
+        r = np.zeros(rows, np.float32)
+        _check(self.lib.agoq_ref_rmsnorm_fwd(_ptr(x), rows, cols, _ptr(gamma), float(eps), _ptr(y), _ptr(r)))
+        return y, r
+
+    def silu_mul_fwd(self, gate_bits, up_bits):
+        g = _c(gate_bits, np.uint16).reshape(-1)
+        u = _c(up_bits, np.uint16).reshape(-1)
+        z = np.zeros(g.size, np.uint16)
+        _check(self.lib.agoq_ref_silu_mul_fwd(_ptr(g), _ptr(u), g.size, _ptr(z)))
         return z
 
     # ---- floating-point code books (E2M1 activations, E4M3 gradients) ----
@@ -278,6 +295,8 @@ lib = _default.lib
 act_quant = _default.act_quant
 act_dequant = _default.act_dequant
 act_dequant_rmsnorm = _default.act_dequant_rmsnorm
+rmsnorm_fwd = _default.rmsnorm_fwd
+silu_mul_fwd = _default.silu_mul_fwd
 act_dequant_silu_mul = _default.act_dequant_silu_mul
 grad_quant = _default.grad_quant
 fp4_act_quant = _default.fp4_act_quant

@@ -57,6 +57,11 @@ MUTANTS = [
      "y[e] = f32_to_bf16_bits((float)((double)gamma[0] * x / r));"),
     ("rmsnorm_skips_bf16_rounding_of_input", "double x = (double)bf16_bits_to_f32(f32_to_bf16_bits(v));\n            ss += x * x;",
      "double x = (double)v;\n            ss += x * x;"),
+    ("rmsnorm_fwd_gamma_squared", "(double)gamma[j] * v / rms));", "(double)gamma[j] * (double)gamma[j] * v / rms));"),
+    ("rmsnorm_fwd_no_eps", "const double rms = sqrt(sumsq / (double)cols + (double)eps);",
+     "const double rms = sqrt(sumsq / (double)cols);"),
+    ("silu_fwd_plain_product", "z[e] = f32_to_bf16_bits((float)(up_v * gate_v / (1.0 + exp(-gate_v))));",
+     "z[e] = f32_to_bf16_bits((float)(up_v * gate_v));"),
     ("silu_sigmoid_of_minus_gate", "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-g))));",
      "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(g))));"),
     ("silu_applied_to_up", "z[e] = f32_to_bf16_bits((float)(u * g / (1.0 + exp(-g))));",

@@ -109,3 +109,37 @@ def test_silu_mul_closed_forms(ref):
     for k in range(0, 6, 2):
         g = q2[k] * 2.0 ** -5
         assert abs((z2[k] - z2[k + 1]) - g) <= abs(g) * 2.0 ** -7
+
+
+# ---- the forward side: plain layer definitions on the original inputs -----------------
+
+def test_rmsnorm_forward_matches_torch(ref):
+    rng = np.random.default_rng(90)
+    rows, cols = 29, 640
+    xb = bf16_bits((rng.standard_normal((rows, cols)) * 2).astype(np.float32))
+    gamma = (1.0 + 0.1 * rng.standard_normal(cols)).astype(np.float32)
+    y, r = ref.rmsnorm_fwd(xb, rows, cols, gamma, 1e-5)
+    xd = torch.from_numpy(bf16_bits_to_f64(xb).reshape(rows, cols))
+    want = torch.nn.functional.rms_norm(xd, (cols,), torch.from_numpy(gamma.astype(np.float64)), 1e-5).numpy()
+    assert np.allclose(r, np.sqrt((xd.numpy() ** 2).mean(axis=1) + 1e-5), rtol=2e-7)
+    d = bf16_steps_apart(y, bf16_bits(want.astype(np.float32)).reshape(-1))
+    assert d.max() <= 1 and np.mean(d == 0) > 0.999
+    # closed form: a row of +-c
+    row = bf16_bits(np.where(np.arange(cols) % 2 == 0, 0.25, -0.25).astype(np.float32))
+    y1, r1 = ref.rmsnorm_fwd(row, 1, cols, np.full(cols, 3.0, np.float32), 0.0)
+    assert r1[0] == 0.25 and np.array_equal(bf16_bits_to_f64(y1), np.where(np.arange(cols) % 2 == 0, 3.0, -3.0))
+
+
+def test_silu_mul_forward_matches_torch(ref):
+    rng = np.random.default_rng(91)
+    n = 5000
+    gb = bf16_bits((rng.standard_normal(n) * 4).astype(np.float32))
+    ub = bf16_bits(rng.standard_normal(n).astype(np.float32))
+    z = ref.silu_mul_fwd(gb, ub)
+    g = torch.from_numpy(bf16_bits_to_f64(gb))
+    u = torch.from_numpy(bf16_bits_to_f64(ub))
+    want = (torch.nn.functional.silu(g) * u).numpy()
+    d = bf16_steps_apart(z, bf16_bits(want.astype(np.float32)))
+    assert d.max() <= 1 and np.mean(d == 0) > 0.999
+    zero = ref.silu_mul_fwd(np.zeros(8, np.uint16), ub[:8])
+    assert not (zero & 0x7FFF).any()
