@@ -117,6 +117,25 @@ int agoq_act_dequant_silu_mul(const void *gate_codes, const float *gate_scales, 
                               int64_t numel, int group, void *z_bf16, void *stream);
 
 /*
+ * Forward-side counterparts: compute the layer and store its quantized input in the same
+ * pass (paper: "Kernel Fusion of Quantization/Dequantization and GEMM" motivates fusing
+ * the element-wise quantization into a neighbouring kernel; here the neighbour is the
+ * element-wise / row-wise layer that produces the next GEMM's input, so the input tensor
+ * is read once instead of twice).  codes/scales are exactly what agoq_act_quant writes
+ * for the same input; y / z are within one bf16 step of the exact value.
+ *   agoq_rmsnorm_fwd_quant : y = bf16(gamma * x / r), r = sqrt(mean(x^2) + eps) per row
+ *                            (r_out may be NULL); cols a multiple of group, <= 16384
+ *   agoq_silu_mul_fwd_quant: z = bf16(up * gate * sigmoid(gate)); the two inputs may be
+ *                            stored at different widths
+ */
+int agoq_rmsnorm_fwd_quant(const void *x_bf16, int64_t rows, int64_t cols, const float *gamma,
+                           float eps, int group, int bits, void *y_bf16, float *r_out, void *codes,
+                           float *scales, void *stream);
+int agoq_silu_mul_fwd_quant(const void *gate_bf16, const void *up_bf16, int64_t numel, int group,
+                            int gate_bits, int up_bits, void *z_bf16, void *gate_codes,
+                            float *gate_scales, void *up_codes, float *up_scales, void *stream);
+
+/*
  * Store a gradient as 8-bit block-wise codes (paper: "Precision-Preserved
  * Gradient Quantization": the main gradient is kept in 8 bits).
  *   grad   : in,  numel fp32

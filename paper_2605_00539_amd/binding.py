@@ -41,6 +41,8 @@ def load_library():
     L.agoq_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _INT, _P, ctypes.c_float, _P, _P, _P]
     L.agoq_act_dequant_silu_mul.argtypes = [_P, _P, _INT, _P, _P, _INT, _I64, _INT, _P, _P]
+    L.agoq_rmsnorm_fwd_quant.argtypes = [_P, _I64, _I64, _P, ctypes.c_float, _INT, _INT, _P, _P, _P, _P, _P]
+    L.agoq_silu_mul_fwd_quant.argtypes = [_P, _P, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _P]
     L.agoq_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
     L.agoq_fp4_act_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
@@ -193,6 +195,50 @@ def act_dequant_silu_mul(gate_codes, gate_scales, gate_bits, up_codes, up_scales
             _raw(up_codes.data_ptr()), _raw(up_scales.data_ptr()), up_bits, numel, group,
             _raw(out.data_ptr()), _stream(stream)))
     return out
+
+
+def rmsnorm_fwd_quant(x, gamma, eps, group, bits, stream=None):
+    """x bf16 [rows, cols] -> (y bf16 [rows, cols], r float32 [rows], codes uint8, scales float32)."""
+    import torch
+    L = load_library()
+    x = _dev(x, torch.bfloat16, "x")
+    _dev(gamma, torch.float32, "gamma")
+    if x.dim() != 2 or gamma.numel() != x.shape[1]:
+        raise ValueError("x must be [rows, cols] and gamma [cols]")
+    rows, cols = x.shape
+    n = rows * cols
+    y = torch.empty_like(x)
+    r = torch.empty(rows, dtype=torch.float32, device=x.device)
+    codes = torch.empty(max(n * bits // 8, 1), dtype=torch.uint8, device=x.device)
+    scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
+    with _on_device(x.device):
+        _check(L.agoq_rmsnorm_fwd_quant(
+            _raw(x.data_ptr()), rows, cols, _raw(gamma.data_ptr()), float(eps), group, bits,
+            _raw(y.data_ptr()), _raw(r.data_ptr()), _raw(codes.data_ptr()), _raw(scales.data_ptr()),
+            _stream(stream)))
+    return y, r, codes, scales
+
+
+def silu_mul_fwd_quant(gate, up, group, gate_bits, up_bits, stream=None):
+    """gate, up bf16 -> (z bf16, gate_codes, gate_scales, up_codes, up_scales)."""
+    import torch
+    L = load_library()
+    gate = _dev(gate, torch.bfloat16, "gate")
+    up = _dev(up, torch.bfloat16, "up")
+    n = gate.numel()
+    if up.numel() != n:
+        raise ValueError("gate and up must have the same number of elements")
+    z = torch.empty_like(gate)
+    gc = torch.empty(max(n * gate_bits // 8, 1), dtype=torch.uint8, device=gate.device)
+    uc = torch.empty(max(n * up_bits // 8, 1), dtype=torch.uint8, device=gate.device)
+    gs = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=gate.device)
+    us = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=gate.device)
+    with _on_device(gate.device):
+        _check(L.agoq_silu_mul_fwd_quant(
+            _raw(gate.data_ptr()), _raw(up.data_ptr()), n, group, gate_bits, up_bits,
+            _raw(z.data_ptr()), _raw(gc.data_ptr()), _raw(gs.data_ptr()), _raw(uc.data_ptr()),
+            _raw(us.data_ptr()), _stream(stream)))
+    return z, gc, gs, uc, us
 
 
 def grad_quant(grad, group, codes=None, scales=None, stream=None):

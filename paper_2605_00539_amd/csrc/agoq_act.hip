@@ -16,9 +16,7 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
                                                            int64_t n_vec, void* __restrict__ codes,
                                                            float* __restrict__ scales)
 {
-    static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
     constexpr int LANES = GROUP / 8;
-    constexpr int QMAX = FP ? 6 : (1 << (BITS - 1)) - 1;   // largest code magnitude
     constexpr int kBlock = AGOQ_AQ_BLOCK;
     constexpr bool NTL = AGOQ_AQ_NTL, NTS = AGOQ_AQ_NTS;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
@@ -34,50 +32,8 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         float f[8];
-        u32 m = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const u32 w = v[u][j];
-            f[2 * j] = as_f32(w << 16);
-            f[2 * j + 1] = as_f32(w & 0xFFFF0000u);
-            m = umax(m, umax((w << 16) & 0x7FFFFFFFu, w & 0x7FFF0000u));
-        }
-        m = group_max_bits<LANES>(m);
-        float scale, inv;
-        scale_and_inv<QMAX>(m, scale, inv);
-        if (vi < n_vec) {
-            if (FP) {
-                const u32 p = encode8_e2m1(f, inv);
-                st<NTS>((u32*)codes + vi, scale != 0.0f ? p : 0u);   // dead group: no signed zeros
-            } else if (BITS == 4) {
-                u32 p = 0;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
-                st<NTS>((u32*)codes + vi, p);
-            } else if (BITS == 5 || BITS == 6) {
-                u32 p = 0, h = 0;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const u32 c = code_bits(f[j], inv);
-                    p = push_nibble(p, c);
-                    h = __builtin_amdgcn_alignbit(c >> 4, h, BITS - 4);  // bits 4.. of the code
-                }
-                st<NTS>((u32*)codes + vi, p);
-                uint8_t* high = (uint8_t*)codes + n_vec * 4;
-                if (BITS == 5)
-                    st<NTS>(high + vi, (uint8_t)(h >> 24));
-                else
-                    st<NTS>((uint16_t*)high + vi, (uint16_t)(h >> 16));
-            } else {
-                u32 p0 = 0, p1 = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
-#pragma unroll
-                for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
-                st<NTS>((u32x2*)codes + vi, u32x2{p0, p1});
-            }
-            if ((threadIdx.x & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
-        }
+        const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f));
+        quantize_store8<BITS, GROUP, FP, NTS>(f, m, vi, n_vec, vi < n_vec, codes, scales);
     }
 }
 

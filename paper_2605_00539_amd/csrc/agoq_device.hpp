@@ -256,6 +256,68 @@ __device__ __forceinline__ u32 pack_bf16x2(float lo, float hi)
 }
 
 
+// A 16-byte vector of 8 bf16 values -> fp32; returns the bit pattern of the largest magnitude.
+__device__ __forceinline__ u32 unpack8_bf16(const u32x4& v, float (&f)[8])
+{
+    u32 m = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const u32 w = v[j];
+        f[2 * j] = as_f32(w << 16);
+        f[2 * j + 1] = as_f32(w & 0xFFFF0000u);
+        m = umax(m, umax((w << 16) & 0x7FFFFFFFu, w & 0x7FFF0000u));
+    }
+    return m;
+}
+
+// Quantize the 8 elements a lane owns and store them.  amax_bits is the abs-max of the
+// lane's whole group (already reduced across its GROUP/8 lanes); vi is the lane's vector
+// index in the tensor of n_vec vectors.  Every lane must call this (the caller reduces
+// across lanes first); `valid` gates the stores.
+template <int BITS, int GROUP, bool FP, bool NTS>
+__device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bits, int64_t vi,
+                                                int64_t n_vec, bool valid, void* codes,
+                                                float* scales)
+{
+    static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
+    constexpr int LANES = GROUP / 8;
+    constexpr int QMAX = FP ? 6 : (1 << (BITS - 1)) - 1;   // largest code magnitude
+    float scale, inv;
+    scale_and_inv<QMAX>(amax_bits, scale, inv);
+    if (!valid) return;
+    if (FP) {
+        const u32 p = encode8_e2m1(f, inv);
+        st<NTS>((u32*)codes + vi, scale != 0.0f ? p : 0u);   // dead group: no signed zeros
+    } else if (BITS == 4) {
+        u32 p = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
+        st<NTS>((u32*)codes + vi, p);
+    } else if (BITS == 5 || BITS == 6) {
+        u32 p = 0, h = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const u32 c = code_bits(f[j], inv);
+            p = push_nibble(p, c);
+            h = __builtin_amdgcn_alignbit(c >> 4, h, BITS - 4);  // bits 4.. of the code
+        }
+        st<NTS>((u32*)codes + vi, p);
+        uint8_t* high = (uint8_t*)codes + n_vec * 4;
+        if (BITS == 5)
+            st<NTS>(high + vi, (uint8_t)(h >> 24));
+        else
+            st<NTS>((uint16_t*)high + vi, (uint16_t)(h >> 16));
+    } else {
+        u32 p0 = 0, p1 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
+#pragma unroll
+        for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
+        st<NTS>((u32x2*)codes + vi, u32x2{p0, p1});
+    }
+    if ((vi & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
+}
+
 // The stored codes of the 8 elements a lane owns.  4/5/6-bit: lo = the nibble word,
 // hi = the lane's field of high bits.  8-bit: lo, hi = the two code words.
 template <int BITS, bool NT>

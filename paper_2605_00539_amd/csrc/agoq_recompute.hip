@@ -1,6 +1,7 @@
-// Dequantize fused with the recomputation of the layer's forward (the stored tensor is
-// the layer's INPUT; what the backward pass needs is recomputed from its dequantized value
-// instead of being written to memory and read again): RMSNorm and SiLU & Multiply.
+// Kernels fused with the two layers whose INPUT is what gets stored (RMSNorm, SiLU &
+// Multiply).  Backward side: dequantize and recompute the layer's forward from the
+// dequantized value, which never goes to memory.  Forward side: compute the layer and store
+// its quantized input in one pass over the input.
 #include "agoq_device.hpp"
 
 namespace {
@@ -158,6 +159,107 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_silu_mul_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// Forward side: compute the layer and store its quantized INPUT in one pass, so the
+// input is read from memory once instead of once by the layer and once by the quantizer.
+// ---------------------------------------------------------------------------
+
+// RMSNorm forward + quantize(x): one workgroup per row (cols <= 2048 * VPT).
+//   y = bf16(x * (1/r) * gamma), r = sqrt(mean(x^2) + eps);  codes, scales = quantize(x)
+template <int BITS, int GROUP, int VPT>
+__global__ __launch_bounds__(kNormBlock) void rmsnorm_fwd_quant_kernel(
+    const u32x4* __restrict__ x, int64_t n_vec_total, int vecs_per_row,
+    const f32x4* __restrict__ gamma, float eps, float inv_cols, u32x4* __restrict__ y,
+    float* __restrict__ r_out, void* __restrict__ codes, float* __restrict__ scales)
+{
+    constexpr int LANES = GROUP / 8;
+    __shared__ float wave_part[kNormBlock / 64];
+    const int64_t row_vec0 = (int64_t)blockIdx.x * vecs_per_row;
+    u32x4 v[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int c = threadIdx.x + u * kNormBlock;
+        v[u] = u32x4{0, 0, 0, 0};
+        if (c < vecs_per_row) v[u] = ld<true>(x + row_vec0 + c);
+    }
+    float f[VPT][8];
+    float ss = 0.0f;
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int c = threadIdx.x + u * kNormBlock;
+        const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f[u]));
+        quantize_store8<BITS, GROUP, false, true>(f[u], m, row_vec0 + c, n_vec_total,
+                                                  c < vecs_per_row, codes, scales);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss = __fmaf_rn(f[u][j], f[u][j], ss);
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float total = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kNormBlock / 64; ++w) total += wave_part[w];
+    const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
+    const float rinv = __fdiv_rn(1.0f, r);
+    if (threadIdx.x == 0 && r_out) r_out[blockIdx.x] = r;
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int c = threadIdx.x + u * kNormBlock;
+        if (c < vecs_per_row) {
+            const f32x4 g0 = gamma[2 * c], g1 = gamma[2 * c + 1];
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[j] = __fmul_rn(__fmul_rn(f[u][j], rinv), g0[j]);
+                o[4 + j] = __fmul_rn(__fmul_rn(f[u][4 + j], rinv), g1[j]);
+            }
+            st<true>(y + row_vec0 + c, u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]),
+                                             pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])});
+        }
+    }
+}
+
+// SiLU & Multiply forward + quantize(gate), quantize(up), elementwise.
+//   z = bf16(up * gate * sigmoid(gate))
+template <int BITS_G, int BITS_U, int GROUP, int UNROLL>
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void silu_mul_fwd_quant_kernel(
+    const u32x4* __restrict__ gate, const u32x4* __restrict__ up, int64_t n_vec,
+    u32x4* __restrict__ z, void* __restrict__ gate_codes, float* __restrict__ gate_scales,
+    void* __restrict__ up_codes, float* __restrict__ up_scales)
+{
+    constexpr int LANES = GROUP / 8;
+    constexpr int kBlock = AGOQ_AQ_BLOCK;
+    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    u32x4 gv[UNROLL], uv[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        gv[u] = uv[u] = u32x4{0, 0, 0, 0};
+        if (vi < n_vec) {
+            gv[u] = ld<true>(gate + vi);
+            uv[u] = ld<true>(up + vi);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t vi = base + (int64_t)u * kBlock;
+        const bool valid = vi < n_vec;
+        float g[8], w[8], o[8];
+        const u32 mg = group_max_bits<LANES>(unpack8_bf16(gv[u], g));
+        const u32 mu = group_max_bits<LANES>(unpack8_bf16(uv[u], w));
+        quantize_store8<BITS_G, GROUP, false, true>(g, mg, vi, n_vec, valid, gate_codes, gate_scales);
+        quantize_store8<BITS_U, GROUP, false, true>(w, mu, vi, n_vec, valid, up_codes, up_scales);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float e = __expf(-g[j]);                          // may be +inf: 1/(1+inf) = 0
+            o[j] = __fmul_rn(__fmul_rn(w[j], g[j]), __builtin_amdgcn_rcpf(1.0f + e));
+        }
+        if (valid)
+            st<true>(z + vi, u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]),
+                                   pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])});
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -274,6 +376,99 @@ int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, 
     }
 #undef AGOQ_SILU_UP
 #undef AGOQ_LAUNCH_SILU
+    return launch_status();
+}
+
+int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const float* gamma,
+                           float eps, int group, int bits, void* y_bf16, float* r_out, void* codes,
+                           float* scales, void* stream)
+{
+    if (!x_bf16 || !gamma || !y_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
+    if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
+    if (group != 64 && group != 128) return AGOQ_ERR_GROUP;
+    if (rows <= 0 || rows > 0x7FFFFFFF || cols <= 0 || cols % group != 0 ||
+        cols > (int64_t)kNormBlock * 8 * 8)
+        return AGOQ_ERR_SHAPE;
+    if (misaligned(x_bf16) || misaligned(gamma) || misaligned(y_bf16) || misaligned(codes) ||
+        misaligned(scales))
+        return AGOQ_ERR_ALIGN;
+    const int vecs_per_row = (int)(cols / 8);
+    const int64_t n_vec_total = rows * vecs_per_row;
+    const float inv_cols = 1.0f / (float)cols;
+    int vpt = 1;
+    while (kNormBlock * vpt < vecs_per_row) vpt *= 2;
+    const dim3 grid((unsigned)rows), block(kNormBlock);
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4* x = (const u32x4*)x_bf16;
+    const f32x4* gm = (const f32x4*)gamma;
+    u32x4* y = (u32x4*)y_bf16;
+#define AGOQ_LAUNCH_NORM_FWD(B, G)                                                                \
+    switch (vpt) {                                                                                \
+    case 1: rmsnorm_fwd_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 4: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    default: rmsnorm_fwd_quant_kernel<B, G, 8><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    }
+    if (group == 128) {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_NORM_FWD(4, 128) break;
+        case 5: AGOQ_LAUNCH_NORM_FWD(5, 128) break;
+        case 6: AGOQ_LAUNCH_NORM_FWD(6, 128) break;
+        default: AGOQ_LAUNCH_NORM_FWD(8, 128) break;
+        }
+    } else {
+        switch (bits) {
+        case 4: AGOQ_LAUNCH_NORM_FWD(4, 64) break;
+        case 5: AGOQ_LAUNCH_NORM_FWD(5, 64) break;
+        case 6: AGOQ_LAUNCH_NORM_FWD(6, 64) break;
+        default: AGOQ_LAUNCH_NORM_FWD(8, 64) break;
+        }
+    }
+#undef AGOQ_LAUNCH_NORM_FWD
+    return launch_status();
+}
+
+int agoq_silu_mul_fwd_quant(const void* gate_bf16, const void* up_bf16, int64_t numel, int group,
+                            int gate_bits, int up_bits, void* z_bf16, void* gate_codes,
+                            float* gate_scales, void* up_codes, float* up_scales, void* stream)
+{
+    if (!gate_bf16 || !up_bf16 || !z_bf16 || !gate_codes || !gate_scales || !up_codes || !up_scales)
+        return AGOQ_ERR_NULL;
+    if ((gate_bits != 4 && gate_bits != 5 && gate_bits != 6 && gate_bits != 8) ||
+        (up_bits != 4 && up_bits != 5 && up_bits != 6 && up_bits != 8))
+        return AGOQ_ERR_BITS;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(gate_bf16) || misaligned(up_bf16) || misaligned(z_bf16) ||
+        misaligned(gate_codes) || misaligned(gate_scales) || misaligned(up_codes) ||
+        misaligned(up_scales))
+        return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 8;
+    constexpr int U = 2;
+    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4* g = (const u32x4*)gate_bf16;
+    const u32x4* up = (const u32x4*)up_bf16;
+    u32x4* z = (u32x4*)z_bf16;
+#define AGOQ_LAUNCH_SILU_FWD(BG, BU)                                                              \
+    if (group == 128)                                                                             \
+        silu_mul_fwd_quant_kernel<BG, BU, 128, U><<<grid, block, 0, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales); \
+    else                                                                                          \
+        silu_mul_fwd_quant_kernel<BG, BU, 64, U><<<grid, block, 0, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
+#define AGOQ_SILU_FWD_UP(BG)                                                                      \
+    switch (up_bits) {                                                                            \
+    case 4: AGOQ_LAUNCH_SILU_FWD(BG, 4) break;                                                    \
+    case 5: AGOQ_LAUNCH_SILU_FWD(BG, 5) break;                                                    \
+    case 6: AGOQ_LAUNCH_SILU_FWD(BG, 6) break;                                                    \
+    default: AGOQ_LAUNCH_SILU_FWD(BG, 8) break;                                                   \
+    }
+    switch (gate_bits) {
+    case 4: AGOQ_SILU_FWD_UP(4) break;
+    case 5: AGOQ_SILU_FWD_UP(5) break;
+    case 6: AGOQ_SILU_FWD_UP(6) break;
+    default: AGOQ_SILU_FWD_UP(8) break;
+    }
+#undef AGOQ_SILU_FWD_UP
+#undef AGOQ_LAUNCH_SILU_FWD
     return launch_status();
 }
 

@@ -127,6 +127,17 @@ def main():
                            P(rs[i % 4].data_ptr()), st) for i in range(m)]
                     us = timed(lambda i: L.agoq_act_dequant_rmsnorm(*na[i % len(na)]), args.launches, args.reps)
                     report(config, "act_dequant_rmsnorm", case, us, nb + 4 * rows_)
+                    # forward side: the layer plus the quantization of its input in one pass
+                    fa = [(P(xs[i % nx].data_ptr()), rows_, cols, P(gamma.data_ptr()), ctypes.c_float(1e-5), group,
+                           bits, P(ys[i % nx].data_ptr()), P(rs[i % 4].data_ptr()), P(cs[i % nc].data_ptr()),
+                           P(ss[i % nc].data_ptr()), st) for i in range(m)]
+                    us = timed(lambda i: L.agoq_rmsnorm_fwd_quant(*fa[i % len(fa)]), args.launches, args.reps)
+                    report(config, "rmsnorm_fwd_quant", case, us, nb + 2 * n + 4 * rows_)
+                    ga = [(P(xs[i % nx].data_ptr()), P(xs[(i + 1) % nx].data_ptr()), n, group, bits, bits,
+                           P(ys[i % nx].data_ptr()), P(cs[i % nc].data_ptr()), P(ss[i % nc].data_ptr()),
+                           P(cs[(i + 1) % nc].data_ptr()), P(ss[(i + 1) % nc].data_ptr()), st) for i in range(m)]
+                    us = timed(lambda i: L.agoq_silu_mul_fwd_quant(*ga[i % len(ga)]), args.launches, args.reps)
+                    report(config, "silu_mul_fwd_quant", case, us, 2 * nb + 2 * n)
                     # SiLU & Multiply recompute from two stored tensors of this shape and width
                     sa = [(P(cs[i % nc].data_ptr()), P(ss[i % nc].data_ptr()), bits,
                            P(cs[(i + 1) % nc].data_ptr()), P(ss[(i + 1) % nc].data_ptr()), bits, n, group,

@@ -133,3 +133,96 @@ def test_recompute_error_codes(agoq):
     assert L.agoq_act_dequant_silu_mul(pc, ps, 4, pc, ps, 4, 1000, 128, py, None) == 4
     torch.cuda.synchronize()
     assert not bool(y.view(torch.int16).any())
+
+
+# ---- forward side: compute the layer and store its quantized input in one pass ---------
+
+def dev_bf16(bits_u16):
+    return torch.from_numpy(np.ascontiguousarray(bits_u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+@pytest.mark.parametrize("bits", [4, 5, 6, 8])
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("rows,cols", [(3, 128), (17, 1024), (64, 4096), (33, 5120), (5, 14336), (2, 16384)])
+def test_rmsnorm_forward_with_quantized_input(agoq, ref, rows, cols, group, bits):
+    x = wl.act_host(rows, cols, 9000 + rows + cols, "student_t3", max(1, cols // 100), 50.0)
+    if rows > 4:
+        x[2] = 0                                                   # a zero row: dead groups, r = sqrt(eps)
+    rng = np.random.default_rng(cols + 1)
+    gamma = (1.0 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    eps = 1e-5
+    y, r, codes, scales = agoq.rmsnorm_fwd_quant(dev_bf16(x), torch.from_numpy(gamma).cuda(), eps, group, bits)
+    torch.cuda.synchronize()
+    wc, ws = ref.act_quant(x, group, bits)                          # the stored form: bit for bit
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+    want_y, want_r = ref.rmsnorm_fwd(x, rows, cols, gamma, eps)      # the layer output: binary64 definition
+    assert np.allclose(r.cpu().numpy(), want_r, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y), want_y)
+
+
+@pytest.mark.parametrize("gate_bits,up_bits", [(4, 4), (8, 4), (5, 6), (6, 5), (8, 8)])
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("n_groups", [1, 9, 2 * 128 * 2 * 8 // 64 + 5, 30011])
+def test_silu_mul_forward_with_quantized_inputs(agoq, ref, n_groups, group, gate_bits, up_bits):
+    n = n_groups * group
+    rng = np.random.default_rng(9500 + n_groups)
+    g = (rng.standard_normal(n) * 4).astype(np.float32)
+    g[::1000] *= 30.0
+    u = rng.standard_normal(n).astype(np.float32)
+    if n_groups > 4:
+        g[group: 2 * group] = 0.0
+        u[2 * group: 3 * group] = -0.0
+    gb = torch.from_numpy(g).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    ub = torch.from_numpy(u).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    z, gc, gs, uc, us = agoq.silu_mul_fwd_quant(dev_bf16(gb), dev_bf16(ub), group, gate_bits, up_bits)
+    torch.cuda.synchronize()
+    for got_c, got_s, bits, src in ((gc, gs, gate_bits, gb), (uc, us, up_bits, ub)):
+        wc, ws = ref.act_quant(src, group, bits)
+        assert np.array_equal(got_c.cpu().numpy(), wc)
+        assert np.array_equal(got_s.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+    got = bits_of(z)
+    assert not np.any((got & 0x7F80) == 0x7F80), "NaN or Inf in the output"
+    check_close_bf16(got, ref.silu_mul_fwd(gb, ub))
+
+
+def test_forward_then_backward_round_trip(agoq, ref):
+    # what the backward recompute returns is the forward output of the dequantized input
+    rows, cols, group, bits = 48, 4096, 128, 4
+    x = wl.act_host(rows, cols, 77, "normal", 20, 30.0)
+    gamma = np.ones(cols, np.float32)
+    y, r, codes, scales = agoq.rmsnorm_fwd_quant(dev_bf16(x), torch.from_numpy(gamma).cuda(), 1e-5, group, bits)
+    y2, r2 = agoq.act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, torch.from_numpy(gamma).cuda(), 1e-5)
+    torch.cuda.synchronize()
+    xd = ref.act_dequant(*ref.act_quant(x, group, bits), rows * cols, group, bits)
+    want_y2, want_r2 = ref.rmsnorm_fwd(xd, rows, cols, gamma, 1e-5)
+    assert np.allclose(r2.cpu().numpy(), want_r2, rtol=2e-6)
+    check_close_bf16(bits_of(y2), want_y2)
+    # 4-bit storage perturbs the normalized output by a bounded amount (step/2 per element / r)
+    a = y.float().cpu().numpy()
+    b = y2.float().cpu().numpy()
+    assert np.abs(a - b).max() < 0.5 * 30 * 6 / 7          # outlier channel: amax ~ 30 * 5 sigma over qmax
+    assert np.median(np.abs(a - b)) < 0.3
+
+
+def test_forward_fused_error_codes(agoq):
+    import ctypes
+    L = agoq.load_library()
+    P = ctypes.c_void_p
+    x = torch.zeros(8 * 1024, dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros(8 * 1024, dtype=torch.bfloat16, device="cuda")
+    gm = torch.ones(1024, dtype=torch.float32, device="cuda")
+    c = torch.zeros(8 * 1024, dtype=torch.uint8, device="cuda")
+    s = torch.zeros(128, dtype=torch.float32, device="cuda")
+    px, py, pg, pc, ps = (P(t.data_ptr()) for t in (x, y, gm, c, s))
+    f = ctypes.c_float(1e-5)
+    assert L.agoq_rmsnorm_fwd_quant(None, 8, 1024, pg, f, 128, 4, py, None, pc, ps, None) == 1
+    assert L.agoq_rmsnorm_fwd_quant(px, 8, 1024, pg, f, 128, 7, py, None, pc, ps, None) == 2
+    assert L.agoq_rmsnorm_fwd_quant(px, 8, 1024, pg, f, 96, 4, py, None, pc, ps, None) == 3
+    assert L.agoq_rmsnorm_fwd_quant(px, 8, 1000, pg, f, 128, 4, py, None, pc, ps, None) == 4
+    assert L.agoq_rmsnorm_fwd_quant(px, 8, 1024, pg, f, 128, 4, P(y.data_ptr() + 2), None, pc, ps, None) == 5
+    assert L.agoq_silu_mul_fwd_quant(px, None, 1024, 128, 4, 4, py, pc, ps, pc, ps, None) == 1
+    assert L.agoq_silu_mul_fwd_quant(px, px, 1024, 128, 4, 9, py, pc, ps, pc, ps, None) == 2
+    assert L.agoq_silu_mul_fwd_quant(px, px, 1000, 128, 4, 4, py, pc, ps, pc, ps, None) == 4
+    torch.cuda.synchronize()
+    assert not bool(y.view(torch.int16).any()) and not bool(c.any())
