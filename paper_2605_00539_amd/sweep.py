@@ -61,7 +61,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--launches", type=int, default=200)
     ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--configs", default="1,2,3,4,5",
+                    help="comma-separated configuration numbers to run (default: all five)")
     args = ap.parse_args()
+    wanted = {int(c) for c in args.configs.split(",")}
     import workloads as wl
 
     import ctypes
@@ -239,53 +242,61 @@ def main():
 
     C = wl.CONFIGS
     # config 1: tiny (launch-latency bound; parity case, reported for completeness)
-    c = C["tiny"]
-    act_case("1-tiny", "act", c["act"]["rows"], c["act"]["cols"], "normal",
-             c["act"]["outlier_channels"] / c["act"]["cols"], c["act"]["outlier_scale"], c["seed"],
-             [c["group"]], [c["bits"]])
-    grad_case("1-tiny", c["grad"]["n"], c["grad"]["sigma"], 0.0, 1.0, 1, c["K"], c["group"], share=False)
+    if 1 in wanted:
+        c = C["tiny"]
+        act_case("1-tiny", "act", c["act"]["rows"], c["act"]["cols"], "normal",
+                 c["act"]["outlier_channels"] / c["act"]["cols"], c["act"]["outlier_scale"], c["seed"],
+                 [c["group"]], [c["bits"]])
+        grad_case("1-tiny", c["grad"]["n"], c["grad"]["sigma"], 0.0, 1.0, 1, c["K"], c["group"], share=False)
     # config 2: LLaMA-8B-shaped activations
-    c = C["llama8b_act"]
-    for name, sh in c["acts"].items():
-        act_case("2-8B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
-                 c["outlier_scale"], c["seed"], [c["group"]], [4, 8], fp=True)
+    if 2 in wanted:
+        c = C["llama8b_act"]
+        for name, sh in c["acts"].items():
+            act_case("2-8B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
+                     c["outlier_scale"], c["seed"], [c["group"]], [4, 8], fp=True)
     # config 3: LLaMA-8B-shaped gradients, K = 8
-    c = C["llama8b_grad"]
-    grad_case("3-8B-grad", c["n"], c["sigma"], c["spike_frac"], c["spike_scale"], c["seed"], c["K"], c["group"],
-              fp8=True)
+    if 3 in wanted:
+        c = C["llama8b_grad"]
+        grad_case("3-8B-grad", c["n"], c["sigma"], c["spike_frac"], c["spike_scale"], c["seed"], c["K"],
+                  c["group"], fp8=True)
     # config 4: 32B-shaped activations, both group sizes
-    c = C["llama32b_act"]
-    for name, sh in c["acts"].items():
-        act_case("4-32B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
-                 c["outlier_scale"], c["seed"], list(c["groups"]), [4, 8])
+    if 4 in wanted:
+        c = C["llama32b_act"]
+        for name, sh in c["acts"].items():
+            act_case("4-32B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
+                     c["outlier_scale"], c["seed"], list(c["groups"]), [4, 8])
     # config 5: stage sweep at seq 8192, K = 16
-    c = C["stage_sweep"]
-    per = {}
-    for name, cols in (("H", c["hidden"]), ("F", c["ffn"])):
-        before = len(rows)
-        act_case("5-stage", name, c["rows"], cols, c["dist"], c["outlier_frac"], c["outlier_scale"],
-                 c["seed"], [c["group"]], [4, 5, 6, 8], fused=True)
-        for r in rows[before:]:
-            per[(name, r["kernel"], int(r["case"].split(" b")[1].split()[0]))] = r
-    gcfg = c["grad"]
-    grad_case("5-stage", gcfg["n"], gcfg["sigma"], gcfg["spike_frac"], gcfg["spike_scale"], c["seed"], c["K"], c["group"])
-    # whole-layer figures per stage bit map (sum of the five tensors' launches)
-    bf16_bytes = c["rows"] * (3 * c["hidden"] + 2 * c["ffn"]) * 2
-    for stage in (1, 2, 3, 4):
-        b = agoq.dbca_bits(4, stage)
-        for native in (True, False):
-            bitmap = agoq.layer_bitmap(b, native=native)
-            if not native and bitmap == agoq.layer_bitmap(b, native=True):
-                continue
-            stored = agoq.layer_stored_bytes(c["rows"], c["hidden"], c["ffn"], c["group"], bitmap, True)
-            for kernel in ("act_quant", "act_dequant"):
-                us = nb = 0.0
-                for slot, bits in enumerate(bitmap):
-                    r = per[("F" if slot >= 3 else "H", kernel, bits)]
-                    us += r["us"]
-                    nb += r["algo_MB"] * 1e6
-                report("5-stage", kernel + "_layer", "stage %d (B=%d) map %s stored %d B (%.1f%% saved vs bf16)" %
-                       (stage, b, bitmap, stored, 100.0 * (1 - stored / bf16_bytes)), us, nb)
+    if 5 in wanted:
+        c = C["stage_sweep"]
+        per = {}
+        for name, cols in (("H", c["hidden"]), ("F", c["ffn"])):
+            before = len(rows)
+            act_case("5-stage", name, c["rows"], cols, c["dist"], c["outlier_frac"], c["outlier_scale"],
+                     c["seed"], [c["group"]], [4, 5, 6, 8], fused=True)
+            for r in rows[before:]:
+                if r["kernel"] in ("act_quant", "act_dequant"):
+                    per[(name, r["kernel"], int(r["case"].split(" b")[1].split()[0]))] = r
+        gcfg = c["grad"]
+        grad_case("5-stage", gcfg["n"], gcfg["sigma"], gcfg["spike_frac"], gcfg["spike_scale"], c["seed"],
+                  c["K"], c["group"])
+        # whole-layer figures per stage bit map (sum of the five tensors' launches)
+        bf16_bytes = c["rows"] * (3 * c["hidden"] + 2 * c["ffn"]) * 2
+        for stage in (1, 2, 3, 4):
+            b = agoq.dbca_bits(4, stage)
+            for native in (True, False):
+                bitmap = agoq.layer_bitmap(b, native=native)
+                if not native and bitmap == agoq.layer_bitmap(b, native=True):
+                    continue
+                stored = agoq.layer_stored_bytes(c["rows"], c["hidden"], c["ffn"], c["group"], bitmap, True)
+                for kernel in ("act_quant", "act_dequant"):
+                    us = nb = 0.0
+                    for slot, bits in enumerate(bitmap):
+                        r = per[("F" if slot >= 3 else "H", kernel, bits)]
+                        us += r["us"]
+                        nb += r["algo_MB"] * 1e6
+                    report("5-stage", kernel + "_layer",
+                           "stage %d (B=%d) map %s stored %d B (%.1f%% saved vs bf16)" %
+                           (stage, b, bitmap, stored, 100.0 * (1 - stored / bf16_bytes)), us, nb)
     print(json.dumps(rows))
     return 0
 
