@@ -727,6 +727,35 @@ int agoq_ref_fp8_grad_reduce_requant(const uint8_t *in_codes, int64_t stride_cod
     return REF_OK;
 }
 
+/* local accumulation on E4M3 codes: acc = fma(decode(code), scale, g_new), requantize */
+int agoq_ref_fp8_grad_accumulate(const uint8_t *main_codes, const float *main_scales,
+                                 const void *g_new, int new_is_bf16, int64_t numel, int group,
+                                 uint8_t *out_codes, float *out_scales)
+{
+    if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales)
+        return REF_ERR_NULL;
+    int rc = check_shape(numel, group, 8);
+    if (rc)
+        return rc;
+    const int64_t n_groups = numel / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < n_groups; ++g) {
+        float acc[4096];
+        for (int j = 0; j < group; ++j) {
+            const int64_t i = g * group + j;
+            const float addend = new_is_bf16 ? bf16_bits_to_f32(((const uint16_t *)g_new)[i])
+                                             : ((const float *)g_new)[i];
+            acc[j] = fmaf(e4m3_decode(main_codes[i]), main_scales[g], addend);
+        }
+        float scale, inv;
+        const int live = fp_group_scale(acc, group, 448.0f, &scale, &inv);
+        out_scales[g] = scale;
+        for (int j = 0; j < group; ++j)
+            out_codes[g * group + j] = live ? e4m3_encode(acc[j] * inv) : 0;
+    }
+    return REF_OK;
+}
+
 /* ---- Dynamic Bit-width Compensation (Eq. "dynamic") --------------------- */
 
 /*

@@ -13,7 +13,7 @@ from . import build as _build
 
 __all__ = [
     "lib", "rmsnorm_fwd", "silu_mul_fwd", "fp4_act_quant", "fp4_act_dequant", "fp8_grad_quant", "fp8_grad_dequant",
-    "fp8_grad_reduce_requant", "e2m1_encode", "e2m1_decode", "e4m3_encode", "e4m3_decode", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
+    "fp8_grad_reduce_requant", "fp8_grad_accumulate", "e2m1_encode", "e2m1_decode", "e4m3_encode", "e4m3_decode", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
     "grad_reduce_requant", "grad_reduce_f64", "grad_accumulate", "dbca_bits",
     "dbca_stored_microbatches", "bf16_to_f32", "f32_to_bf16", "max_threads",
     "set_threads", "OracleError", "Oracle",
@@ -48,6 +48,7 @@ def _bind(path):
     L.agoq_ref_fp8_grad_quant.argtypes = [_P, _I64, _INT, _P, _P]
     L.agoq_ref_fp8_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P]
     L.agoq_ref_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P]
+    L.agoq_ref_fp8_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P]
     for name in ("e2m1", "e4m3"):
         enc = getattr(L, "agoq_ref_%s_encode" % name)
         enc.argtypes = [ctypes.c_float]
@@ -202,6 +203,20 @@ class Oracle:
             group, _ptr(out_codes), _ptr(out_scales)))
         return out_codes, out_scales
 
+    def fp8_grad_accumulate(self, main_codes, main_scales, g_new, group):
+        main_codes = _c(main_codes, np.uint8).reshape(-1)
+        main_scales = _c(main_scales, np.float32).reshape(-1)
+        g_new = np.ascontiguousarray(g_new).reshape(-1)
+        if g_new.dtype not in (np.dtype(np.float32), np.dtype(np.uint16)):
+            raise TypeError("g_new must be float32 or uint16 (bf16 bits)")
+        n = main_codes.size
+        out_codes = np.zeros(n, np.uint8)
+        out_scales = np.zeros(n // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_fp8_grad_accumulate(
+            _ptr(main_codes), _ptr(main_scales), _ptr(g_new), 1 if g_new.dtype == np.uint16 else 0,
+            n, group, _ptr(out_codes), _ptr(out_scales)))
+        return out_codes, out_scales
+
     def e2m1_encode(self, t):
         return self.lib.agoq_ref_e2m1_encode(float(t))
 
@@ -304,6 +319,7 @@ fp4_act_dequant = _default.fp4_act_dequant
 fp8_grad_quant = _default.fp8_grad_quant
 fp8_grad_dequant = _default.fp8_grad_dequant
 fp8_grad_reduce_requant = _default.fp8_grad_reduce_requant
+fp8_grad_accumulate = _default.fp8_grad_accumulate
 e2m1_encode = _default.e2m1_encode
 e2m1_decode = _default.e2m1_decode
 e4m3_encode = _default.e4m3_encode

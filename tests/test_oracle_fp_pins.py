@@ -230,3 +230,54 @@ def test_fp8_reduce_uses_one_rounding_per_term(ref):
         if found >= 20:
             break
     assert found > 0
+
+
+@pytest.mark.parametrize("as_bf16", [False, True])
+def test_fp8_accumulate_matches_exact_arithmetic(ref, as_bf16):
+    group, n = 16, 64
+    rng = np.random.default_rng(77)
+    codes = rng.integers(0, 256, size=n).astype(np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x22
+    scales = (rng.random(n // group) * 1e-3).astype(np.float32)
+    g32 = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    if as_bf16:
+        t = torch.from_numpy(g32).to(torch.bfloat16)
+        g_in = t.view(torch.int16).numpy().view(np.uint16)
+        g32 = t.to(torch.float32).numpy()
+    else:
+        g_in = g32
+    acc = np.array([fraction_to_f32(e4m3_value(int(codes[i])) * f32_fraction(scales[i // group]) + f32_fraction(g32[i]))
+                    for i in range(n)], np.float32)
+    want = ref.fp8_grad_quant(acc, group)
+    got = ref.fp8_grad_accumulate(codes, scales, g_in, group)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1].view(np.uint32), want[1].view(np.uint32))
+    # accumulating onto an all-zero stored gradient is the plain store
+    z = ref.fp8_grad_accumulate(np.zeros(n, np.uint8), np.zeros(n // group, np.float32), g_in, group)
+    plain = ref.fp8_grad_quant(g32, group)
+    assert np.array_equal(z[0], plain[0]) and np.array_equal(z[1], plain[1])
+
+
+def test_fp8_accumulate_uses_one_rounding(ref):
+    table = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    rng = np.random.default_rng(12)
+    group, found = 8, 0
+    for _ in range(4000):
+        codes = rng.integers(0, 256, size=group).astype(np.uint8)
+        codes[(codes & 0x7F) == 0x7F] = 0x41
+        scale = (rng.random(1) + 0.5).astype(np.float32)
+        g = (rng.standard_normal(group) * 50).astype(np.float32)
+        v = table[codes]
+        unfused = ((v * scale[0]).astype(np.float32) + g).astype(np.float32)
+        fused = np.array([fraction_to_f32(f32_fraction(v[i]) * f32_fraction(scale[0]) + f32_fraction(g[i]))
+                          for i in range(group)], np.float32)
+        if np.array_equal(fused, unfused):
+            continue
+        want, other = ref.fp8_grad_quant(fused, group), ref.fp8_grad_quant(unfused, group)
+        if np.array_equal(want[0], other[0]) and np.array_equal(want[1], other[1]):
+            continue
+        found += 1
+        got = ref.fp8_grad_accumulate(codes, scale, g, group)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1].view(np.uint32), want[1].view(np.uint32))
+        if found >= 10:
+            break
+    assert found > 0

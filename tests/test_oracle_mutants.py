@@ -87,6 +87,10 @@ MUTANTS = [
      "a = a + v * in_scales[k * stride_scales + g];"),
     ("fp8_reduce_ignores_stride", "const float v = e4m3_decode(in_codes[k * stride_codes + e]);",
      "const float v = e4m3_decode(in_codes[k * numel + e]);"),
+    ("fp8_accumulate_two_roundings", "acc[j] = fmaf(e4m3_decode(main_codes[i]), main_scales[g], addend);",
+     "acc[j] = e4m3_decode(main_codes[i]) * main_scales[g] + addend;"),
+    ("fp8_accumulate_drops_addend", "acc[j] = fmaf(e4m3_decode(main_codes[i]), main_scales[g], addend);",
+     "acc[j] = fmaf(e4m3_decode(main_codes[i]), main_scales[g], 0.0f * addend);"),
     ("dbca_printed_index", "return 3 * n_stages - 2 * stage + 1;", "return n_stages + 2 * stage - 1;"),
     ("dbca_floor_instead_of_round", "int r = (int)floor(b + 0.5);", "int r = (int)floor(b);"),
     ("dbca_no_cap", "if (r > 8)\n        r = 8;", ""),
