@@ -215,6 +215,9 @@ int agoq_fp8_grad_reduce_requant(const uint8_t *in_codes, int64_t chunk_stride_c
                                  const float *in_scales, int64_t chunk_stride_scales, int K,
                                  int64_t numel, int group, uint8_t *out_codes, float *out_scales,
                                  void *stream);
+int agoq_fp8_grad_accumulate(const uint8_t *main_codes, const float *main_scales, const void *g_new,
+                             int g_new_is_bf16, int64_t numel, int group, uint8_t *out_codes,
+                             float *out_scales, void *stream);
 
 /* ---- host-only helpers: pure functions, no device access ---------------- */
 

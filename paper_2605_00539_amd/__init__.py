@@ -7,7 +7,7 @@ without a GPU, the calls raise.
 """
 from .binding import (AgoqError, act_dequant, act_dequant_rmsnorm, act_dequant_silu_mul, act_quant, codes_bytes, dbca_bits,
                       dbca_stored_microbatches, fp4_act_dequant, fp4_act_quant, fp8_grad_dequant,
-                      fp8_grad_quant, fp8_grad_reduce_requant, grad_accumulate, grad_dequant, grad_quant,
+                      fp8_grad_accumulate, fp8_grad_quant, fp8_grad_reduce_requant, grad_accumulate, grad_dequant, grad_quant,
                       grad_reduce_requant, rmsnorm_fwd_quant, silu_mul_fwd_quant,
                       layer_bitmap, layer_stored_bytes, library_path, load_library,
                       num_groups, strerror, version)
@@ -15,7 +15,7 @@ from .binding import (AgoqError, act_dequant, act_dequant_rmsnorm, act_dequant_s
 __all__ = [
     "AgoqError", "act_quant", "act_dequant", "grad_quant", "grad_reduce_requant",
     "grad_accumulate", "grad_dequant", "fp4_act_quant", "fp4_act_dequant", "fp8_grad_quant",
-    "fp8_grad_dequant", "fp8_grad_reduce_requant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "rmsnorm_fwd_quant", "silu_mul_fwd_quant",
+    "fp8_grad_dequant", "fp8_grad_reduce_requant", "fp8_grad_accumulate", "act_dequant_rmsnorm", "act_dequant_silu_mul", "rmsnorm_fwd_quant", "silu_mul_fwd_quant",
     "codes_bytes", "num_groups", "dbca_bits", "dbca_stored_microbatches", "layer_bitmap",
     "layer_stored_bytes", "strerror", "version", "load_library", "library_path",
 ]

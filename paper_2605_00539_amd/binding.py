@@ -50,6 +50,7 @@ def load_library():
     L.agoq_fp8_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
     L.agoq_fp8_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
     L.agoq_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
+    L.agoq_fp8_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_codes_bytes.argtypes = [_I64, _INT]
     L.agoq_codes_bytes.restype = _I64
     L.agoq_num_groups.argtypes = [_I64, _INT]
@@ -414,6 +415,31 @@ def fp8_grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, o
         _check(L.agoq_fp8_grad_reduce_requant(
             _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
             in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),
+            _raw(out_scales.data_ptr()), _stream(stream)))
+    return out_codes, out_scales
+
+
+def fp8_grad_accumulate(main_codes, main_scales, g_new, group, out_codes=None, out_scales=None,
+                        stream=None):
+    """E4M3 form of grad_accumulate; in place when out_codes / out_scales are left None."""
+    import torch
+    L = load_library()
+    _dev(main_codes, torch.uint8, "main_codes")
+    _dev(main_scales, torch.float32, "main_scales")
+    if not isinstance(g_new, torch.Tensor) or g_new.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("g_new must be a float32 or bfloat16 tensor")
+    _dev(g_new, g_new.dtype, "g_new")
+    n = main_codes.numel()
+    if g_new.numel() != n:
+        raise ValueError("g_new must have as many elements as main_codes")
+    out_codes = main_codes if out_codes is None else out_codes
+    out_scales = main_scales if out_scales is None else out_scales
+    _dev(out_codes, torch.uint8, "out_codes")
+    _dev(out_scales, torch.float32, "out_scales")
+    with _on_device(main_codes.device):
+        _check(L.agoq_fp8_grad_accumulate(
+            _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
+            1 if g_new.dtype == torch.bfloat16 else 0, n, group, _raw(out_codes.data_ptr()),
             _raw(out_scales.data_ptr()), _stream(stream)))
     return out_codes, out_scales
 

@@ -159,7 +159,7 @@ __global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_kernel(const int8_t
 //   fp32 addend: lane layout of grad_quant_kernel (one DPP row per group).
 //   bf16 addend: lane layout of act_quant_kernel (8 elements per lane).
 // ---------------------------------------------------------------------------
-template <int GROUP, int UNROLL>
+template <int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
     const u32* main_codes, const float* main_scales, const f32x4* __restrict__ g_new,
     int64_t n_groups, u32* out_codes, float* out_scales)
@@ -194,21 +194,23 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
         float acc[VPL][4];
         u32 m = 0;
 #pragma unroll
-        for (int p = 0; p < VPL; ++p)
+        for (int p = 0; p < VPL; ++p) {
+            float q[4];
+            decode4_bytes<FP>(c[u][p], q);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                acc[p][j] = __fmaf_rn(byte_to_f32(c[u][p], j), s[u], v[u][p][j]);
+                acc[p][j] = __fmaf_rn(q[j], s[u], v[u][p][j]);
                 m = umax(m, as_u32(acc[p][j]) & 0x7FFFFFFFu);
             }
+        }
         m = group_max_bits<16>(m);
         float scale, inv;
-        scale_and_inv<127>(m, scale, inv);
+        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (grp < n_groups) {
 #pragma unroll
             for (int p = 0; p < VPL; ++p) {
-                u32 w = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) w = push_byte(w, code_bits(acc[p][j], inv));
+                u32 w = encode4_bytes<FP>(acc[p][0], acc[p][1], acc[p][2], acc[p][3], inv);
+                if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
                 st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
             }
             if (lane16 == 0) st<true>(out_scales + grp, scale);
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
     }
 }
 
-template <int GROUP, int UNROLL>
+template <int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
     const u32x2* main_codes, const float* main_scales, const u32x4* __restrict__ g_new,
     int64_t n_vec, u32x2* out_codes, float* out_scales)
@@ -243,24 +245,24 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        float acc[8];
+        float acc[8], g[8], q0[4], q1[4];
+        unpack8_bf16(v[u], g);
+        decode4_bytes<FP>(c[u][0], q0);
+        decode4_bytes<FP>(c[u][1], q1);
         u32 m = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const u32 w = v[u][j >> 1];
-            const float g = as_f32((j & 1) ? (w & 0xFFFF0000u) : (w << 16));
-            acc[j] = __fmaf_rn(byte_to_f32(c[u][j >> 2], j & 3), s[u], g);
-            m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
+        for (int j = 0; j < 4; ++j) {
+            acc[j] = __fmaf_rn(q0[j], s[u], g[j]);
+            acc[4 + j] = __fmaf_rn(q1[j], s[u], g[4 + j]);
+            m = umax(m, umax(as_u32(acc[j]) & 0x7FFFFFFFu, as_u32(acc[4 + j]) & 0x7FFFFFFFu));
         }
         m = group_max_bits<LANES>(m);
         float scale, inv;
-        scale_and_inv<127>(m, scale, inv);
+        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (vi < n_vec) {
-            u32 p0 = 0, p1 = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(acc[j], inv));
-#pragma unroll
-            for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(acc[j], inv));
+            u32 p0 = encode4_bytes<FP>(acc[0], acc[1], acc[2], acc[3], inv);
+            u32 p1 = encode4_bytes<FP>(acc[4], acc[5], acc[6], acc[7], inv);
+            if (FP && scale == 0.0f) p0 = p1 = 0;              // dead group: no signed zeros
             st<true>(out_codes + vi, u32x2{p0, p1});
             if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
         }
@@ -302,6 +304,46 @@ __global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* 
         for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(q[j], s[u]);
         if (vi < n_vec) st<AGOQ_GD_NTS>(out + vi, o);
     }
+}
+
+// Validation and launch shared by the int8 and E4M3 forms of the local accumulation.
+template <bool FP>
+int launch_accumulate(const void* main_codes, const float* main_scales, const void* g_new,
+                      int g_new_is_bf16, int64_t numel, int group, void* out_codes,
+                      float* out_scales, void* stream)
+{
+    if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(main_codes) || misaligned(main_scales) || misaligned(g_new) ||
+        misaligned(out_codes) || misaligned(out_scales))
+        return AGOQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (g_new_is_bf16) {
+        const int64_t n_vec = numel / 8;
+        constexpr int U = AGOQ_AQ_UNROLL;
+        const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+        if (group == 128)
+            grad_accumulate_bf16_kernel<128, U, FP><<<grid, block, 0, st>>>(
+                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                (u32x2*)out_codes, out_scales);
+        else
+            grad_accumulate_bf16_kernel<64, U, FP><<<grid, block, 0, st>>>(
+                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                (u32x2*)out_codes, out_scales);
+    } else {
+        const int64_t n_groups = numel / group;
+        constexpr int U = AGOQ_GQ_UNROLL;
+        const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
+        if (group == 128)
+            grad_accumulate_f32_kernel<128, U, FP><<<grid, block, 0, st>>>(
+                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
+                (u32*)out_codes, out_scales);
+        else
+            grad_accumulate_f32_kernel<64, U, FP><<<grid, block, 0, st>>>(
+                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
+                (u32*)out_codes, out_scales);
+    }
+    return launch_status();
 }
 
 }  // namespace
@@ -369,38 +411,16 @@ int agoq_grad_accumulate(const int8_t* main_codes, const float* main_scales, con
                          int g_new_is_bf16, int64_t numel, int group, int8_t* out_codes,
                          float* out_scales, void* stream)
 {
-    if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (misaligned(main_codes) || misaligned(main_scales) || misaligned(g_new) ||
-        misaligned(out_codes) || misaligned(out_scales))
-        return AGOQ_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)stream;
-    if (g_new_is_bf16) {
-        const int64_t n_vec = numel / 8;
-        constexpr int U = AGOQ_AQ_UNROLL;
-        const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
-        if (group == 128)
-            grad_accumulate_bf16_kernel<128, U><<<grid, block, 0, st>>>(
-                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
-                (u32x2*)out_codes, out_scales);
-        else
-            grad_accumulate_bf16_kernel<64, U><<<grid, block, 0, st>>>(
-                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
-                (u32x2*)out_codes, out_scales);
-    } else {
-        const int64_t n_groups = numel / group;
-        constexpr int U = AGOQ_GQ_UNROLL;
-        const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
-        if (group == 128)
-            grad_accumulate_f32_kernel<128, U><<<grid, block, 0, st>>>(
-                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
-                (u32*)out_codes, out_scales);
-        else
-            grad_accumulate_f32_kernel<64, U><<<grid, block, 0, st>>>(
-                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
-                (u32*)out_codes, out_scales);
-    }
-    return launch_status();
+    return launch_accumulate<false>(main_codes, main_scales, g_new, g_new_is_bf16, numel, group,
+                                    out_codes, out_scales, stream);
+}
+
+int agoq_fp8_grad_accumulate(const uint8_t* main_codes, const float* main_scales, const void* g_new,
+                             int g_new_is_bf16, int64_t numel, int group, uint8_t* out_codes,
+                             float* out_scales, void* stream)
+{
+    return launch_accumulate<true>(main_codes, main_scales, g_new, g_new_is_bf16, numel, group,
+                                   out_codes, out_scales, stream);
 }
 
 int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, int group,

@@ -173,3 +173,32 @@ def test_fp_error_codes(agoq):
     assert L.agoq_fp8_grad_reduce_requant(pc, 1032, ps, 8, 2, 1024, 128, pc, ps, None) == 5
     torch.cuda.synchronize()
     assert bool((c == 7).all()) and bool((s == 3.0).all())
+
+
+@pytest.mark.parametrize("as_bf16", [False, True])
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("n_groups", [1, 17, 4 * 32 + 3, 30011])
+def test_fp8_gradient_accumulate(agoq, ref, group, n_groups, as_bf16):
+    n = n_groups * group
+    base = wl.grad_host(n, 7100 + n_groups, 1e-4, 0.001, 100.0)
+    main_c, main_s = ref.fp8_grad_quant(base, group)
+    g32 = wl.grad_host(n, 7200 + n_groups, 1e-4, 0.001, 100.0)
+    if n_groups > 8:
+        g32[group * 2: group * 3] = 0.0
+        main_c[group * 2: group * 3] = 0x80                   # -0 + 0: a dead group with signed zeros
+        g32[group * 5: group * 6] = -ref.fp8_grad_dequant(main_c, main_s, group)[group * 5: group * 6]
+    if as_bf16:
+        t = torch.from_numpy(g32).to(torch.bfloat16)
+        g_host = t.view(torch.int16).numpy().view(np.uint16)
+        g_dev = t.cuda()
+    else:
+        g_host, g_dev = g32, torch.from_numpy(g32).cuda()
+    want = ref.fp8_grad_accumulate(main_c, main_s, g_host, group)
+    d_c, d_s = torch.from_numpy(main_c).cuda(), torch.from_numpy(main_s).cuda()
+    out_c, out_s = torch.empty_like(d_c), torch.empty_like(d_s)
+    agoq.fp8_grad_accumulate(d_c, d_s, g_dev, group, out_codes=out_c, out_scales=out_s)
+    torch.cuda.synchronize()
+    assert same_f32(out_s.cpu().numpy(), want[1]) and np.array_equal(out_c.cpu().numpy(), want[0])
+    agoq.fp8_grad_accumulate(d_c, d_s, g_dev, group)          # in place
+    torch.cuda.synchronize()
+    assert same_f32(d_s.cpu().numpy(), want[1]) and np.array_equal(d_c.cpu().numpy(), want[0])
