@@ -159,3 +159,21 @@ def test_step_captured_in_a_hip_graph(agoq, ref):
         r_c, r_s = ref.grad_reduce_requant(np.stack([p[0] for p in pairs]), np.stack([p[1] for p in pairs]), ng, group)
         a_c, a_s = ref.grad_accumulate(r_c, r_s, gh, group)
         assert np.array_equal(rc.cpu().numpy(), a_c) and np.array_equal(rs.cpu().numpy().view(np.uint32), a_s.view(np.uint32))
+
+
+def test_c_abi_from_a_torch_free_client():
+    """tests/native/cabi_check (built by __graft_entry__.build()) drives the library with
+    hipMalloc'd memory and compares with the oracle it links; no Python, no torch in that process."""
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    exe = os.path.join(here, "native", "cabi_check")
+    if not os.path.exists(exe):
+        import sys
+        sys.path.insert(0, os.path.dirname(here))
+        import __graft_entry__
+        exe = __graft_entry__.build_native_check()
+    proc = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert proc.returncode == 0, proc.stdout
+    assert "all C-ABI checks passed" in proc.stdout
+    assert proc.stdout.count("match") == 10
