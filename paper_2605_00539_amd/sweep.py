@@ -51,6 +51,25 @@ def timed(fn, launches, reps):
     return out[len(out) // 2]
 
 
+def timed_wall(fn, launches, reps):
+    """Host-clock variant for launches that go to more than one stream (events on one stream
+    would not see the others): device-wide synchronization on both sides of the loop."""
+    import time
+    for i in range(min(10, launches)):
+        fn(i)
+    torch.cuda.synchronize()
+    out = []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(launches):
+            fn(i)
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) * 1e6 / launches)
+    out.sort()
+    return out[len(out) // 2]
+
+
 def slots_for(bytes_each, floor=2, cap=128):
     """Buffers needed for a 1.5 GiB rotation, at most `cap` (tiny tensors stay cache-resident
     whatever the rotation; they measure launch latency, not bandwidth)."""
@@ -110,6 +129,19 @@ def main():
                 report(config, "act_quant", case, us, nb)
                 us = timed(lambda i: L.agoq_act_dequant(*da[i % len(da)]), args.launches, args.reps)
                 report(config, "act_dequant", case, us, nb)
+                if 2 * n <= (64 << 20):
+                    # small tensors: each launch lasts under 13 us, about 3 of which are the dispatch
+                    # gap between dependent launches of one stream.  Alternating two streams lets
+                    # one kernel's ramp overlap the other's drain and shows the kernel's own rate.
+                    two = [torch.cuda.Stream(), torch.cuda.Stream()]
+                    sp = [P(t.cuda_stream) for t in two]
+                    for t in two:
+                        t.wait_stream(torch.cuda.current_stream())
+                    us = timed_wall(lambda i: L.agoq_act_quant(*qa[i % len(qa)][:6], sp[i & 1]), 2 * args.launches, args.reps)
+                    report(config, "act_quant (2 streams)", case, us, nb)
+                    us = timed_wall(lambda i: L.agoq_act_dequant(*da[i % len(da)][:6], sp[i & 1]), 2 * args.launches, args.reps)
+                    report(config, "act_dequant (2 streams)", case, us, nb)
+                    torch.cuda.synchronize()
                 if fp and bits == 4:
                     us = timed(lambda i: L.agoq_fp4_act_quant(qa[i % len(qa)][0], n, group, qa[i % len(qa)][4],
                                                               qa[i % len(qa)][5], st), args.launches, args.reps)
