@@ -4,11 +4,12 @@
 One "step" is one pass of the whole path over the LLaMA-8B-shaped workload:
   * quantize the five stored activations of a decoder layer (seq 4096, micro-batch 1:
     three [4096,4096] and two [4096,14336] bf16 tensors) under the bit map
-    norm inputs 8-bit, linear / FFN-intermediate inputs 4-bit, group 128;
+    norm inputs 8-bit, linear / FFN-intermediate inputs 4-bit, group 128 (one launch for
+    the layer);
   * store one decoder layer's fp32 gradient (218,103,808 elements) as int8, group 128;
   * local reduce + requantize of K=8 such int8 gradients (the receive buffer of the
     All-to-All), n = 218,103,808;
-  * dequantize the five stored activations back to bf16.
+  * dequantize the five stored activations back to bf16 (one launch).
 The order puts ~3 GB of gradient traffic between writing the activation codes and reading
 them back, so no launch finds its input in the last-level cache.
 
@@ -123,6 +124,9 @@ def main():
     bytes_step = bytes_quant + bytes_dequant + bytes_gq + bytes_red
 
     stream = torch.cuda.current_stream()
+    # descriptor arrays of the two layer launches (host memory, marshalled once)
+    q_slots = agoq.layer_slots(acts, act_bits, act_codes, act_scales)
+    d_slots = agoq.layer_slots(act_out, act_bits, act_codes, act_scales)
 
     def step(ev=None):
         """One pass of the path.  ev: optional dict of per-kernel-class event lists."""
@@ -132,16 +136,15 @@ def main():
                 e.record(stream)
                 ev[name].append(e)
         mark("t0")
-        for x, b, c, s in zip(acts, act_bits, act_codes, act_scales):
-            agoq.act_quant(x, GROUP, b, codes=c, scales=s, stream=stream)
+        agoq.act_quant_layer(acts, GROUP, act_bits, slots=q_slots, stream=stream)
         mark("t1")
         agoq.grad_quant(grad, GROUP, codes=g_codes, scales=g_scales, stream=stream)
         mark("t2")
         agoq.grad_reduce_requant(in_codes, in_scales, n_grad, GROUP, out_codes=r_codes,
                                  out_scales=r_scales, stream=stream)
         mark("t3")
-        for x, b, c, s, y in zip(acts, act_bits, act_codes, act_scales, act_out):
-            agoq.act_dequant(c, s, x.numel(), GROUP, b, out=y, stream=stream)
+        agoq.act_dequant_layer(act_codes, act_scales, None, GROUP, act_bits, outs=act_out,
+                               slots=d_slots, stream=stream)
         mark("t4")
 
     # ---- warm-up, then the timed region -------------------------------------------------
@@ -153,8 +156,7 @@ def main():
     red_events = []
     t_start = time.perf_counter()
     for _ in range(args.steps):
-        for x, b, c, s in zip(acts, act_bits, act_codes, act_scales):
-            agoq.act_quant(x, GROUP, b, codes=c, scales=s, stream=stream)
+        agoq.act_quant_layer(acts, GROUP, act_bits, slots=q_slots, stream=stream)
         agoq.grad_quant(grad, GROUP, codes=g_codes, scales=g_scales, stream=stream)
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -163,8 +165,8 @@ def main():
                                  out_scales=r_scales, stream=stream)
         e1.record(stream)
         red_events.append((e0, e1))
-        for x, b, c, s, y in zip(acts, act_bits, act_codes, act_scales, act_out):
-            agoq.act_dequant(c, s, x.numel(), GROUP, b, out=y, stream=stream)
+        agoq.act_dequant_layer(act_codes, act_scales, None, GROUP, act_bits, outs=act_out,
+                               slots=d_slots, stream=stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
@@ -232,10 +234,9 @@ def main():
 
 def cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_codes, g_scales,
                  in_codes, in_scales, r_codes, r_scales, n_grad):
-    """Time the oracle (as it stands) on the host, on a bounded sample of the step's inputs:
-    all five activations (quant + dequant), the first 1/4 of the gradient (grad quant), and
-    the first 1/16 of the 8 int8 chunks (reduce).  Also checks the GPU outputs of the last
-    step against the oracle on that sample."""
+    """Time the oracle (as it stands) on the host, with all its threads, on one whole step of
+    the same inputs (a few seconds of work), and check the GPU outputs of the last timed
+    step against it, every byte.  A one-thread figure on 1/16 of the step follows."""
     import numpy as np
     import oracle
 
@@ -270,8 +271,25 @@ def cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_
     nbytes += algo_bytes_reduce(nr, K_CHUNKS)
     ok &= np.array_equal(r_codes[:nr].cpu().numpy(), oc) and np.array_equal(
         r_scales[:nr // GROUP].cpu().numpy().view(np.uint32), os_.view(np.uint32))
+    # one thread: the first stored activation (quantize + dequantize), 1/16 of the gradient
+    # store and 1/16 of the reduce
+    oracle.set_threads(1)
+    xb = bits_of(acts[0])
+    n16 = (n_grad // 16) // GROUP * GROUP
+    ch16 = np.ascontiguousarray(ch[:, :n16])
+    sh16 = np.ascontiguousarray(sh[:, :n16 // GROUP])
+    t = time.perf_counter()
+    oc, os_ = oracle.act_quant(xb, GROUP, act_bits[0])
+    oracle.act_dequant(oc, os_, xb.size, GROUP, act_bits[0])
+    oracle.grad_quant(gh[:n16], GROUP)
+    oracle.grad_reduce_requant(ch16, sh16, n16, GROUP)
+    secs1 = time.perf_counter() - t
+    nbytes1 = 2 * algo_bytes_act(xb.size, act_bits[0]) + algo_bytes_grad_quant(n16) + \
+        algo_bytes_reduce(n16, K_CHUNKS)
+    oracle.set_threads(threads)
     return {
         "value": round(nbytes / secs / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "one_thread_GB/s": round(nbytes1 / secs1 / 1e9, 3),
         "sample": "one whole step (5 activations quant+dequant, gradient store, 8-chunk reduce): "
                   "%.0f MB algorithmic in %.2f s wall on %d threads" % (nbytes / 1e6, secs, threads),
         "gpu_matches_oracle_on_sample": bool(ok),

@@ -56,7 +56,8 @@ enum {
     AGOQ_ERR_SHAPE = 4, /* numel <= 0, numel % group != 0, or a stride below its extent */
     AGOQ_ERR_ALIGN = 5, /* a pointer (or a chunk stride) breaks 16-byte alignment */
     AGOQ_ERR_K = 6,     /* K outside 1..64 */
-    AGOQ_ERR_HIP = 7    /* the HIP runtime refused the launch */
+    AGOQ_ERR_HIP = 7,   /* the HIP runtime refused the launch */
+    AGOQ_ERR_COUNT = 8  /* a layer call with fewer than 1 or more than AGOQ_MAX_LAYER_SLOTS tensors */
 };
 
 /*
@@ -84,6 +85,35 @@ int agoq_act_quant(const void *x_bf16, int64_t numel, int group, int bits, void 
  */
 int agoq_act_dequant(const void *codes, const float *scales, int64_t numel, int group, int bits,
                      void *y_bf16, void *stream);
+
+/*
+ * All stored tensors of one layer in one launch (paper: "Layer-Aware Activation
+ * Quantization", each stored tensor of a layer has the bit-width that the bit map gives
+ * its layer type; "Dynamic Bit-width Compensation", the map changes with the pipeline
+ * stage).  The result in every buffer is exactly that of agoq_act_quant /
+ * agoq_act_dequant called once per tensor; one launch instead of `count` saves the fixed
+ * cost of a launch, which is a third of the run time of a 32 MiB tensor.
+ *   slots : in, HOST array of `count` descriptors, read before the call returns (the
+ *           caller may free or reuse it at once); every pointer inside is a device
+ *           pointer with the meaning, size, alignment and ownership of the matching
+ *           single-tensor argument: for quantize `bf16` is the input and `codes`, `scales`
+ *           are written; for dequantize `codes`, `scales` are the inputs and `bf16` is
+ *           written
+ *   count : 1..AGOQ_MAX_LAYER_SLOTS, else AGOQ_ERR_COUNT
+ *   group : one group size for the whole call
+ * Tensors must not overlap each other.  Any invalid slot fails the whole call with the
+ * error the single-tensor call would give, and nothing is enqueued.
+ */
+enum { AGOQ_MAX_LAYER_SLOTS = 8 };
+typedef struct agoq_act_slot {
+    void *bf16;     /* numel bf16 values */
+    void *codes;    /* numel*bits/8 bytes */
+    float *scales;  /* numel/group fp32 */
+    int64_t numel;
+    int bits;       /* 4, 5, 6 or 8 */
+} agoq_act_slot;
+int agoq_act_quant_layer(const agoq_act_slot *slots, int count, int group, void *stream);
+int agoq_act_dequant_layer(const agoq_act_slot *slots, int count, int group, void *stream);
 
 /*
  * Dequantize a stored RMSNorm input and recompute the layer's forward from it (paper:

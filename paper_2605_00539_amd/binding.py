@@ -10,6 +10,12 @@ _I64 = ctypes.c_int64
 _INT = ctypes.c_int
 _P = ctypes.c_void_p
 _SLOTS = 5
+MAX_LAYER_SLOTS = 8
+
+
+class ActSlot(ctypes.Structure):
+    """agoq_act_slot: one stored tensor of a layer call (device pointers)."""
+    _fields_ = [("bf16", _P), ("codes", _P), ("scales", _P), ("numel", _I64), ("bits", _INT)]
 
 
 class AgoqError(RuntimeError):
@@ -37,6 +43,8 @@ def load_library():
     L = ctypes.CDLL(_LIB_PATH)
     L.agoq_act_quant.argtypes = [_P, _I64, _INT, _INT, _P, _P, _P]
     L.agoq_act_dequant.argtypes = [_P, _P, _I64, _INT, _INT, _P, _P]
+    L.agoq_act_quant_layer.argtypes = [ctypes.POINTER(ActSlot), _INT, _INT, _P]
+    L.agoq_act_dequant_layer.argtypes = [ctypes.POINTER(ActSlot), _INT, _INT, _P]
     L.agoq_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
     L.agoq_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _INT, _P, ctypes.c_float, _P, _P, _P]
@@ -152,6 +160,65 @@ def act_dequant(codes, scales, numel, group, bits, out=None, stream=None):
         _check(L.agoq_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
                                   bits, _raw(out.data_ptr()), _stream(stream)))
     return out
+
+
+def layer_slots(xs, bits_list, codes_list, scales_list):
+    """Descriptor array (host memory) for a layer call from lists of device tensors: xs bf16,
+    codes_list uint8, scales_list float32, bits_list ints.  Reusable across calls for as long as
+    the tensors live."""
+    import torch
+    count = len(xs)
+    if not (len(bits_list) == len(codes_list) == len(scales_list) == count):
+        raise ValueError("layer call: the four lists must have one entry per tensor")
+    arr = (ActSlot * max(count, 1))()
+    for i, (x, b, c, s) in enumerate(zip(xs, bits_list, codes_list, scales_list)):
+        _dev(x, torch.bfloat16, "bf16[%d]" % i)
+        _dev(c, torch.uint8, "codes[%d]" % i)
+        _dev(s, torch.float32, "scales[%d]" % i)
+        if c.device != x.device or s.device != x.device:
+            raise ValueError("layer call: all tensors must be on one device")
+        arr[i] = ActSlot(x.data_ptr(), c.data_ptr(), s.data_ptr(), x.numel(), int(b))
+    return arr, count
+
+
+def act_quant_layer(xs, group, bits_list, codes_list=None, scales_list=None, slots=None, stream=None):
+    """Quantize all stored tensors of a layer in one launch.  xs: list of bf16 tensors;
+    bits_list: the bit map.  Returns (codes_list, scales_list).  `slots` = a descriptor array
+    from layer_slots() to skip the marshalling on repeated calls."""
+    import torch
+    L = load_library()
+    if slots is None:
+        if codes_list is None:
+            codes_list = [torch.empty(max(x.numel() * b // 8, 1), dtype=torch.uint8, device=x.device)
+                          for x, b in zip(xs, bits_list)]
+        if scales_list is None:
+            scales_list = [torch.empty(max(x.numel() // max(group, 1), 1), dtype=torch.float32,
+                                       device=x.device) for x in xs]
+        slots = layer_slots(xs, bits_list, codes_list, scales_list)
+    arr, count = slots
+    with _on_device(xs[0].device):
+        _check(L.agoq_act_quant_layer(arr, count, group, _stream(stream)))
+    return codes_list, scales_list
+
+
+def act_dequant_layer(codes_list, scales_list, numels, group, bits_list, outs=None, slots=None,
+                      stream=None):
+    """Dequantize all stored tensors of a layer in one launch.  Returns the list of flat bf16
+    outputs."""
+    import torch
+    L = load_library()
+    if slots is None:
+        if outs is None:
+            outs = [torch.empty(n, dtype=torch.bfloat16, device=c.device)
+                    for n, c in zip(numels, codes_list)]
+        for n, o in zip(numels, outs):
+            if o.numel() != n:
+                raise ValueError("layer call: output size differs from numel")
+        slots = layer_slots(outs, bits_list, codes_list, scales_list)
+    arr, count = slots
+    with _on_device(codes_list[0].device):
+        _check(L.agoq_act_dequant_layer(arr, count, group, _stream(stream)))
+    return outs
 
 
 def act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, gamma, eps, out=None, r_out=None,

@@ -11,15 +11,15 @@ namespace {
 // the low nibbles exactly where 4-bit codes would go, the remaining high bits
 // (one byte or two bytes per lane) to a second plane that starts n_vec*4 bytes in.
 // ---------------------------------------------------------------------------
-template <int BITS, int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
-                                                           int64_t n_vec, void* __restrict__ codes,
-                                                           float* __restrict__ scales)
+template <int BITS, int GROUP, int UNROLL, bool FP>
+__device__ __forceinline__ void act_quant_tile(const u32x4* __restrict__ x, int64_t n_vec,
+                                               void* __restrict__ codes, float* __restrict__ scales,
+                                               unsigned block)
 {
     constexpr int LANES = GROUP / 8;
     constexpr int kBlock = AGOQ_AQ_BLOCK;
     constexpr bool NTL = AGOQ_AQ_NTL, NTS = AGOQ_AQ_NTS;
-    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    const int64_t base = (int64_t)block * (kBlock * UNROLL) + threadIdx.x;
 
     u32x4 v[UNROLL];
 #pragma unroll
@@ -37,20 +37,28 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
     }
 }
 
+template <int BITS, int GROUP, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
+                                                           int64_t n_vec, void* __restrict__ codes,
+                                                           float* __restrict__ scales)
+{
+    act_quant_tile<BITS, GROUP, UNROLL, FP>(x, n_vec, codes, scales, blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------
 // Activation dequantize: codes + scales -> bf16.  One lane produces 8 elements
 // (one 16-byte store).
 // ---------------------------------------------------------------------------
-template <int BITS, int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
-                                                             const float* __restrict__ scales,
-                                                             int64_t n_vec, u32x4* __restrict__ y)
+template <int BITS, int GROUP, int UNROLL, bool FP>
+__device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
+                                                 const float* __restrict__ scales, int64_t n_vec,
+                                                 u32x4* __restrict__ y, unsigned block)
 {
     static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
     constexpr int LANES = GROUP / 8;
     constexpr int kBlock = AGOQ_DQ_BLOCK;
     constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
-    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    const int64_t base = (int64_t)block * (kBlock * UNROLL) + threadIdx.x;
 
     u32 lo[UNROLL], hi[UNROLL];
     float s[UNROLL];
@@ -80,6 +88,121 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* 
             st<NTS>(y + vi, u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
                                   pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])});
     }
+}
+
+template <int BITS, int GROUP, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
+                                                             const float* __restrict__ scales,
+                                                             int64_t n_vec, u32x4* __restrict__ y)
+{
+    act_dequant_tile<BITS, GROUP, UNROLL, FP>(codes, scales, n_vec, y, blockIdx.x);
+}
+
+// ---------------------------------------------------------------------------
+// The stored tensors of one layer in one launch.  Consecutive ranges of workgroups serve
+// consecutive tensors, each at its own code width; a workgroup finds its tensor from the
+// table of first workgroup indices (all scalar work) and then runs the single-tensor tile.
+// A launch costs a few microseconds of ramp and drain whatever its size, which is a third
+// of the run time of a 32 MiB tensor: one launch per layer pays it once.
+// ---------------------------------------------------------------------------
+struct LayerArgs {
+    const void* src[AGOQ_MAX_LAYER_SLOTS];   // quantize: bf16 input; dequantize: codes
+    void* dst[AGOQ_MAX_LAYER_SLOTS];         // quantize: codes; dequantize: bf16 output
+    float* scales[AGOQ_MAX_LAYER_SLOTS];
+    int64_t n_vec[AGOQ_MAX_LAYER_SLOTS];
+    unsigned first_block[AGOQ_MAX_LAYER_SLOTS];  // unused entries hold 0xFFFFFFFF
+    int bits[AGOQ_MAX_LAYER_SLOTS];
+};
+
+__device__ __forceinline__ int layer_slot_of(const LayerArgs& a, unsigned block)
+{
+    int t = 0;
+#pragma unroll
+    for (int i = 1; i < AGOQ_MAX_LAYER_SLOTS; ++i) t += block >= a.first_block[i] ? 1 : 0;
+    return t;
+}
+
+// Vectors per lane in the layer dequantize (measured on 8B-shaped layers at seq 4096 and
+// 8192 under every stage map: two for every width is best or within 1% of best).
+#ifndef AGOQ_LDQ_UNROLL8
+#define AGOQ_LDQ_UNROLL8 2
+#endif
+#ifndef AGOQ_LDQ_UNROLL
+#define AGOQ_LDQ_UNROLL 2
+#endif
+constexpr int kLayerDqUnroll8 = AGOQ_LDQ_UNROLL8;   // 8-bit codes
+constexpr int kLayerDqUnroll = AGOQ_LDQ_UNROLL;     // 4-, 5- and 6-bit codes
+
+template <int GROUP>
+__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_layer_kernel(const LayerArgs a)
+{
+    const int t = layer_slot_of(a, blockIdx.x);
+    const unsigned block = blockIdx.x - a.first_block[t];
+    const u32x4* x = (const u32x4*)a.src[t];
+    void* codes = a.dst[t];
+    float* scales = a.scales[t];
+    const int64_t n_vec = a.n_vec[t];
+    switch (a.bits[t]) {
+    case 4: act_quant_tile<4, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
+    case 5: act_quant_tile<5, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
+    case 6: act_quant_tile<6, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
+    default: act_quant_tile<8, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
+    }
+}
+
+template <int GROUP>
+__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_layer_kernel(const LayerArgs a)
+{
+    const int t = layer_slot_of(a, blockIdx.x);
+    const unsigned block = blockIdx.x - a.first_block[t];
+    const void* codes = a.src[t];
+    const float* scales = a.scales[t];
+    u32x4* y = (u32x4*)a.dst[t];
+    const int64_t n_vec = a.n_vec[t];
+    switch (a.bits[t]) {
+    case 4: act_dequant_tile<4, GROUP, kLayerDqUnroll, false>(codes, scales, n_vec, y, block); break;
+    case 5: act_dequant_tile<5, GROUP, kLayerDqUnroll, false>(codes, scales, n_vec, y, block); break;
+    case 6: act_dequant_tile<6, GROUP, kLayerDqUnroll, false>(codes, scales, n_vec, y, block); break;
+    default: act_dequant_tile<8, GROUP, kLayerDqUnroll8, false>(codes, scales, n_vec, y, block); break;
+    }
+}
+
+// Validates the slots of a layer call and lays out the workgroup ranges.
+int layer_args(const agoq_act_slot* slots, int count, int group, bool quantize, LayerArgs& a,
+               unsigned& total_blocks)
+{
+    if (!slots) return AGOQ_ERR_NULL;
+    if (count < 1 || count > AGOQ_MAX_LAYER_SLOTS) return AGOQ_ERR_COUNT;
+    if (group != 64 && group != 128) return AGOQ_ERR_GROUP;
+    uint64_t blocks = 0;
+    for (int i = 0; i < AGOQ_MAX_LAYER_SLOTS; ++i) {
+        a.src[i] = nullptr;
+        a.dst[i] = nullptr;
+        a.scales[i] = nullptr;
+        a.n_vec[i] = 0;
+        a.first_block[i] = 0xFFFFFFFFu;
+        a.bits[i] = 8;
+    }
+    for (int i = 0; i < count; ++i) {
+        const agoq_act_slot& s = slots[i];
+        if (!s.bf16 || !s.codes || !s.scales) return AGOQ_ERR_NULL;
+        if (s.bits != 4 && s.bits != 5 && s.bits != 6 && s.bits != 8) return AGOQ_ERR_BITS;
+        if (int rc = check_common(s.numel, group)) return rc;
+        if (misaligned(s.bf16) || misaligned(s.codes) || misaligned(s.scales)) return AGOQ_ERR_ALIGN;
+        const int64_t n_vec = s.numel / 8;
+        const int per_block = quantize ? AGOQ_AQ_BLOCK * AGOQ_AQ_UNROLL
+                                       : AGOQ_DQ_BLOCK * (s.bits == 8 ? kLayerDqUnroll8 : kLayerDqUnroll);
+        a.src[i] = quantize ? (const void*)s.bf16 : (const void*)s.codes;
+        a.dst[i] = quantize ? s.codes : s.bf16;
+        a.scales[i] = s.scales;
+        a.n_vec[i] = n_vec;
+        a.bits[i] = s.bits;
+        a.first_block[i] = (unsigned)blocks;
+        blocks += (uint64_t)((n_vec + per_block - 1) / per_block);
+        if (blocks > 0x7FFFFFFFull) return AGOQ_ERR_SHAPE;
+    }
+    total_blocks = (unsigned)blocks;
+    return AGOQ_OK;
 }
 
 }  // namespace
@@ -196,6 +319,32 @@ int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, 
         act_dequant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
     else
         act_dequant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    return launch_status();
+}
+
+int agoq_act_quant_layer(const agoq_act_slot* slots, int count, int group, void* stream)
+{
+    LayerArgs a;
+    unsigned blocks = 0;
+    if (int rc = layer_args(slots, count, group, true, a, blocks)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        act_quant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), 0, st>>>(a);
+    else
+        act_quant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), 0, st>>>(a);
+    return launch_status();
+}
+
+int agoq_act_dequant_layer(const agoq_act_slot* slots, int count, int group, void* stream)
+{
+    LayerArgs a;
+    unsigned blocks = 0;
+    if (int rc = layer_args(slots, count, group, false, a, blocks)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        act_dequant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), 0, st>>>(a);
+    else
+        act_dequant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), 0, st>>>(a);
     return launch_status();
 }
 

@@ -93,10 +93,11 @@ const char* agoq_strerror(int status)
     case AGOQ_ERR_ALIGN: return "pointers and chunk strides must be 16-byte aligned";
     case AGOQ_ERR_K: return "K must be in 1..64";
     case AGOQ_ERR_HIP: return "HIP runtime error at launch";
+    case AGOQ_ERR_COUNT: return "layer call: tensor count outside 1..8";
     default: return "unknown status";
     }
 }
 
-int agoq_version(void) { return 100; }
+int agoq_version(void) { return 101; }
 
 }  // extern "C"

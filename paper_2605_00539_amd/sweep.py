@@ -182,6 +182,36 @@ def main():
                 del cs, ss
         del xs, ys, base
 
+    def layer_case(config, label, rows_, hidden, ffn, dist, frac, scale, seed, group, bitmap):
+        """The five stored tensors of one layer in ONE launch (agoq_act_quant_layer /
+        agoq_act_dequant_layer); whole layers rotate so that each side's cycle exceeds 1 GiB."""
+        cols = [hidden, hidden, hidden, ffn, ffn]
+        layer_bytes = 2 * rows_ * sum(cols)
+        nl = min(8, max(2, -(-(GiB + GiB // 2) // layer_bytes)))
+        base = [wl.act_device(rows_, c, seed + i, dist, wl.n_outlier_channels(c, frac), scale).reshape(-1)
+                for i, c in enumerate(cols)]
+        xs = [base] + [[b.roll(7919 * (l + 1)) for b in base] for l in range(nl - 1)]
+        ys = [[torch.empty_like(b) for b in base] for _ in range(nl)]
+        code_bytes = sum(b.numel() * w // 8 for b, w in zip(base, bitmap))
+        nc = min(16, max(2, -(-(GiB + GiB // 2) // code_bytes)))
+        cs = [[torch.empty(b.numel() * w // 8, dtype=torch.uint8, device=dev) for b, w in zip(base, bitmap)]
+              for _ in range(nc)]
+        ss = [[torch.empty(b.numel() // group, dtype=torch.float32, device=dev) for b in base] for _ in range(nc)]
+        m = max(nl, nc)
+        qs = [agoq.layer_slots(xs[i % nl], bitmap, cs[i % nc], ss[i % nc]) for i in range(m)]
+        ds = [agoq.layer_slots(ys[i % nl], bitmap, cs[i % nc], ss[i % nc]) for i in range(m)]
+        for i in range(nc):
+            L.agoq_act_quant_layer(qs[i % m][0], 5, group, st)
+        torch.cuda.synchronize()
+        nb = sum(algo_act(b.numel(), w, group) for b, w in zip(base, bitmap))
+        case = "%s rows %d map %s g%d" % (label, rows_, bitmap, group)
+        us = timed(lambda i: L.agoq_act_quant_layer(qs[i % m][0], 5, group, st), args.launches, args.reps)
+        report(config, "act_quant_layer (1 launch)", case, us, nb)
+        us = timed(lambda i: L.agoq_act_dequant_layer(ds[i % m][0], 5, group, st), args.launches, args.reps)
+        report(config, "act_dequant_layer (1 launch)", case, us, nb)
+        del xs, ys, cs, ss, base, qs, ds
+        torch.cuda.empty_cache()
+
     def grad_case(config, n, sigma, spike_frac, spike_scale, seed, K, group, share=True, fp8=False):
         g = [wl.grad_device(n, seed + i, sigma, spike_frac, spike_scale) for i in range(2 if n > (1 << 26) else 8)]
         nout = slots_for(n, floor=3)
@@ -286,6 +316,9 @@ def main():
         for name, sh in c["acts"].items():
             act_case("2-8B-act", name, sh["rows"], sh["cols"], c["dist"], c["outlier_frac"],
                      c["outlier_scale"], c["seed"], [c["group"]], [4, 8], fp=True)
+        a = c["acts"]
+        layer_case("2-8B-act", "layer", a["A"]["rows"], a["A"]["cols"], a["F"]["cols"], c["dist"],
+                   c["outlier_frac"], c["outlier_scale"], c["seed"], c["group"], agoq.layer_bitmap(5))
     # config 3: LLaMA-8B-shaped gradients, K = 8
     if 3 in wanted:
         c = C["llama8b_grad"]
@@ -329,6 +362,16 @@ def main():
                     report("5-stage", kernel + "_layer",
                            "stage %d (B=%d) map %s stored %d B (%.1f%% saved vs bf16)" %
                            (stage, b, bitmap, stored, 100.0 * (1 - stored / bf16_bytes)), us, nb)
+        seen = []
+        for stage in (1, 2, 3, 4):
+            b = agoq.dbca_bits(4, stage)
+            for native in (True, False):
+                bitmap = agoq.layer_bitmap(b, native=native)
+                if bitmap in seen:
+                    continue
+                seen.append(bitmap)
+                layer_case("5-stage", "stage %d (B=%d)" % (stage, b), c["rows"], c["hidden"], c["ffn"],
+                           c["dist"], c["outlier_frac"], c["outlier_scale"], c["seed"], c["group"], bitmap)
     print(json.dumps(rows))
     return 0
 

@@ -135,3 +135,28 @@ def test_generated_isa_has_no_packed_fp32_math(tmp_path):
     for mnemonic in ("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32"):
         assert mnemonic not in text, mnemonic
     assert "scratch_" not in text                       # no register spills to scratch memory
+
+
+def test_layer_call_argument_checks(agoq):
+    # every rejection happens on the host before anything touches a device, so it can be
+    # exercised here with made-up (aligned, never dereferenced) addresses
+    import ctypes
+    L = agoq.load_library()
+    Slot = agoq.ActSlot
+
+    def call(fn, slots, count, group=128):
+        arr = (Slot * max(len(slots), 1))(*slots)
+        return fn(arr, count, group, None)
+
+    good = Slot(0x10000, 0x20000, 0x30000, 1024, 4)
+    for fn in (L.agoq_act_quant_layer, L.agoq_act_dequant_layer):
+        assert fn(None, 1, 128, None) == 1
+        assert call(fn, [good], 0) == 8
+        assert call(fn, [good] * 9, 9) == 8
+        assert call(fn, [good], 1, group=32) == 3
+        assert call(fn, [good, Slot(0x10000, 0, 0x30000, 1024, 4)], 2) == 1
+        assert call(fn, [good, Slot(0x10000, 0x20000, 0x30000, 1024, 7)], 2) == 2
+        assert call(fn, [good, Slot(0x10000, 0x20000, 0x30000, 1000, 4)], 2) == 4
+        assert call(fn, [good, Slot(0x10000, 0x20000, 0x30000, 0, 4)], 2) == 4
+        assert call(fn, [good, Slot(0x10008, 0x20000, 0x30000, 1024, 4)], 2) == 5
+    assert "count" in agoq.strerror(8)
