@@ -60,15 +60,14 @@ __device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
     constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
     const int64_t base = (int64_t)block * (kBlock * UNROLL) + threadIdx.x;
 
-    u32 lo[UNROLL], hi[UNROLL];
+    Codes8<BITS> c[UNROLL];
     float s[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        lo[u] = hi[u] = 0;
         s[u] = 0.0f;
         if (vi < n_vec) {
-            load_codes8<BITS, NTC>(codes, n_vec, vi, lo[u], hi[u]);
+            c[u] = load_codes8<BITS, NTC>(codes, n_vec, vi);
             s[u] = ld<NTSC>(scales + vi / LANES);
         }
     }
@@ -76,11 +75,11 @@ __device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         float q[8], f[8];
-        if (FP) {
-            decode8_e2m1(lo[u], q);
+        if constexpr (FP) {
+            decode8_e2m1(c[u].lo, q);
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) q[j] = decode8<BITS>(lo[u], hi[u], j);
+            for (int j = 0; j < 8; ++j) q[j] = decode8<BITS>(c[u], j);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) f[j] = __fmul_rn(q[j], s[u]);

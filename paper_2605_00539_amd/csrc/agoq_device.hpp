@@ -318,44 +318,69 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
     if ((vi & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
 }
 
-// The stored codes of the 8 elements a lane owns.  4/5/6-bit: lo = the nibble word,
-// hi = the lane's field of high bits.  8-bit: lo, hi = the two code words.
+// The stored codes of the 8 elements a lane owns, as loaded.  4/5/6-bit: lo = the nibble
+// word, hi = the lane's field of high bits.  8-bit: the two code words, kept as the one
+// 64-bit integer the load fills (copying its halves out right after the load, or keeping
+// it as a two-element vector that the compiler splits, makes the lane wait for the data
+// before it can issue its next load).
+template <int BITS>
+struct Codes8 {
+    u32 lo = 0, hi = 0;
+};
+template <>
+struct Codes8<8> {
+    uint64_t w = 0;
+};
+
 template <int BITS, bool NT>
-__device__ __forceinline__ void load_codes8(const void* codes, int64_t n_vec, int64_t vi, u32& lo,
-                                            u32& hi)
+__device__ __forceinline__ Codes8<BITS> load_codes8(const void* codes, int64_t n_vec, int64_t vi)
 {
-    if (BITS == 8) {
-        const u32x2 c = ld<NT>((const u32x2*)codes + vi);
-        lo = c[0];
-        hi = c[1];
+    Codes8<BITS> c;
+    if constexpr (BITS == 8) {
+        c.w = ld<NT>((const uint64_t*)codes + vi);
     } else {
-        lo = ld<NT>((const u32*)codes + vi);
-        hi = 0;
+        c.lo = ld<NT>((const u32*)codes + vi);
         const uint8_t* high = (const uint8_t*)codes + n_vec * 4;
-        if (BITS == 5) hi = ld<NT>(high + vi);
-        if (BITS == 6) hi = ld<NT>((const uint16_t*)high + vi);
+        if (BITS == 5) c.hi = ld<NT>(high + vi);
+        if (BITS == 6) c.hi = ld<NT>((const uint16_t*)high + vi);
+    }
+    return c;
+}
+
+template <int BITS>
+__device__ __forceinline__ float decode8(const Codes8<BITS>& c, int j)
+{
+    if constexpr (BITS == 8) {
+        return byte_to_f32(j < 4 ? (u32)c.w : (u32)(c.w >> 32), j & 3);
+    } else if constexpr (BITS == 4) {
+        return (float)(int)__builtin_amdgcn_sbfe((int)c.lo, 4 * j, 4);
+    } else {
+        const int h = (int)__builtin_amdgcn_sbfe((int)c.hi, (BITS - 4) * j, BITS - 4);
+        return (float)(int)(((u32)h << 4) | __builtin_amdgcn_ubfe(c.lo, 4 * j, 4));
     }
 }
 
+// x' = bf16(code * scale) for the lane's 8 elements, as four words of two bf16 each
+// (element 2k in the low half of word k).
 template <int BITS>
-__device__ __forceinline__ float decode8(u32 lo, u32 hi, int j)
-{
-    if (BITS == 4) return (float)(int)__builtin_amdgcn_sbfe((int)lo, 4 * j, 4);
-    if (BITS == 8) return byte_to_f32(j < 4 ? lo : hi, j & 3);
-    const int h = (int)__builtin_amdgcn_sbfe((int)hi, (BITS - 4) * j, BITS - 4);
-    return (float)(int)(((u32)h << 4) | __builtin_amdgcn_ubfe(lo, 4 * j, 4));
-}
-
-// x' = bf16(code * scale) for the lane's 8 elements, returned as fp32 values.
-template <int BITS>
-__device__ __forceinline__ void dequant8_bf16(u32 lo, u32 hi, float scale, float (&x)[8])
+__device__ __forceinline__ void dequant8_packed(const Codes8<BITS>& c, float scale, u32 (&w)[4])
 {
 #pragma unroll
-    for (int j = 0; j < 8; j += 2) {
-        const u32 w = pack_bf16x2(__fmul_rn(decode8<BITS>(lo, hi, j), scale),
-                                  __fmul_rn(decode8<BITS>(lo, hi, j + 1), scale));
-        x[j] = as_f32(w << 16);
-        x[j + 1] = as_f32(w & 0xFFFF0000u);
+    for (int k = 0; k < 4; ++k)
+        w[k] = pack_bf16x2(__fmul_rn(decode8<BITS>(c, 2 * k), scale),
+                           __fmul_rn(decode8<BITS>(c, 2 * k + 1), scale));
+}
+
+// The same as fp32 values.
+template <int BITS>
+__device__ __forceinline__ void dequant8_bf16(const Codes8<BITS>& c, float scale, float (&x)[8])
+{
+    u32 w[4];
+    dequant8_packed<BITS>(c, scale, w);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        x[2 * k] = as_f32(w[k] << 16);
+        x[2 * k + 1] = as_f32(w[k] & 0xFFFF0000u);
     }
 }
 

@@ -6,112 +6,176 @@
 
 namespace {
 
-// RMSNorm recompute: one workgroup of 256 lanes per row of `cols` elements
-// (cols <= 2048 * VPT); the row stays in registers between the two phases.
-//   r = sqrt(mean(x'^2) + eps);  y = bf16(x' * (1/r) * gamma)
-constexpr int kNormBlock = 256;
-template <int BITS, int GROUP, int VPT>
-__global__ __launch_bounds__(kNormBlock) void act_dequant_rmsnorm_kernel(
-    const void* __restrict__ codes, const float* __restrict__ scales, int64_t n_vec_total,
-    int vecs_per_row, const f32x4* __restrict__ gamma, float eps, float inv_cols,
-    u32x4* __restrict__ y, float* __restrict__ r_out)
+// RMSNorm recompute:  r = sqrt(mean(x'^2) + eps);  y = bf16(x' * (1/r) * gamma).
+// A workgroup owns a set of rows (blockIdx.x, + gridDim.x, ...) and works through them one
+// at a time; each lane owns the same VPT column vectors in every row, so its slice of
+// gamma is loaded once and stays in registers.  While a row is being reduced and stored,
+// the codes of the workgroup's next row are already in flight: a row's load -> reduce ->
+// store chain would otherwise leave the memory pipes idle for most of a workgroup's life.
+// The row waits in registers as the bf16 pairs it consists of.
+constexpr int kNormMaxBlock = 1024;
+constexpr int64_t kNormMaxCols = 16384;          // widest row the row kernels take
+// Most lanes a row kernel with VPT vectors per lane is ever launched with (the register
+// budget per lane follows from it).
+constexpr int norm_max_block(int vpt)
 {
-    constexpr int LANES = GROUP / 8;
-    __shared__ float wave_part[kNormBlock / 64];
-    const int64_t row_vec0 = (int64_t)blockIdx.x * vecs_per_row;
-    float x[VPT][8];
-    float ss = 0.0f;
-#pragma unroll
-    for (int u = 0; u < VPT; ++u) {
-        const int v = threadIdx.x + u * kNormBlock;
-        u32 lo = 0, hi = 0;
-        float sc = 0.0f;
-        if (v < vecs_per_row) {
-            const int64_t vi = row_vec0 + v;
-            load_codes8<BITS, true>(codes, n_vec_total, vi, lo, hi);
-            sc = ld<false>(scales + vi / LANES);
-        }
-        dequant8_bf16<BITS>(lo, hi, sc, x[u]);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ss = __fmaf_rn(x[u][j], x[u][j], ss);
-    }
-    ss = wave_sum(ss);
-    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = ss;
+    return (int)(kNormMaxCols / 8 / vpt) < kNormMaxBlock ? (int)(kNormMaxCols / 8 / vpt) : kNormMaxBlock;
+}
+#ifndef AGOQ_NORM_VPT          // column vectors per lane (doubled while a row needs > 1024 lanes)
+#define AGOQ_NORM_VPT 4
+#endif
+#ifndef AGOQ_NORM_DEPTH        // rows in flight beyond the one being reduced: 1 or 2
+#define AGOQ_NORM_DEPTH 2
+#endif
+#ifndef AGOQ_NORM_VPT8         // the same two for 8-bit codes, whose buffers are twice the size
+#define AGOQ_NORM_VPT8 2
+#endif
+#ifndef AGOQ_NORM_DEPTH8
+#define AGOQ_NORM_DEPTH8 2
+#endif
+#ifndef AGOQ_NORM_FWD_VPT      // the same two for the forward kernel
+#define AGOQ_NORM_FWD_VPT 2
+#endif
+#ifndef AGOQ_NORM_FWD_DEPTH
+#define AGOQ_NORM_FWD_DEPTH 2
+#endif
+#ifndef AGOQ_NORM_RESIDENT     // lanes per compute unit the grid is sized for
+#define AGOQ_NORM_RESIDENT 1024
+#endif
+
+// Sum of the per-wavefront partial sums of a workgroup, in wavefront order.
+__device__ __forceinline__ float block_sum(float wave_total, float* wave_part)
+{
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = wave_total;
     __syncthreads();
     float total = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kNormBlock / 64; ++w) total += wave_part[w];
-    const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
-    const float rinv = __fdiv_rn(1.0f, r);
-    if (threadIdx.x == 0) r_out[blockIdx.x] = r;
-#pragma unroll
-    for (int u = 0; u < VPT; ++u) {
-        const int v = threadIdx.x + u * kNormBlock;
-        if (v < vecs_per_row) {
-            const f32x4 g0 = gamma[2 * v], g1 = gamma[2 * v + 1];
-            float o[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                o[j] = __fmul_rn(__fmul_rn(x[u][j], rinv), g0[j]);
-                o[4 + j] = __fmul_rn(__fmul_rn(x[u][4 + j], rinv), g1[j]);
-            }
-            st<true>(y + row_vec0 + v, u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]),
-                                             pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])});
-        }
-    }
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) total += wave_part[w];
+    return total;
 }
 
-// Narrow rows (cols <= 512 * VPT, i.e. up to 4096): one wavefront per row, four rows per
-// workgroup, every load of the row in flight at once, no LDS and no barrier.
+// y for the lane's 8 elements from x' (bf16 pairs), 1/r and gamma.
+__device__ __forceinline__ u32x4 norm_out8(const u32 (&xp)[4], float rinv, const f32x4& g0,
+                                           const f32x4& g1)
+{
+    float o[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float x0 = as_f32(xp[k] << 16), x1 = as_f32(xp[k] & 0xFFFF0000u);
+        const f32x4& g = k < 2 ? g0 : g1;
+        o[2 * k] = __fmul_rn(__fmul_rn(x0, rinv), g[(2 * k) & 3]);
+        o[2 * k + 1] = __fmul_rn(__fmul_rn(x1, rinv), g[(2 * k + 1) & 3]);
+    }
+    return u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                 pack_bf16x2(o[6], o[7])};
+}
+
+// Adds the squares of the lane's 8 elements (bf16 pairs) to ss, in element order.
+__device__ __forceinline__ float sumsq8(const u32 (&xp)[4], float ss)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float x0 = as_f32(xp[k] << 16), x1 = as_f32(xp[k] & 0xFFFF0000u);
+        ss = __fmaf_rn(x0, x0, ss);
+        ss = __fmaf_rn(x1, x1, ss);
+    }
+    return ss;
+}
+
 template <int BITS, int GROUP, int VPT>
-__global__ __launch_bounds__(kNormBlock) void act_dequant_rmsnorm_wave_kernel(
+__global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kernel(
     const void* __restrict__ codes, const float* __restrict__ scales, int64_t n_vec_total,
     int64_t rows, int vecs_per_row, const f32x4* __restrict__ gamma, float eps, float inv_cols,
     u32x4* __restrict__ y, float* __restrict__ r_out)
 {
     constexpr int LANES = GROUP / 8;
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * (kNormBlock / 64) + (threadIdx.x >> 6);
-    if (row >= rows) return;                      // whole wavefronts leave together
-    const int64_t row_vec0 = row * vecs_per_row;
-    u32 lo[VPT], hi[VPT];
-    float sc[VPT];
+    __shared__ float wave_part[2][kNormMaxBlock / 64];
+    f32x4 g0[VPT], g1[VPT];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int v = lane + u * 64;
-        lo[u] = hi[u] = 0;
-        sc[u] = 0.0f;
+        const int v = threadIdx.x + u * blockDim.x;
+        g0[u] = g1[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (v < vecs_per_row) {
-            const int64_t vi = row_vec0 + v;
-            load_codes8<BITS, true>(codes, n_vec_total, vi, lo[u], hi[u]);
-            sc[u] = ld<false>(scales + vi / LANES);
+            g0[u] = gamma[2 * v];
+            g1[u] = gamma[2 * v + 1];
         }
     }
-    float x[VPT][8];
-    float ss = 0.0f;
+    // Three row buffers in rotation: while one row is reduced and stored, the loads of the
+    // workgroup's next two rows are in flight.  The rotation is written out (no buffer is
+    // ever copied into another: a copy would have to wait for the load that fills it).
+    // Loads are unconditional (a lane past the end of the row re-reads the row's last vector
+    // and uses scale 0, so it adds nothing to the row sum): a load under a branch would have
+    // to be merged with the register's old value, which again waits for the data.
+    constexpr int kDepth = BITS == 8 ? AGOQ_NORM_DEPTH8 : AGOQ_NORM_DEPTH;
+    struct RowBuf {
+        Codes8<BITS> c[VPT];
+        float sc[VPT];
+    };
+    const int64_t step = gridDim.x;
+    auto fetch = [&](RowBuf& b, int64_t row) {
+        if (row >= rows) return;                    // the same for every lane of the workgroup
 #pragma unroll
-    for (int u = 0; u < VPT; ++u) {
-        dequant8_bf16<BITS>(lo[u], hi[u], sc[u], x[u]);
+        for (int u = 0; u < VPT; ++u) {
+            const int v = threadIdx.x + u * blockDim.x;
+            const int64_t vi = row * vecs_per_row + (v < vecs_per_row ? v : vecs_per_row - 1);
+            b.c[u] = load_codes8<BITS, true>(codes, n_vec_total, vi);
+            b.sc[u] = ld<false>(scales + vi / LANES);
+        }
+    };
+    // One row from its buffer to memory; `refill` (the same buffer, free once the row has
+    // been decoded) then receives the row that is kDepth + 1 steps on.
+    auto finish = [&](const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
+        u32 xp[VPT][4];
+        float ss = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) ss = __fmaf_rn(x[u][j], x[u][j], ss);
-    }
-    const float total = wave_sum(ss);
-    const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
-    const float rinv = __fdiv_rn(1.0f, r);
-    if (lane == 0) r_out[row] = r;
+        for (int u = 0; u < VPT; ++u) {
+            const bool valid = (int)(threadIdx.x + u * blockDim.x) < vecs_per_row;
+            dequant8_packed<BITS>(b.c[u], valid ? b.sc[u] : 0.0f, xp[u]);
+            ss = sumsq8(xp[u], ss);
+        }
+        fetch(refill, row + (kDepth + 1) * step);
+        const float total = block_sum(wave_sum(ss), wave_part[phase]);
+        const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
+        const float rinv = __fdiv_rn(1.0f, r);
+        if (threadIdx.x == 0) r_out[row] = r;
 #pragma unroll
-    for (int u = 0; u < VPT; ++u) {
-        const int v = lane + u * 64;
-        if (v < vecs_per_row) {
-            const f32x4 g0 = gamma[2 * v], g1 = gamma[2 * v + 1];
-            float o[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                o[j] = __fmul_rn(__fmul_rn(x[u][j], rinv), g0[j]);
-                o[4 + j] = __fmul_rn(__fmul_rn(x[u][4 + j], rinv), g1[j]);
-            }
-            st<true>(y + row_vec0 + v, u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]),
-                                             pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])});
+        for (int u = 0; u < VPT; ++u) {
+            const int v = threadIdx.x + u * blockDim.x;
+            if (v < vecs_per_row)
+                st<true>(y + row * vecs_per_row + v, norm_out8(xp[u], rinv, g0[u], g1[u]));
+        }
+    };
+    // wave_part has two buffers used alternately: a wavefront is never more than one
+    // barrier ahead of another, so a buffer is rewritten only after everyone has read it.
+    int64_t row = blockIdx.x;                       // the grid never exceeds the row count
+    if constexpr (kDepth == 2) {
+        RowBuf b0, b1, b2;
+        fetch(b0, row);
+        fetch(b1, row + step);
+        fetch(b2, row + 2 * step);
+        while (true) {
+            finish(b0, row, b0, 0);
+            if ((row += step) >= rows) break;
+            finish(b1, row, b1, 1);
+            if ((row += step) >= rows) break;
+            finish(b2, row, b2, 0);
+            if ((row += step) >= rows) break;
+            finish(b0, row, b0, 1);
+            if ((row += step) >= rows) break;
+            finish(b1, row, b1, 0);
+            if ((row += step) >= rows) break;
+            finish(b2, row, b2, 1);
+            if ((row += step) >= rows) break;
+        }
+    } else {
+        RowBuf b0, b1;
+        fetch(b0, row);
+        fetch(b1, row + step);
+        while (true) {
+            finish(b0, row, b0, 0);
+            if ((row += step) >= rows) break;
+            finish(b1, row, b1, 1);
+            if ((row += step) >= rows) break;
         }
     }
 }
@@ -127,16 +191,16 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_silu_mul_kernel(
     constexpr int LANES = GROUP / 8;
     constexpr int kBlock = AGOQ_DQ_BLOCK;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
-    u32 glo[UNROLL], ghi[UNROLL], ulo[UNROLL], uhi[UNROLL];
+    Codes8<BITS_G> gc[UNROLL];
+    Codes8<BITS_U> uc[UNROLL];
     float gs[UNROLL], us[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        glo[u] = ghi[u] = ulo[u] = uhi[u] = 0;
         gs[u] = us[u] = 0.0f;
         if (vi < n_vec) {
-            load_codes8<BITS_G, true>(gate_codes, n_vec, vi, glo[u], ghi[u]);
-            load_codes8<BITS_U, true>(up_codes, n_vec, vi, ulo[u], uhi[u]);
+            gc[u] = load_codes8<BITS_G, true>(gate_codes, n_vec, vi);
+            uc[u] = load_codes8<BITS_U, true>(up_codes, n_vec, vi);
             gs[u] = ld<false>(gate_scales + vi / LANES);
             us[u] = ld<false>(up_scales + vi / LANES);
         }
@@ -145,8 +209,8 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_silu_mul_kernel(
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         float g[8], up[8], o[8];
-        dequant8_bf16<BITS_G>(glo[u], ghi[u], gs[u], g);
-        dequant8_bf16<BITS_U>(ulo[u], uhi[u], us[u], up);
+        dequant8_bf16<BITS_G>(gc[u], gs[u], g);
+        dequant8_bf16<BITS_U>(uc[u], us[u], up);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float e = __expf(-g[j]);                          // may be +inf: 1/(1+inf) = 0
@@ -164,59 +228,99 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_silu_mul_kernel(
 // input is read from memory once instead of once by the layer and once by the quantizer.
 // ---------------------------------------------------------------------------
 
-// RMSNorm forward + quantize(x): one workgroup per row (cols <= 2048 * VPT).
+// RMSNorm forward + quantize(x): one workgroup per row, shaped like the recompute kernel.
 //   y = bf16(x * (1/r) * gamma), r = sqrt(mean(x^2) + eps);  codes, scales = quantize(x)
 template <int BITS, int GROUP, int VPT>
-__global__ __launch_bounds__(kNormBlock) void rmsnorm_fwd_quant_kernel(
-    const u32x4* __restrict__ x, int64_t n_vec_total, int vecs_per_row,
+__global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
+    const u32x4* __restrict__ x, int64_t n_vec_total, int64_t rows, int vecs_per_row,
     const f32x4* __restrict__ gamma, float eps, float inv_cols, u32x4* __restrict__ y,
     float* __restrict__ r_out, void* __restrict__ codes, float* __restrict__ scales)
 {
     constexpr int LANES = GROUP / 8;
-    __shared__ float wave_part[kNormBlock / 64];
-    const int64_t row_vec0 = (int64_t)blockIdx.x * vecs_per_row;
-    u32x4 v[VPT];
+    __shared__ float wave_part[2][kNormMaxBlock / 64];
+    f32x4 g0[VPT], g1[VPT];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int c = threadIdx.x + u * kNormBlock;
-        v[u] = u32x4{0, 0, 0, 0};
-        if (c < vecs_per_row) v[u] = ld<true>(x + row_vec0 + c);
-    }
-    float f[VPT][8];
-    float ss = 0.0f;
-#pragma unroll
-    for (int u = 0; u < VPT; ++u) {
-        const int c = threadIdx.x + u * kNormBlock;
-        const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f[u]));
-        quantize_store8<BITS, GROUP, false, true>(f[u], m, row_vec0 + c, n_vec_total,
-                                                  c < vecs_per_row, codes, scales);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ss = __fmaf_rn(f[u][j], f[u][j], ss);
-    }
-    ss = wave_sum(ss);
-    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    float total = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kNormBlock / 64; ++w) total += wave_part[w];
-    const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
-    const float rinv = __fdiv_rn(1.0f, r);
-    if (threadIdx.x == 0 && r_out) r_out[blockIdx.x] = r;
-#pragma unroll
-    for (int u = 0; u < VPT; ++u) {
-        const int c = threadIdx.x + u * kNormBlock;
+        const int c = threadIdx.x + u * blockDim.x;
+        g0[u] = g1[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (c < vecs_per_row) {
-            const f32x4 g0 = gamma[2 * c], g1 = gamma[2 * c + 1];
-            float o[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                o[j] = __fmul_rn(__fmul_rn(f[u][j], rinv), g0[j]);
-                o[4 + j] = __fmul_rn(__fmul_rn(f[u][4 + j], rinv), g1[j]);
-            }
-            st<true>(y + row_vec0 + c, u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]),
-                                             pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])});
+            g0[u] = gamma[2 * c];
+            g1[u] = gamma[2 * c + 1];
         }
     }
+    // Row buffers in rotation, as in the recompute kernel: the row waits in registers as the
+    // bf16 pairs it arrived in, and the next rows of the workgroup are already in flight.
+    struct RowBuf {
+        u32x4 v[VPT];
+    };
+    const int64_t step = gridDim.x;
+    auto fetch = [&](RowBuf& b, int64_t row) {
+        if (row >= rows) return;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const int c = threadIdx.x + u * blockDim.x;
+            b.v[u] = ld<true>(x + row * vecs_per_row + (c < vecs_per_row ? c : vecs_per_row - 1));
+        }
+    };
+    auto finish = [&](const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
+        u32x4 v[VPT];
+        float ss = 0.0f;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const int c = threadIdx.x + u * blockDim.x;
+            const bool valid = c < vecs_per_row;
+            v[u] = valid ? b.v[u] : u32x4{0, 0, 0, 0};
+            float f[8];
+            const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f));
+            quantize_store8<BITS, GROUP, false, true>(f, m, row * vecs_per_row + c, n_vec_total,
+                                                      valid, codes, scales);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ss = __fmaf_rn(f[j], f[j], ss);
+        }
+        fetch(refill, row + (AGOQ_NORM_FWD_DEPTH + 1) * step);
+        const float total = block_sum(wave_sum(ss), wave_part[phase]);
+        const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
+        const float rinv = __fdiv_rn(1.0f, r);
+        if (threadIdx.x == 0 && r_out) r_out[row] = r;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const int c = threadIdx.x + u * blockDim.x;
+            const u32 xp[4] = {v[u][0], v[u][1], v[u][2], v[u][3]};
+            if (c < vecs_per_row)
+                st<true>(y + row * vecs_per_row + c, norm_out8(xp, rinv, g0[u], g1[u]));
+        }
+    };
+    int64_t row = blockIdx.x;                       // the grid never exceeds the row count
+#if AGOQ_NORM_FWD_DEPTH == 2
+    RowBuf b0, b1, b2;
+    fetch(b0, row);
+    fetch(b1, row + step);
+    fetch(b2, row + 2 * step);
+    while (true) {
+        finish(b0, row, b0, 0);
+        if ((row += step) >= rows) break;
+        finish(b1, row, b1, 1);
+        if ((row += step) >= rows) break;
+        finish(b2, row, b2, 0);
+        if ((row += step) >= rows) break;
+        finish(b0, row, b0, 1);
+        if ((row += step) >= rows) break;
+        finish(b1, row, b1, 0);
+        if ((row += step) >= rows) break;
+        finish(b2, row, b2, 1);
+        if ((row += step) >= rows) break;
+    }
+#else
+    RowBuf b0, b1;
+    fetch(b0, row);
+    fetch(b1, row + step);
+    while (true) {
+        finish(b0, row, b0, 0);
+        if ((row += step) >= rows) break;
+        finish(b1, row, b1, 1);
+        if ((row += step) >= rows) break;
+    }
+#endif
 }
 
 // SiLU & Multiply forward + quantize(gate), quantize(up), elementwise.
@@ -260,6 +364,24 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void silu_mul_fwd_quant_kernel(
     }
 }
 
+// Launch shape of the row kernels: VPT vectors per lane (the preferred count, doubled
+// while a row would need more than 1024 lanes) and the number of lanes, a whole number of
+// wavefronts.
+inline void norm_launch_shape(int vecs_per_row, int preferred_vpt, int& vpt, int& threads)
+{
+    vpt = preferred_vpt;
+    while ((vecs_per_row + vpt - 1) / vpt > kNormMaxBlock) vpt *= 2;
+    threads = ((vecs_per_row + vpt - 1) / vpt + 63) / 64 * 64;
+}
+
+// Workgroups of a row kernel that walks its rows: as many as are resident at once.
+inline unsigned norm_grid(int64_t rows, int threads)
+{
+    const int per_cu = AGOQ_NORM_RESIDENT / threads > 0 ? AGOQ_NORM_RESIDENT / threads : 1;
+    const int64_t resident = (int64_t)compute_units() * per_cu;
+    return (unsigned)(rows < resident ? rows : resident);
+}
+
 }  // namespace
 
 extern "C" {
@@ -272,7 +394,7 @@ int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t row
     if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
     if (group != 64 && group != 128) return AGOQ_ERR_GROUP;
     if (rows <= 0 || rows > 0x7FFFFFFF || cols <= 0 || cols % group != 0 ||
-        cols > (int64_t)kNormBlock * 8 * 8)
+        cols > kNormMaxCols)
         return AGOQ_ERR_SHAPE;
     if (misaligned(codes) || misaligned(scales) || misaligned(gamma) || misaligned(y_bf16))
         return AGOQ_ERR_ALIGN;
@@ -282,43 +404,14 @@ int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t row
     hipStream_t st = (hipStream_t)stream;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
-    if (vecs_per_row <= 64 * 8 && bits != 8) {
-        // one wavefront per row (measured faster for the narrow codes; 8-bit codes need too many
-        // registers per lane for it and keep the workgroup-per-row form)
-        const int wvpt = vecs_per_row <= 64 * 4 ? 4 : 8;
-        const dim3 wgrid((unsigned)((rows + kNormBlock / 64 - 1) / (kNormBlock / 64))), wblock(kNormBlock);
-#define AGOQ_LAUNCH_NORM_WAVE(B, G)                                                               \
-    if (wvpt == 4)                                                                                \
-        act_dequant_rmsnorm_wave_kernel<B, G, 4><<<wgrid, wblock, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); \
-    else                                                                                          \
-        act_dequant_rmsnorm_wave_kernel<B, G, 8><<<wgrid, wblock, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out);
-        if (group == 128) {
-            switch (bits) {
-            case 4: AGOQ_LAUNCH_NORM_WAVE(4, 128) break;
-            case 5: AGOQ_LAUNCH_NORM_WAVE(5, 128) break;
-            case 6: AGOQ_LAUNCH_NORM_WAVE(6, 128) break;
-            default: AGOQ_LAUNCH_NORM_WAVE(8, 128) break;
-            }
-        } else {
-            switch (bits) {
-            case 4: AGOQ_LAUNCH_NORM_WAVE(4, 64) break;
-            case 5: AGOQ_LAUNCH_NORM_WAVE(5, 64) break;
-            case 6: AGOQ_LAUNCH_NORM_WAVE(6, 64) break;
-            default: AGOQ_LAUNCH_NORM_WAVE(8, 64) break;
-            }
-        }
-#undef AGOQ_LAUNCH_NORM_WAVE
-        return launch_status();
-    }
-    int vpt = 1;
-    while (kNormBlock * vpt < vecs_per_row) vpt *= 2;
-    const dim3 grid((unsigned)rows), block(kNormBlock);
+    int vpt, threads;
+    norm_launch_shape(vecs_per_row, bits == 8 ? AGOQ_NORM_VPT8 : AGOQ_NORM_VPT, vpt, threads);
+    const dim3 grid(norm_grid(rows, threads)), block(threads);
 #define AGOQ_LAUNCH_NORM(B, G)                                                                    \
     switch (vpt) {                                                                                \
-    case 1: act_dequant_rmsnorm_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    case 2: act_dequant_rmsnorm_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    case 4: act_dequant_rmsnorm_kernel<B, G, 4><<<grid, block, 0, st>>>(codes, scales, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    default: act_dequant_rmsnorm_kernel<B, G, 8><<<grid, block, 0, st>>>(codes, scales, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    case 1: act_dequant_rmsnorm_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    case 2: act_dequant_rmsnorm_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    default: act_dequant_rmsnorm_kernel<B, G, 4><<<grid, block, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
     }
     if (group == 128) {
         switch (bits) {
@@ -387,7 +480,7 @@ int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const
     if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
     if (group != 64 && group != 128) return AGOQ_ERR_GROUP;
     if (rows <= 0 || rows > 0x7FFFFFFF || cols <= 0 || cols % group != 0 ||
-        cols > (int64_t)kNormBlock * 8 * 8)
+        cols > kNormMaxCols)
         return AGOQ_ERR_SHAPE;
     if (misaligned(x_bf16) || misaligned(gamma) || misaligned(y_bf16) || misaligned(codes) ||
         misaligned(scales))
@@ -395,19 +488,18 @@ int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const
     const int vecs_per_row = (int)(cols / 8);
     const int64_t n_vec_total = rows * vecs_per_row;
     const float inv_cols = 1.0f / (float)cols;
-    int vpt = 1;
-    while (kNormBlock * vpt < vecs_per_row) vpt *= 2;
-    const dim3 grid((unsigned)rows), block(kNormBlock);
+    int vpt, threads;
+    norm_launch_shape(vecs_per_row, AGOQ_NORM_FWD_VPT, vpt, threads);
+    const dim3 grid(norm_grid(rows, threads)), block(threads);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
 #define AGOQ_LAUNCH_NORM_FWD(B, G)                                                                \
     switch (vpt) {                                                                                \
-    case 1: rmsnorm_fwd_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    case 4: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    default: rmsnorm_fwd_quant_kernel<B, G, 8><<<grid, block, 0, st>>>(x, n_vec_total, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 1: rmsnorm_fwd_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    default: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
     }
     if (group == 128) {
         switch (bits) {
