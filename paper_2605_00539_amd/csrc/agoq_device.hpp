@@ -86,6 +86,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define AGOQ_RD_NTS 1
 #endif
 
+#ifndef AGOQ_SCALE_NT          // scale stores (a few bytes per wavefront) streaming too, or cached
+#define AGOQ_SCALE_NT 1
+#endif
 #ifndef AGOQ_GD_BLOCK          // gradient dequantize
 #define AGOQ_GD_BLOCK 512
 #endif
@@ -315,7 +318,7 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
         for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
         st<NTS>((u32x2*)codes + vi, u32x2{p0, p1});
     }
-    if ((vi & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
+    if ((vi & (LANES - 1)) == 0) st<NTS && AGOQ_SCALE_NT>(scales + vi / LANES, scale);
 }
 
 // The stored codes of the 8 elements a lane owns, as loaded.  4/5/6-bit: lo = the nibble

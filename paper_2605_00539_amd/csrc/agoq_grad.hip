@@ -52,7 +52,7 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* 
                 if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
                 st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
             }
-            if (lane16 == 0) st<NTS>(scales + grp, scale);
+            if (lane16 == 0) st<NTS && AGOQ_SCALE_NT>(scales + grp, scale);
         }
     }
 }
@@ -82,7 +82,7 @@ __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi
             w[d] = encode4_bytes<FP>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv);
         if (FP && scale == 0.0f) w = u32x4{0, 0, 0, 0};       // dead group: no signed zeros
         st<AGOQ_RD_NTS>(out_codes + vi, w);
-        if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS>(out_scales + vi / LANES, scale);
+        if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS && AGOQ_SCALE_NT>(out_scales + vi / LANES, scale);
     }
 }
 
@@ -173,19 +173,18 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
     f32x4 v[UNROLL][VPL];
     u32 c[UNROLL][VPL];
     float s[UNROLL];
+    // Loads are unconditional (lanes past the end re-read the last group; only their stores
+    // are masked): under a branch each, the compiler waits for the first loads before it
+    // issues the last.
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t grp = (slot + (int64_t)u * kBlock) >> 4;
-        s[u] = 0.0f;
-        if (grp < n_groups) s[u] = ld<true>(main_scales + grp);
+        const int64_t gc = grp < n_groups ? grp : n_groups - 1;
+        s[u] = ld<true>(main_scales + gc);
 #pragma unroll
         for (int p = 0; p < VPL; ++p) {
-            v[u][p] = f32x4{0.f, 0.f, 0.f, 0.f};
-            c[u][p] = 0;
-            if (grp < n_groups) {
-                v[u][p] = ld<true>(g_new + grp * VPG + p * 16 + lane16);
-                c[u][p] = ld<true>(main_codes + grp * VPG + p * 16 + lane16);
-            }
+            v[u][p] = ld<true>(g_new + gc * VPG + p * 16 + lane16);
+            c[u][p] = ld<true>(main_codes + gc * VPG + p * 16 + lane16);
         }
     }
 #pragma unroll
@@ -213,7 +212,7 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
                 if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
                 st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
             }
-            if (lane16 == 0) st<true>(out_scales + grp, scale);
+            if (lane16 == 0) st<AGOQ_SCALE_NT>(out_scales + grp, scale);
         }
     }
 }
@@ -264,7 +263,7 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
             u32 p1 = encode4_bytes<FP>(acc[4], acc[5], acc[6], acc[7], inv);
             if (FP && scale == 0.0f) p0 = p1 = 0;              // dead group: no signed zeros
             st<true>(out_codes + vi, u32x2{p0, p1});
-            if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
+            if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_SCALE_NT>(out_scales + vi / LANES, scale);
         }
     }
 }

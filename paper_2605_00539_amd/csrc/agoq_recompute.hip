@@ -27,6 +27,9 @@ constexpr int norm_max_block(int vpt)
 #ifndef AGOQ_NORM_DEPTH        // rows in flight beyond the one being reduced: 1 or 2
 #define AGOQ_NORM_DEPTH 2
 #endif
+#ifndef AGOQ_NORM_DEPTH56      // ... with 5- and 6-bit codes (three loads per vector)
+#define AGOQ_NORM_DEPTH56 1
+#endif
 #ifndef AGOQ_NORM_VPT8         // the same two for 8-bit codes, whose buffers are twice the size
 #define AGOQ_NORM_VPT8 2
 #endif
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     // Loads are unconditional (a lane past the end of the row re-reads the row's last vector
     // and uses scale 0, so it adds nothing to the row sum): a load under a branch would have
     // to be merged with the register's old value, which again waits for the data.
-    constexpr int kDepth = BITS == 8 ? AGOQ_NORM_DEPTH8 : AGOQ_NORM_DEPTH;
+    constexpr int kDepth = BITS == 8 ? AGOQ_NORM_DEPTH8 : BITS == 4 ? AGOQ_NORM_DEPTH : AGOQ_NORM_DEPTH56;
     struct RowBuf {
         Codes8<BITS> c[VPT];
         float sc[VPT];
