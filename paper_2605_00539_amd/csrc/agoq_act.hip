@@ -11,8 +11,17 @@ namespace {
 // the low nibbles exactly where 4-bit codes would go, the remaining high bits
 // (one byte or two bytes per lane) to a second plane that starts n_vec*4 bytes in.
 // ---------------------------------------------------------------------------
-template <int BITS, int GROUP, int UNROLL, bool FP>
-__device__ __forceinline__ void act_quant_tile(const u32x4* __restrict__ x, int64_t n_vec,
+// A tile runs in three phases with nothing moved across their borders: every load of the
+// lane; then everything that needs the loaded data; then the encoding and the stores.  A
+// load that is waited for after a store has been issued would also wait for that store to
+// be acknowledged (one counter orders both), which costs more than the load itself.
+// FULL: the whole tile lies inside the tensor and the code has no bounds test at all (with
+// one, the compiler sinks loads and arithmetic into the guarded store blocks and the
+// phases are gone).  Otherwise -- the one workgroup that straddles the end -- a lane past
+// the end re-reads the last vector, which is always in bounds, and its stores are masked;
+// lanes of one group are all inside or all outside.
+template <int BITS, int GROUP, int UNROLL, bool FP, bool FULL>
+__device__ __forceinline__ void act_quant_body(const u32x4* __restrict__ x, int64_t n_vec,
                                                void* __restrict__ codes, float* __restrict__ scales,
                                                unsigned block)
 {
@@ -25,16 +34,29 @@ __device__ __forceinline__ void act_quant_tile(const u32x4* __restrict__ x, int6
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        v[u] = u32x4{0, 0, 0, 0};
-        if (vi < n_vec) v[u] = ld<NTL>(x + vi);
+        v[u] = ld<NTL>(x + (FULL || vi < n_vec ? vi : n_vec - 1));
     }
+    float f[UNROLL][8];
+    u32 m[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) m[u] = group_max_bits<LANES>(unpack8_bf16(v[u], f[u]));
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        float f[8];
-        const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f));
-        quantize_store8<BITS, GROUP, FP, NTS>(f, m, vi, n_vec, vi < n_vec, codes, scales);
+        quantize_store8<BITS, GROUP, FP, NTS>(f[u], m[u], vi, n_vec, FULL || vi < n_vec, codes, scales);
     }
+}
+
+template <int BITS, int GROUP, int UNROLL, bool FP>
+__device__ __forceinline__ void act_quant_tile(const u32x4* __restrict__ x, int64_t n_vec,
+                                               void* __restrict__ codes, float* __restrict__ scales,
+                                               unsigned block)
+{
+    if (((int64_t)block + 1) * (AGOQ_AQ_BLOCK * UNROLL) <= n_vec)
+        act_quant_body<BITS, GROUP, UNROLL, FP, true>(x, n_vec, codes, scales, block);
+    else
+        act_quant_body<BITS, GROUP, UNROLL, FP, false>(x, n_vec, codes, scales, block);
 }
 
 template <int BITS, int GROUP, int UNROLL, bool FP = false>
@@ -49,8 +71,12 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* _
 // Activation dequantize: codes + scales -> bf16.  One lane produces 8 elements
 // (one 16-byte store).
 // ---------------------------------------------------------------------------
-template <int BITS, int GROUP, int UNROLL, bool FP>
-__device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
+// PACE: a lane waits for each store to be acknowledged before it starts on its next vector.
+// Measured to help in one case only, 8-bit codes of a tensor small enough for the whole
+// grid to be resident at once, where it keeps the burst of stores at the end of the single
+// generation of wavefronts from piling up.
+template <int BITS, int GROUP, int UNROLL, bool FP, bool FULL, bool PACE>
+__device__ __forceinline__ void act_dequant_body(const void* __restrict__ codes,
                                                  const float* __restrict__ scales, int64_t n_vec,
                                                  u32x4* __restrict__ y, unsigned block)
 {
@@ -60,17 +86,23 @@ __device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
     constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
     const int64_t base = (int64_t)block * (kBlock * UNROLL) + threadIdx.x;
 
+    // loads; decode (uses every loaded value); pack and store -- see act_quant_body
     Codes8<BITS> c[UNROLL];
     float s[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        s[u] = 0.0f;
-        if (vi < n_vec) {
-            c[u] = load_codes8<BITS, NTC>(codes, n_vec, vi);
-            s[u] = ld<NTSC>(scales + vi / LANES);
-        }
+        const int64_t vc = FULL || vi < n_vec ? vi : n_vec - 1;
+        c[u] = load_codes8<BITS, NTC>(codes, n_vec, vc);
+        s[u] = ld<NTSC>(scales + vc / LANES);
     }
+    // phase border: every loaded register is needed here, so every wait happens here
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        need_now(c[u]);
+        need_now(s[u]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
@@ -83,18 +115,31 @@ __device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) f[j] = __fmul_rn(q[j], s[u]);
-        if (vi < n_vec)
+        if (FULL || vi < n_vec)
             st<NTS>(y + vi, u32x4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
                                   pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])});
+        if (PACE && u + 1 < UNROLL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);   // the next vector's arithmetic stays behind this store
     }
 }
 
-template <int BITS, int GROUP, int UNROLL, bool FP = false>
+template <int BITS, int GROUP, int UNROLL, bool FP, bool PACE = false>
+__device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
+                                                 const float* __restrict__ scales, int64_t n_vec,
+                                                 u32x4* __restrict__ y, unsigned block)
+{
+    if (((int64_t)block + 1) * (AGOQ_DQ_BLOCK * UNROLL) <= n_vec)
+        act_dequant_body<BITS, GROUP, UNROLL, FP, true, PACE>(codes, scales, n_vec, y, block);
+    else
+        act_dequant_body<BITS, GROUP, UNROLL, FP, false, PACE>(codes, scales, n_vec, y, block);
+}
+
+template <int BITS, int GROUP, int UNROLL, bool FP = false, bool PACE = false>
 __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
                                                              const float* __restrict__ scales,
                                                              int64_t n_vec, u32x4* __restrict__ y)
 {
-    act_dequant_tile<BITS, GROUP, UNROLL, FP>(codes, scales, n_vec, y, blockIdx.x);
+    act_dequant_tile<BITS, GROUP, UNROLL, FP, PACE>(codes, scales, n_vec, y, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -253,10 +298,15 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    // measured: 4-bit codes run best with four vectors per lane at every size; 8-bit codes
-    // with four when the whole grid is resident at once and with one otherwise
+    // measured: a tensor small enough for (about) the whole grid to be resident at once runs
+    // best with four vectors per lane, 8-bit codes then with paced stores; larger tensors
+    // with two
+    // ("about": up to one and a half rounds; for 8-bit codes exactly one)
     int unroll = AGOQ_DQ_FORCE_UNROLL;
-    if (unroll == 0) unroll = (bits != 8 || fits_one_round(n_vec, AGOQ_DQ_BLOCK, 4)) ? 4 : 1;
+    const bool small = bits == 8 ? fits_rounds(n_vec, AGOQ_DQ_BLOCK, 4, 1, 1)
+                                 : fits_rounds(n_vec, AGOQ_DQ_BLOCK, 4, 3, 2);
+    if (unroll == 0) unroll = small ? 4 : 2;
+    const bool pace = small && bits == 8;
     const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
@@ -266,7 +316,12 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     case 2: act_dequant_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
     default: act_dequant_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break; \
     }
-    if (group == 128) {
+    if (pace && unroll == 4) {
+        if (group == 128)
+            act_dequant_kernel<8, 128, 4, false, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        else
+            act_dequant_kernel<8, 64, 4, false, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    } else if (group == 128) {
         switch (bits) {
         case 4: AGOQ_LAUNCH_DQ(4, 128) break;
         case 5: AGOQ_LAUNCH_DQ(5, 128) break;
@@ -310,14 +365,21 @@ int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, 
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    constexpr int U = 4;
-    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * U)), block(AGOQ_DQ_BLOCK);
+    const int unroll = fits_rounds(n_vec, AGOQ_DQ_BLOCK, 4, 3, 2) ? 4 : 2;   // as for 4-bit integer codes
+    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
-    if (group == 128)
-        act_dequant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
-    else
-        act_dequant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    if (group == 128) {
+        if (unroll == 4)
+            act_dequant_kernel<4, 128, 4, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        else
+            act_dequant_kernel<4, 128, 2, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    } else {
+        if (unroll == 4)
+            act_dequant_kernel<4, 64, 4, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+        else
+            act_dequant_kernel<4, 64, 2, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+    }
     return launch_status();
 }
 

@@ -335,6 +335,23 @@ struct Codes8<8> {
     uint64_t w = 0;
 };
 
+// Marks a point where a loaded value must have arrived: the compiler places the wait for
+// its load before this point (an empty statement that takes the value in a register).
+__device__ __forceinline__ void need_now(float v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void need_now(u32 v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void need_now(uint64_t v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void need_now(const u32x4& v) { asm volatile("" ::"v"(v)); }
+template <int BITS>
+__device__ __forceinline__ void need_now(const Codes8<BITS>& c)
+{
+    if constexpr (BITS == 8) {
+        asm volatile("" ::"v"(c.w));
+    } else {
+        asm volatile("" ::"v"(c.lo));
+        if (BITS != 4) asm volatile("" ::"v"(c.hi));
+    }
+}
+
 template <int BITS, bool NT>
 __device__ __forceinline__ Codes8<BITS> load_codes8(const void* codes, int64_t n_vec, int64_t vi)
 {
@@ -438,13 +455,14 @@ inline int compute_units()
     return cached[dev];
 }
 
-// True when a one-shot grid of `block`-thread workgroups with `unroll` vectors per lane is
-// resident on the chip all at once (2048 threads per compute unit for these small-register
-// kernels).
-inline bool fits_one_round(int64_t n_vec, int block, int unroll)
+// True when a one-shot grid of `block`-thread workgroups with `unroll` vectors per lane needs
+// at most num/den rounds of the chip (2048 lanes resident per compute unit for these
+// small-register kernels); 1/1 = the whole grid is resident at once.
+inline bool fits_rounds(int64_t n_vec, int block, int unroll, int num, int den)
 {
     const int64_t capacity = (int64_t)compute_units() * (2048 / block);
-    return (n_vec + (int64_t)block * unroll - 1) / ((int64_t)block * unroll) <= capacity;
+    const int64_t blocks = (n_vec + (int64_t)block * unroll - 1) / ((int64_t)block * unroll);
+    return blocks * den <= capacity * num;
 }
 
 }  // namespace

@@ -226,28 +226,34 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void grad_accumulate_bf16_kernel(
     constexpr int kBlock = AGOQ_AQ_BLOCK;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
+    // Loads are unconditional (lanes past the end re-read the last vector; only their stores
+    // are masked) and all issued before the first wait; the 8 code bytes stay one 64-bit
+    // register until they are decoded.
     u32x4 v[UNROLL];
-    u32x2 c[UNROLL];
+    uint64_t c[UNROLL];
     float s[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        v[u] = u32x4{0, 0, 0, 0};
-        c[u] = u32x2{0, 0};
-        s[u] = 0.0f;
-        if (vi < n_vec) {
-            v[u] = ld<true>(g_new + vi);
-            c[u] = ld<true>(main_codes + vi);
-            s[u] = ld<true>(main_scales + vi / LANES);
-        }
+        const int64_t vc = vi < n_vec ? vi : n_vec - 1;
+        v[u] = ld<true>(g_new + vc);
+        c[u] = ld<true>((const uint64_t*)main_codes + vc);
+        s[u] = ld<true>(main_scales + vc / LANES);
     }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        need_now(v[u]);
+        need_now(c[u]);
+        need_now(s[u]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         float acc[8], g[8], q0[4], q1[4];
         unpack8_bf16(v[u], g);
-        decode4_bytes<FP>(c[u][0], q0);
-        decode4_bytes<FP>(c[u][1], q1);
+        decode4_bytes<FP>((u32)c[u], q0);
+        decode4_bytes<FP>((u32)(c[u] >> 32), q1);
         u32 m = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {

@@ -194,20 +194,28 @@ __global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_silu_mul_kernel(
     constexpr int LANES = GROUP / 8;
     constexpr int kBlock = AGOQ_DQ_BLOCK;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    // loads (unconditional: a lane past the end re-reads the last vector and stores nothing),
+    // one point where all of them are waited for, then arithmetic and stores vector by vector
     Codes8<BITS_G> gc[UNROLL];
     Codes8<BITS_U> uc[UNROLL];
     float gs[UNROLL], us[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        gs[u] = us[u] = 0.0f;
-        if (vi < n_vec) {
-            gc[u] = load_codes8<BITS_G, true>(gate_codes, n_vec, vi);
-            uc[u] = load_codes8<BITS_U, true>(up_codes, n_vec, vi);
-            gs[u] = ld<false>(gate_scales + vi / LANES);
-            us[u] = ld<false>(up_scales + vi / LANES);
-        }
+        const int64_t vc = vi < n_vec ? vi : n_vec - 1;
+        gc[u] = load_codes8<BITS_G, true>(gate_codes, n_vec, vc);
+        uc[u] = load_codes8<BITS_U, true>(up_codes, n_vec, vc);
+        gs[u] = ld<false>(gate_scales + vc / LANES);
+        us[u] = ld<false>(up_scales + vc / LANES);
     }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        need_now(gc[u]);
+        need_now(uc[u]);
+        need_now(gs[u]);
+        need_now(us[u]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
