@@ -266,11 +266,7 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
 #define AGOQ_LAUNCH_AQ(B, G)                                                                     \
-    switch (unroll) {                                                                            \
-    case 4: act_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
-    case 2: act_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;   \
-    default: act_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec, codes, scales); break;  \
-    }
+    act_quant_kernel<B, G, AGOQ_AQ_UNROLL><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
     if (group == 128) {
         switch (bits) {
         case 4: AGOQ_LAUNCH_AQ(4, 128) break;
