@@ -3,7 +3,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libagoq.so")
+# AGOQ_LIBRARY names another build of the same library (a tuning variant); default: in-tree
+_LIB_PATH = os.environ.get("AGOQ_LIBRARY") or os.path.join(_HERE, "libagoq.so")
 _lib = None
 
 _I64 = ctypes.c_int64

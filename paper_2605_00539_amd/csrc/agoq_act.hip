@@ -266,7 +266,7 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
 #define AGOQ_LAUNCH_AQ(B, G)                                                                     \
-    act_quant_kernel<B, G, AGOQ_AQ_UNROLL><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+    act_quant_kernel<B, G, AGOQ_AQ_UNROLL><<<grid, block, kCapLds, st>>>(x, n_vec, codes, scales);
     if (group == 128) {
         switch (bits) {
         case 4: AGOQ_LAUNCH_AQ(4, 128) break;
@@ -306,17 +306,18 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
+    const size_t cap = (bits == 8 && !small) ? kCapDq8 : kCapLds;
 #define AGOQ_LAUNCH_DQ(B, G)                                                                      \
     switch (unroll) {                                                                             \
-    case 4: act_dequant_kernel<B, G, 4><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
-    case 2: act_dequant_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break;  \
-    default: act_dequant_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec, y); break; \
+    case 4: act_dequant_kernel<B, G, 4><<<grid, block, cap, st>>>(codes, scales, n_vec, y); break;  \
+    case 2: act_dequant_kernel<B, G, 2><<<grid, block, cap, st>>>(codes, scales, n_vec, y); break;  \
+    default: act_dequant_kernel<B, G, 1><<<grid, block, cap, st>>>(codes, scales, n_vec, y); break; \
     }
     if (pace && unroll == 4) {
         if (group == 128)
-            act_dequant_kernel<8, 128, 4, false, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+            act_dequant_kernel<8, 128, 4, false, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
         else
-            act_dequant_kernel<8, 64, 4, false, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+            act_dequant_kernel<8, 64, 4, false, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
     } else if (group == 128) {
         switch (bits) {
         case 4: AGOQ_LAUNCH_DQ(4, 128) break;
@@ -348,9 +349,9 @@ int agoq_fp4_act_quant(const void* x_bf16, int64_t numel, int group, void* codes
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     if (group == 128)
-        act_quant_kernel<4, 128, U, true><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+        act_quant_kernel<4, 128, U, true><<<grid, block, kCapLds, st>>>(x, n_vec, codes, scales);
     else
-        act_quant_kernel<4, 64, U, true><<<grid, block, 0, st>>>(x, n_vec, codes, scales);
+        act_quant_kernel<4, 64, U, true><<<grid, block, kCapLds, st>>>(x, n_vec, codes, scales);
     return launch_status();
 }
 
@@ -367,14 +368,14 @@ int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, 
     u32x4* y = (u32x4*)y_bf16;
     if (group == 128) {
         if (unroll == 4)
-            act_dequant_kernel<4, 128, 4, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+            act_dequant_kernel<4, 128, 4, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
         else
-            act_dequant_kernel<4, 128, 2, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+            act_dequant_kernel<4, 128, 2, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
     } else {
         if (unroll == 4)
-            act_dequant_kernel<4, 64, 4, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+            act_dequant_kernel<4, 64, 4, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
         else
-            act_dequant_kernel<4, 64, 2, true><<<grid, block, 0, st>>>(codes, scales, n_vec, y);
+            act_dequant_kernel<4, 64, 2, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
     }
     return launch_status();
 }
@@ -386,9 +387,9 @@ int agoq_act_quant_layer(const agoq_act_slot* slots, int count, int group, void*
     if (int rc = layer_args(slots, count, group, true, a, blocks)) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        act_quant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), 0, st>>>(a);
+        act_quant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLds, st>>>(a);
     else
-        act_quant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), 0, st>>>(a);
+        act_quant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLds, st>>>(a);
     return launch_status();
 }
 
@@ -399,9 +400,9 @@ int agoq_act_dequant_layer(const agoq_act_slot* slots, int count, int group, voi
     if (int rc = layer_args(slots, count, group, false, a, blocks)) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        act_dequant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), 0, st>>>(a);
+        act_dequant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), kCapLdq, st>>>(a);
     else
-        act_dequant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), 0, st>>>(a);
+        act_dequant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), kCapLdq, st>>>(a);
     return launch_status();
 }
 

@@ -92,6 +92,31 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_SCALE_NT          // scale stores (a few bytes per wavefront) streaming too, or cached
 #define AGOQ_SCALE_NT 1
 #endif
+#ifndef AGOQ_GB_BLOCK          // accumulate, bf16 addend
+#define AGOQ_GB_BLOCK 128
+#endif
+#ifndef AGOQ_GB_UNROLL
+#define AGOQ_GB_UNROLL 2
+#endif
+// Occupancy caps: dynamic LDS (KB per workgroup, never touched by the kernel) that limits
+// how many workgroups share a compute unit's 160 KB.  Measured per kernel: kernels that
+// read or write several streams at once run faster with fewer wavefronts in flight than
+// the registers allow.  0 = no cap.
+#ifndef AGOQ_GA_CAP_KB         // accumulate, fp32 addend: 6 workgroups of 256
+#define AGOQ_GA_CAP_KB 26
+#endif
+#ifndef AGOQ_SF_CAP_KB         // SiLU & Multiply forward + quantize: 8 workgroups of 128
+#define AGOQ_SF_CAP_KB 20
+#endif
+#ifndef AGOQ_LDQ_CAP_KB        // layer dequantize: 3 workgroups of 512
+#define AGOQ_LDQ_CAP_KB 48
+#endif
+#ifndef AGOQ_DQ8_CAP_KB        // dequantize of 8-bit codes, tensors beyond one round: 3 of 512
+#define AGOQ_DQ8_CAP_KB 48
+#endif
+#ifndef AGOQ_CAP_KB            // tuning: dynamic LDS (KB, never touched) per workgroup of the
+#define AGOQ_CAP_KB 0          // kernels that have no cap of their own; 0 = no cap
+#endif
 #ifndef AGOQ_GD_BLOCK          // gradient dequantize
 #define AGOQ_GD_BLOCK 512
 #endif
@@ -102,6 +127,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define AGOQ_GD_NTS 1
 #endif
 
+constexpr size_t kCapLds = (size_t)AGOQ_CAP_KB * 1024;
+constexpr size_t kCapGa = (size_t)AGOQ_GA_CAP_KB * 1024;
+constexpr size_t kCapSf = (size_t)AGOQ_SF_CAP_KB * 1024;
+constexpr size_t kCapLdq = (size_t)AGOQ_LDQ_CAP_KB * 1024;
+constexpr size_t kCapDq8 = (size_t)AGOQ_DQ8_CAP_KB * 1024;
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
 constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
 

@@ -420,9 +420,9 @@ int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t row
     const dim3 grid(norm_grid(rows, threads)), block(threads);
 #define AGOQ_LAUNCH_NORM(B, G)                                                                    \
     switch (vpt) {                                                                                \
-    case 1: act_dequant_rmsnorm_kernel<B, G, 1><<<grid, block, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    case 2: act_dequant_rmsnorm_kernel<B, G, 2><<<grid, block, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    default: act_dequant_rmsnorm_kernel<B, G, 4><<<grid, block, 0, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    case 1: act_dequant_rmsnorm_kernel<B, G, 1><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    case 2: act_dequant_rmsnorm_kernel<B, G, 2><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    default: act_dequant_rmsnorm_kernel<B, G, 4><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
     }
     if (group == 128) {
         switch (bits) {
@@ -462,9 +462,9 @@ int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, 
     u32x4* z = (u32x4*)z_bf16;
 #define AGOQ_LAUNCH_SILU(BG, BU)                                                                  \
     if (group == 128)                                                                             \
-        act_dequant_silu_mul_kernel<BG, BU, 128, U><<<grid, block, 0, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z); \
+        act_dequant_silu_mul_kernel<BG, BU, 128, U><<<grid, block, kCapLds, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z); \
     else                                                                                          \
-        act_dequant_silu_mul_kernel<BG, BU, 64, U><<<grid, block, 0, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
+        act_dequant_silu_mul_kernel<BG, BU, 64, U><<<grid, block, kCapLds, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
 #define AGOQ_SILU_UP(BG)                                                                          \
     switch (up_bits) {                                                                            \
     case 4: AGOQ_LAUNCH_SILU(BG, 4) break;                                                        \
@@ -508,9 +508,9 @@ int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const
     u32x4* y = (u32x4*)y_bf16;
 #define AGOQ_LAUNCH_NORM_FWD(B, G)                                                                \
     switch (vpt) {                                                                                \
-    case 1: rmsnorm_fwd_quant_kernel<B, G, 1><<<grid, block, 0, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, 0, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    default: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, 0, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 1: rmsnorm_fwd_quant_kernel<B, G, 1><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    default: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
     }
     if (group == 128) {
         switch (bits) {
@@ -554,9 +554,9 @@ int agoq_silu_mul_fwd_quant(const void* gate_bf16, const void* up_bf16, int64_t 
     u32x4* z = (u32x4*)z_bf16;
 #define AGOQ_LAUNCH_SILU_FWD(BG, BU)                                                              \
     if (group == 128)                                                                             \
-        silu_mul_fwd_quant_kernel<BG, BU, 128, U><<<grid, block, 0, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales); \
+        silu_mul_fwd_quant_kernel<BG, BU, 128, U><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales); \
     else                                                                                          \
-        silu_mul_fwd_quant_kernel<BG, BU, 64, U><<<grid, block, 0, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
+        silu_mul_fwd_quant_kernel<BG, BU, 64, U><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
 #define AGOQ_SILU_FWD_UP(BG)                                                                      \
     switch (up_bits) {                                                                            \
     case 4: AGOQ_LAUNCH_SILU_FWD(BG, 4) break;                                                    \
