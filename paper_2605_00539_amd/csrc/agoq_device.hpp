@@ -76,9 +76,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_RD_BLOCK          // reduce + requantize
 #define AGOQ_RD_BLOCK 512
 #endif
-#ifndef AGOQ_RD_KT_BLOCK       // the same when K is 4, 8 or 16 (all loads hoisted)
-#define AGOQ_RD_KT_BLOCK 256
-#endif
 #ifndef AGOQ_RD_NTC
 #define AGOQ_RD_NTC 1
 #endif

@@ -184,27 +184,27 @@ __global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_anyk_kernel(
 }
 
 // Launch of the reduce for either code book (arguments already checked).
-// Measured on K = 8 and 16 streams of 218M elements: the kernel is fastest with FEWER
-// wavefronts in flight than the registers allow -- two workgroups of 256 lanes per compute
-// unit, two vectors per lane (K = 8: 6.5 TB/s against 5.8 at full occupancy) -- presumably
-// because every resident wavefront keeps K DRAM pages open.  The cap is a dynamic LDS
-// allocation that no kernel touches: 64 KB per workgroup lets two share a compute unit's
-// 160 KB.  Small inputs (fewer than four workgroups per compute unit that way) take one
-// vector per lane so that the grid still covers the chip.
+// Measured on K = 8 and 16 streams of 7M to 218M elements: the kernel is fastest with
+// FEWER wavefronts in flight than the registers allow -- two workgroups per compute unit
+// (K = 8 on 218M elements: 6.5 TB/s against 5.8 at full occupancy) -- presumably because
+// every resident wavefront keeps K DRAM pages open.  The cap is a dynamic LDS allocation
+// that no kernel touches: 64 KB per workgroup lets two share a compute unit's 160 KB.
+// From 40M elements on the two workgroups are of 256 lanes with two vectors per lane, below
+// that of 512 lanes with one (+2 % at 27M elements, +10 % at 7M, -6 % at 218M).
 constexpr size_t kTwoPerCuLds = 64 * 1024;
+constexpr int64_t kReduceTwoVectorsFrom = 2500000;    // 16-element vectors
 template <bool FP>
 int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_scales,
                   int64_t stride_scales, int K, int64_t n_vec, int group, u32x4* oc,
                   float* out_scales, hipStream_t st)
 {
-    constexpr int B = AGOQ_RD_KT_BLOCK;
-    const bool two = n_vec >= (int64_t)compute_units() * 4 * B * 2;
+    const bool two = n_vec >= kReduceTwoVectorsFrom;
 #define AGOQ_LAUNCH_REDUCE(G, KT)                                                               \
     if (two)                                                                                    \
-        grad_reduce_kernel<G, KT, FP, B, 2><<<dim3(blocks_for(n_vec, B * 2)), dim3(B), kTwoPerCuLds, st>>>( \
+        grad_reduce_kernel<G, KT, FP, 256, 2><<<dim3(blocks_for(n_vec, 512)), dim3(256), kTwoPerCuLds, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales);           \
     else                                                                                        \
-        grad_reduce_kernel<G, KT, FP, B, 1><<<dim3(blocks_for(n_vec, B)), dim3(B), kTwoPerCuLds, st>>>( \
+        grad_reduce_kernel<G, KT, FP, 512, 1><<<dim3(blocks_for(n_vec, 512)), dim3(512), kTwoPerCuLds, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales)
 #define AGOQ_LAUNCH_REDUCE_G(G)                                                                 \
     switch (K) {                                                                                \

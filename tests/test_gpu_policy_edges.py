@@ -53,9 +53,8 @@ def test_dequant_around_the_resident_grid_thresholds(agoq, ref, bits):
 @pytest.mark.parametrize("K", [4, 8, 16])
 @pytest.mark.parametrize("group", [64, 128])
 def test_reduce_around_the_two_vector_threshold(agoq, ref, K, group):
-    # the reduce takes two vectors per lane from compute_units * 4 * 256 * 2 vectors of 16 on
-    cus = compute_units()
-    edge = cus * 4 * 256 * 2 * 16                # elements
+    # the reduce takes two vectors per lane from 2,500,000 vectors of 16 elements on
+    edge = 2500000 * 16 // 2048 * 2048           # elements, rounded to whole groups
     rng = np.random.default_rng(1000 + K)
     sizes = (edge - group, edge + 37 * group) if K == 16 else (edge - group, edge, edge + group, edge + 37 * group)
     for numel in sizes:
