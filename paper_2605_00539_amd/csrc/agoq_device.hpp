@@ -89,6 +89,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_SCALE_NT          // scale stores (a few bytes per wavefront) streaming too, or cached
 #define AGOQ_SCALE_NT 1
 #endif
+#ifndef AGOQ_SI_BLOCK          // SiLU & Multiply recompute
+#define AGOQ_SI_BLOCK 256
+#endif
+#ifndef AGOQ_SI_UNROLL
+#define AGOQ_SI_UNROLL 2
+#endif
 #ifndef AGOQ_GB_BLOCK          // accumulate, bf16 addend
 #define AGOQ_GB_BLOCK 128
 #endif
@@ -104,6 +110,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #endif
 #ifndef AGOQ_SF_CAP_KB         // SiLU & Multiply forward + quantize: 8 workgroups of 128
 #define AGOQ_SF_CAP_KB 20
+#endif
+#ifndef AGOQ_SI_CAP_KB         // SiLU & Multiply recompute
+#define AGOQ_SI_CAP_KB 0
 #endif
 #ifndef AGOQ_LDQ_CAP_KB        // layer dequantize: 3 workgroups of 512
 #define AGOQ_LDQ_CAP_KB 48
@@ -127,6 +136,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr size_t kCapLds = (size_t)AGOQ_CAP_KB * 1024;
 constexpr size_t kCapGa = (size_t)AGOQ_GA_CAP_KB * 1024;
 constexpr size_t kCapSf = (size_t)AGOQ_SF_CAP_KB * 1024;
+constexpr size_t kCapSi = (size_t)AGOQ_SI_CAP_KB * 1024;
 constexpr size_t kCapLdq = (size_t)AGOQ_LDQ_CAP_KB * 1024;
 constexpr size_t kCapDq8 = (size_t)AGOQ_DQ8_CAP_KB * 1024;
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23

@@ -186,13 +186,13 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
 // SiLU & Multiply recompute: z = bf16(u' * g' * sigmoid(g')), elementwise over the two
 // stored tensors (which may have different code widths).
 template <int BITS_G, int BITS_U, int GROUP, int UNROLL>
-__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_silu_mul_kernel(
+__global__ __launch_bounds__(AGOQ_SI_BLOCK) void act_dequant_silu_mul_kernel(
     const void* __restrict__ gate_codes, const float* __restrict__ gate_scales,
     const void* __restrict__ up_codes, const float* __restrict__ up_scales, int64_t n_vec,
     u32x4* __restrict__ z)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = AGOQ_DQ_BLOCK;
+    constexpr int kBlock = AGOQ_SI_BLOCK;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
     // loads (unconditional: a lane past the end re-reads the last vector and stores nothing),
     // one point where all of them are waited for, then arithmetic and stores vector by vector
@@ -456,15 +456,15 @@ int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, 
         misaligned(up_scales) || misaligned(z_bf16))
         return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    constexpr int U = 2;
-    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * U)), block(AGOQ_DQ_BLOCK);
+    constexpr int U = AGOQ_SI_UNROLL;
+    const dim3 grid(blocks_for(n_vec, AGOQ_SI_BLOCK * U)), block(AGOQ_SI_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     u32x4* z = (u32x4*)z_bf16;
 #define AGOQ_LAUNCH_SILU(BG, BU)                                                                  \
     if (group == 128)                                                                             \
-        act_dequant_silu_mul_kernel<BG, BU, 128, U><<<grid, block, kCapLds, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z); \
+        act_dequant_silu_mul_kernel<BG, BU, 128, U><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z); \
     else                                                                                          \
-        act_dequant_silu_mul_kernel<BG, BU, 64, U><<<grid, block, kCapLds, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
+        act_dequant_silu_mul_kernel<BG, BU, 64, U><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
 #define AGOQ_SILU_UP(BG)                                                                          \
     switch (up_bits) {                                                                            \
     case 4: AGOQ_LAUNCH_SILU(BG, 4) break;                                                        \
