@@ -121,6 +121,56 @@ int main() {
         HIP_OK(hipFree(dg)); HIP_OK(hipFree(dic)); HIP_OK(hipFree(dis)); HIP_OK(hipFree(dgc));
         HIP_OK(hipFree(drc)); HIP_OK(hipFree(dgs)); HIP_OK(hipFree(drs));
     }
+    // one launch for a layer: three tensors of different sizes at three widths
+    {
+        const int group = 128;
+        const int bits[3] = {8, 4, 6};
+        const int64_t numel[3] = {(int64_t)group * 1031, (int64_t)group * 4099, (int64_t)group * 517};
+        std::vector<uint16_t> x[3], y[3], y_ref[3];
+        std::vector<uint8_t> c[3], c_ref[3];
+        std::vector<float> sc[3], sc_ref[3];
+        agoq_act_slot slots[3];
+        for (int t = 0; t < 3; ++t) {
+            const int64_t n = numel[t];
+            x[t].resize(n); y[t].resize(n); y_ref[t].resize(n);
+            c[t].resize(n * bits[t] / 8); c_ref[t].resize(n * bits[t] / 8);
+            sc[t].resize(n / group); sc_ref[t].resize(n / group);
+            for (auto& v : x[t]) v = to_bf16_trunc(bell() * ((lcg() & 63) == 0 ? 30.f : 1.f));
+            agoq_ref_act_quant(x[t].data(), n, group, bits[t], c_ref[t].data(), sc_ref[t].data());
+            agoq_ref_act_dequant(c_ref[t].data(), sc_ref[t].data(), n, group, bits[t], y_ref[t].data());
+            uint8_t* dc = nullptr;
+            float* ds = nullptr;
+            HIP_OK(hipMalloc(&dc, c[t].size()));
+            HIP_OK(hipMalloc(&ds, sc[t].size() * 4));
+            slots[t].bf16 = dev_copy(x[t]);
+            slots[t].codes = dc;
+            slots[t].scales = ds;
+            slots[t].numel = n;
+            slots[t].bits = bits[t];
+            if (!slots[t].bf16) return 2;
+        }
+        int rc = agoq_act_quant_layer(slots, 3, group, stream);
+        if (rc != AGOQ_OK) { printf("status %d: %s\n", rc, agoq_strerror(rc)); return 2; }
+        HIP_OK(hipStreamSynchronize(stream));
+        for (int t = 0; t < 3; ++t)      // wipe the inputs: the dequantize must rewrite them
+            HIP_OK(hipMemset(slots[t].bf16, 0xFF, numel[t] * 2));
+        rc = agoq_act_dequant_layer(slots, 3, group, stream);
+        if (rc != AGOQ_OK) { printf("status %d: %s\n", rc, agoq_strerror(rc)); return 2; }
+        HIP_OK(hipStreamSynchronize(stream));
+        bool ok = true;
+        for (int t = 0; t < 3; ++t) {
+            HIP_OK(hipMemcpy(c[t].data(), slots[t].codes, c[t].size(), hipMemcpyDeviceToHost));
+            HIP_OK(hipMemcpy(sc[t].data(), slots[t].scales, sc[t].size() * 4, hipMemcpyDeviceToHost));
+            HIP_OK(hipMemcpy(y[t].data(), slots[t].bf16, numel[t] * 2, hipMemcpyDeviceToHost));
+            ok = ok && c[t] == c_ref[t] && !memcmp(sc[t].data(), sc_ref[t].data(), sc[t].size() * 4) &&
+                 y[t] == y_ref[t];
+            HIP_OK(hipFree(slots[t].bf16)); HIP_OK(hipFree(slots[t].codes)); HIP_OK(hipFree(slots[t].scales));
+        }
+        printf("layer launch, 3 tensors at 8/4/6 bits: %s\n", ok ? "match" : "MISMATCH");
+        failures += !ok;
+        if (agoq_act_quant_layer(slots, 0, group, stream) != AGOQ_ERR_COUNT) ++failures;
+        if (agoq_act_quant_layer(slots, 9, group, stream) != AGOQ_ERR_COUNT) ++failures;
+    }
     // error paths: nothing launched
     if (agoq_act_quant(nullptr, 128, 128, 4, nullptr, nullptr, nullptr) != AGOQ_ERR_NULL) ++failures;
     HIP_OK(hipStreamDestroy(stream));
