@@ -206,13 +206,31 @@ int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_
     else                                                                                        \
         grad_reduce_kernel<G, KT, FP, 512, 1><<<dim3(blocks_for(n_vec, 512)), dim3(512), kTwoPerCuLds, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales)
+#ifndef AGOQ_RD_SMALLK_BLOCK
+#define AGOQ_RD_SMALLK_BLOCK 256
+#endif
+#ifndef AGOQ_RD_SMALLK_RU
+#define AGOQ_RD_SMALLK_RU 2
+#endif
+#ifndef AGOQ_RD_SMALLK_CAP_KB
+#define AGOQ_RD_SMALLK_CAP_KB 0
+#endif
+    // K = 1, 2 (and 3 in the run-time-K kernel): too few loads per vector to fill the memory
+    // pipes under a cap; two vectors per lane and full occupancy instead (K = 1: 5.5 TB/s
+    // against 3.9 capped, K = 2: 5.8 against 4.5, K = 3: 6.1 against 4.8)
+#define AGOQ_LAUNCH_REDUCE_SMALLK(G, KT)                                                        \
+    grad_reduce_kernel<G, KT, FP, AGOQ_RD_SMALLK_BLOCK, AGOQ_RD_SMALLK_RU>                      \
+        <<<dim3(blocks_for(n_vec, AGOQ_RD_SMALLK_BLOCK * AGOQ_RD_SMALLK_RU)), dim3(AGOQ_RD_SMALLK_BLOCK), (size_t)AGOQ_RD_SMALLK_CAP_KB * 1024, st>>>( \
+            in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales)
 #define AGOQ_LAUNCH_REDUCE_G(G)                                                                 \
     switch (K) {                                                                                \
+    case 1: AGOQ_LAUNCH_REDUCE_SMALLK(G, 1); break;                                             \
+    case 2: AGOQ_LAUNCH_REDUCE_SMALLK(G, 2); break;                                             \
     case 4: AGOQ_LAUNCH_REDUCE(G, 4); break;                                                    \
     case 8: AGOQ_LAUNCH_REDUCE(G, 8); break;                                                    \
     case 16: AGOQ_LAUNCH_REDUCE(G, 16); break;                                                  \
     default:                                                                                    \
-        grad_reduce_anyk_kernel<G, FP><<<dim3(blocks_for(n_vec, AGOQ_RD_BLOCK)), dim3(AGOQ_RD_BLOCK), kTwoPerCuLds, st>>>( \
+        grad_reduce_anyk_kernel<G, FP><<<dim3(blocks_for(n_vec, AGOQ_RD_BLOCK)), dim3(AGOQ_RD_BLOCK), K < 4 ? 0 : kTwoPerCuLds, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, K, n_vec, oc, out_scales);        \
         break;                                                                                  \
     }
@@ -222,6 +240,7 @@ int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_
         AGOQ_LAUNCH_REDUCE_G(64)
     }
 #undef AGOQ_LAUNCH_REDUCE_G
+#undef AGOQ_LAUNCH_REDUCE_SMALLK
 #undef AGOQ_LAUNCH_REDUCE
     return launch_status();
 }
