@@ -111,6 +111,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_SF_CAP_KB         // SiLU & Multiply forward + quantize: 8 workgroups of 128
 #define AGOQ_SF_CAP_KB 20
 #endif
+#ifndef AGOQ_GD_CAP_KB         // gradient dequantize
+#define AGOQ_GD_CAP_KB 0
+#endif
 #ifndef AGOQ_SI_CAP_KB         // SiLU & Multiply recompute
 #define AGOQ_SI_CAP_KB 0
 #endif
@@ -127,7 +130,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define AGOQ_GD_BLOCK 512
 #endif
 #ifndef AGOQ_GD_UNROLL
-#define AGOQ_GD_UNROLL 1
+#define AGOQ_GD_UNROLL 2
 #endif
 #ifndef AGOQ_GD_NTS
 #define AGOQ_GD_NTS 1
@@ -136,6 +139,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr size_t kCapLds = (size_t)AGOQ_CAP_KB * 1024;
 constexpr size_t kCapGa = (size_t)AGOQ_GA_CAP_KB * 1024;
 constexpr size_t kCapSf = (size_t)AGOQ_SF_CAP_KB * 1024;
+constexpr size_t kCapGd = (size_t)AGOQ_GD_CAP_KB * 1024;
 constexpr size_t kCapSi = (size_t)AGOQ_SI_CAP_KB * 1024;
 constexpr size_t kCapLdq = (size_t)AGOQ_LDQ_CAP_KB * 1024;
 constexpr size_t kCapDq8 = (size_t)AGOQ_DQ8_CAP_KB * 1024;

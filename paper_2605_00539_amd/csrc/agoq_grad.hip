@@ -379,17 +379,24 @@ __global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* 
     constexpr int LANES = GROUP / 4;      // lanes per group
     constexpr int kBlock = AGOQ_GD_BLOCK;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    // loads (unconditional: a lane past the end re-reads the last vector and stores nothing),
+    // one point where all of them are waited for, then arithmetic and stores vector by vector
     u32 c[UNROLL];
     float s[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        c[u] = 0;
-        s[u] = 0.0f;
-        if (vi < n_vec) {
-            c[u] = ld<true>(codes + vi);
-            s[u] = ld<false>(scales + vi / LANES);
+        const int64_t vc = vi < n_vec ? vi : n_vec - 1;
+        c[u] = ld<true>(codes + vc);
+        s[u] = ld<false>(scales + vc / LANES);
+    }
+    if (UNROLL > 1) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            need_now(c[u]);
+            need_now(s[u]);
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -400,6 +407,7 @@ __global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* 
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(q[j], s[u]);
         if (vi < n_vec) st<AGOQ_GD_NTS>(out + vi, o);
+        if (UNROLL > 1) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -510,10 +518,10 @@ int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, i
     const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        grad_dequant_kernel<128, U><<<grid, block, kCapLds, st>>>((const u32*)codes, scales, n_vec,
+        grad_dequant_kernel<128, U><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
                                                             (f32x4*)out);
     else
-        grad_dequant_kernel<64, U><<<grid, block, kCapLds, st>>>((const u32*)codes, scales, n_vec,
+        grad_dequant_kernel<64, U><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
                                                            (f32x4*)out);
     return launch_status();
 }
@@ -548,10 +556,10 @@ int agoq_fp8_grad_dequant(const uint8_t* codes, const float* scales, int64_t num
     const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        grad_dequant_kernel<128, U, true><<<grid, block, kCapLds, st>>>((const u32*)codes, scales, n_vec,
+        grad_dequant_kernel<128, U, true><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
                                                                   (f32x4*)out);
     else
-        grad_dequant_kernel<64, U, true><<<grid, block, kCapLds, st>>>((const u32*)codes, scales, n_vec,
+        grad_dequant_kernel<64, U, true><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
                                                                  (f32x4*)out);
     return launch_status();
 }
