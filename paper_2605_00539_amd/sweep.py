@@ -212,7 +212,7 @@ def main():
         del xs, ys, cs, ss, base, qs, ds
         torch.cuda.empty_cache()
 
-    def grad_case(config, n, sigma, spike_frac, spike_scale, seed, K, group, share=True, fp8=False):
+    def grad_case(config, n, sigma, spike_frac, spike_scale, seed, K, group, share=True, fp8=False, kscan=False):
         g = [wl.grad_device(n, seed + i, sigma, spike_frac, spike_scale) for i in range(2 if n > (1 << 26) else 8)]
         nout = slots_for(n, floor=3)
         ocs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nout)]
@@ -300,6 +300,19 @@ def main():
             us = timed(shard_raw, args.launches, args.reps)
             report(config, "grad_reduce_requant", "K=%d share n=%d g%d" % (K, ns, group), us,
                    algo_red(ns, K, group))
+        if kscan:
+            # other chunk counts on the shard size (random codes and scales: timing only)
+            ns = n // 8
+            for Kx in (1, 2, 3, 5, 12, 32, 64):
+                nsl = max(1, -(-(GiB + GiB // 2) // (Kx * ns)))
+                bufs = [(torch.randint(-127, 128, (Kx, ns), device=dev, dtype=torch.int8),
+                         torch.rand((Kx, ns // group), device=dev, dtype=torch.float32) * 1e-5 + 1e-8)
+                        for _ in range(min(nsl, 8))]
+                us = timed(lambda i: agoq.grad_reduce_requant(bufs[i % len(bufs)][0], bufs[i % len(bufs)][1], ns, group,
+                                                              out_codes=ocs[i % nout][:ns], out_scales=oss[i % nout][:ns // group]),
+                           args.launches, args.reps)
+                report(config, "grad_reduce_requant", "K=%d n=%d g%d" % (Kx, ns, group), us, algo_red(ns, Kx, group))
+                del bufs
         del ins, g, ocs, oss
 
     C = wl.CONFIGS
@@ -323,7 +336,7 @@ def main():
     if 3 in wanted:
         c = C["llama8b_grad"]
         grad_case("3-8B-grad", c["n"], c["sigma"], c["spike_frac"], c["spike_scale"], c["seed"], c["K"],
-                  c["group"], fp8=True)
+                  c["group"], fp8=True, kscan=True)
     # config 4: 32B-shaped activations, both group sizes
     if 4 in wanted:
         c = C["llama32b_act"]
