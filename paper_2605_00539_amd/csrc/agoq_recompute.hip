@@ -375,21 +375,29 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void silu_mul_fwd_quant_kernel(
     }
 }
 
-// Launch shape of the row kernels: VPT vectors per lane (the preferred count, doubled
-// while a row would need more than 1024 lanes) and the number of lanes, a whole number of
-// wavefronts.
+// Launch shape of the row kernels: VPT vectors per lane and the number of lanes, a whole
+// number of wavefronts.  VPT is the preferred count, or half of it when that leaves fewer
+// lanes idle in the last wavefront (640 vectors: 4 per lane would idle a sixth of the
+// lanes, 2 per lane none), doubled while a row would need more than 1024 lanes.
+inline int norm_lanes(int vecs_per_row, int vpt) { return ((vecs_per_row + vpt - 1) / vpt + 63) / 64 * 64; }
 inline void norm_launch_shape(int vecs_per_row, int preferred_vpt, int& vpt, int& threads)
 {
     vpt = preferred_vpt;
+    if (vpt >= 2 && norm_lanes(vecs_per_row, vpt / 2) * (vpt / 2) < norm_lanes(vecs_per_row, vpt) * vpt &&
+        norm_lanes(vecs_per_row, vpt / 2) <= kNormMaxBlock)
+        vpt /= 2;
     while ((vecs_per_row + vpt - 1) / vpt > kNormMaxBlock) vpt *= 2;
-    threads = ((vecs_per_row + vpt - 1) / vpt + 63) / 64 * 64;
+    threads = norm_lanes(vecs_per_row, vpt);
 }
 
-// Workgroups of a row kernel that walks its rows: as many as are resident at once.
-inline unsigned norm_grid(int64_t rows, int threads)
+// Workgroups of a row kernel that walks its rows: as many as are resident at once when
+// every compute unit holds AGOQ_NORM_RESIDENT lanes -- one workgroup per unit for wide
+// rows (workgroups of six wavefronts or more) when two further rows are in flight
+// (measured +2-4 % on 14336-wide rows; with one row in flight it costs 9 %).
+inline unsigned norm_grid(int64_t rows, int threads, int depth)
 {
-    const int per_cu = AGOQ_NORM_RESIDENT / threads > 0 ? AGOQ_NORM_RESIDENT / threads : 1;
-    const int64_t resident = (int64_t)compute_units() * per_cu;
+    const int per_cu = (threads >= 384 && depth >= 2) ? 1 : AGOQ_NORM_RESIDENT / threads;
+    const int64_t resident = (int64_t)compute_units() * (per_cu > 0 ? per_cu : 1);
     return (unsigned)(rows < resident ? rows : resident);
 }
 
@@ -417,7 +425,8 @@ int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t row
     u32x4* y = (u32x4*)y_bf16;
     int vpt, threads;
     norm_launch_shape(vecs_per_row, bits == 8 ? AGOQ_NORM_VPT8 : AGOQ_NORM_VPT, vpt, threads);
-    const dim3 grid(norm_grid(rows, threads)), block(threads);
+    const int depth = bits == 8 ? AGOQ_NORM_DEPTH8 : bits == 4 ? AGOQ_NORM_DEPTH : AGOQ_NORM_DEPTH56;
+    const dim3 grid(norm_grid(rows, threads, depth)), block(threads);
 #define AGOQ_LAUNCH_NORM(B, G)                                                                    \
     switch (vpt) {                                                                                \
     case 1: act_dequant_rmsnorm_kernel<B, G, 1><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
@@ -501,7 +510,7 @@ int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const
     const float inv_cols = 1.0f / (float)cols;
     int vpt, threads;
     norm_launch_shape(vecs_per_row, AGOQ_NORM_FWD_VPT, vpt, threads);
-    const dim3 grid(norm_grid(rows, threads)), block(threads);
+    const dim3 grid(norm_grid(rows, threads, AGOQ_NORM_FWD_DEPTH)), block(threads);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     const f32x4* gm = (const f32x4*)gamma;
