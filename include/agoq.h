@@ -237,6 +237,20 @@ int agoq_fp4_act_quant(const void *x_bf16, int64_t numel, int group, void *codes
                        void *stream);
 int agoq_fp4_act_dequant(const void *codes, const float *scales, int64_t numel, int group,
                          void *y_bf16, void *stream);
+/* The four calls fused with RMSNorm and SiLU & Multiply, on E2M1 codes (arguments as in the
+ * integer forms above, without the `bits` arguments; same limits, same error codes). */
+int agoq_fp4_act_dequant_rmsnorm(const void *codes, const float *scales, int64_t rows, int64_t cols,
+                                 int group, const float *gamma, float eps, void *y_bf16,
+                                 float *r_out, void *stream);
+int agoq_fp4_act_dequant_silu_mul(const void *gate_codes, const float *gate_scales,
+                                  const void *up_codes, const float *up_scales, int64_t numel,
+                                  int group, void *z_bf16, void *stream);
+int agoq_fp4_rmsnorm_fwd_quant(const void *x_bf16, int64_t rows, int64_t cols, const float *gamma,
+                               float eps, int group, void *y_bf16, float *r_out, void *codes,
+                               float *scales, void *stream);
+int agoq_fp4_silu_mul_fwd_quant(const void *gate_bf16, const void *up_bf16, int64_t numel, int group,
+                                void *z_bf16, void *gate_codes, float *gate_scales, void *up_codes,
+                                float *up_scales, void *stream);
 int agoq_fp8_grad_quant(const float *grad, int64_t numel, int group, uint8_t *codes, float *scales,
                         void *stream);
 int agoq_fp8_grad_dequant(const uint8_t *codes, const float *scales, int64_t numel, int group,

@@ -54,6 +54,10 @@ def load_library():
     L.agoq_silu_mul_fwd_quant.argtypes = [_P, _P, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _P]
     L.agoq_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
+    L.agoq_fp4_act_dequant_rmsnorm.argtypes = [_P, _P, _I64, _I64, _INT, _P, ctypes.c_float, _P, _P, _P]
+    L.agoq_fp4_act_dequant_silu_mul.argtypes = [_P, _P, _P, _P, _I64, _INT, _P, _P]
+    L.agoq_fp4_rmsnorm_fwd_quant.argtypes = [_P, _I64, _I64, _P, ctypes.c_float, _INT, _P, _P, _P, _P, _P]
+    L.agoq_fp4_silu_mul_fwd_quant.argtypes = [_P, _P, _I64, _INT, _P, _P, _P, _P, _P, _P]
     L.agoq_fp4_act_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
     L.agoq_fp4_act_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
     L.agoq_fp8_grad_quant.argtypes = [_P, _I64, _INT, _P, _P, _P]
@@ -223,8 +227,9 @@ def act_dequant_layer(codes_list, scales_list, numels, group, bits_list, outs=No
 
 
 def act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, gamma, eps, out=None, r_out=None,
-                        stream=None):
-    """Stored RMSNorm input -> (y bf16 [rows, cols] = gamma * x' / r, r float32 [rows])."""
+                        stream=None, fp4=False):
+    """Stored RMSNorm input -> (y bf16 [rows, cols] = gamma * x' / r, r float32 [rows]).
+    fp4=True: the codes are E2M1 (bits must be 4)."""
     import torch
     L = load_library()
     _dev(codes, torch.uint8, "codes")
@@ -239,16 +244,25 @@ def act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, gamma, eps, out=
     _dev(out, torch.bfloat16, "out")
     _dev(r_out, torch.float32, "r_out")
     with _on_device(codes.device):
-        _check(L.agoq_act_dequant_rmsnorm(
-            _raw(codes.data_ptr()), _raw(scales.data_ptr()), rows, cols, group, bits,
-            _raw(gamma.data_ptr()), float(eps), _raw(out.data_ptr()), _raw(r_out.data_ptr()),
-            _stream(stream)))
+        if fp4:
+            if bits != 4:
+                raise ValueError("E2M1 codes are 4 bits wide")
+            _check(L.agoq_fp4_act_dequant_rmsnorm(
+                _raw(codes.data_ptr()), _raw(scales.data_ptr()), rows, cols, group,
+                _raw(gamma.data_ptr()), float(eps), _raw(out.data_ptr()), _raw(r_out.data_ptr()),
+                _stream(stream)))
+        else:
+            _check(L.agoq_act_dequant_rmsnorm(
+                _raw(codes.data_ptr()), _raw(scales.data_ptr()), rows, cols, group, bits,
+                _raw(gamma.data_ptr()), float(eps), _raw(out.data_ptr()), _raw(r_out.data_ptr()),
+                _stream(stream)))
     return out, r_out
 
 
 def act_dequant_silu_mul(gate_codes, gate_scales, gate_bits, up_codes, up_scales, up_bits, numel,
-                         group, out=None, stream=None):
-    """Stored gate and up tensors -> z bf16 [numel] = up' * gate' * sigmoid(gate')."""
+                         group, out=None, stream=None, fp4=False):
+    """Stored gate and up tensors -> z bf16 [numel] = up' * gate' * sigmoid(gate').
+    fp4=True: both tensors hold E2M1 codes (both widths must be 4)."""
     import torch
     L = load_library()
     _dev(gate_codes, torch.uint8, "gate_codes")
@@ -259,15 +273,23 @@ def act_dequant_silu_mul(gate_codes, gate_scales, gate_bits, up_codes, up_scales
         out = torch.empty(numel, dtype=torch.bfloat16, device=gate_codes.device)
     _dev(out, torch.bfloat16, "out")
     with _on_device(gate_codes.device):
-        _check(L.agoq_act_dequant_silu_mul(
-            _raw(gate_codes.data_ptr()), _raw(gate_scales.data_ptr()), gate_bits,
-            _raw(up_codes.data_ptr()), _raw(up_scales.data_ptr()), up_bits, numel, group,
-            _raw(out.data_ptr()), _stream(stream)))
+        if fp4:
+            if gate_bits != 4 or up_bits != 4:
+                raise ValueError("E2M1 codes are 4 bits wide")
+            _check(L.agoq_fp4_act_dequant_silu_mul(
+                _raw(gate_codes.data_ptr()), _raw(gate_scales.data_ptr()), _raw(up_codes.data_ptr()),
+                _raw(up_scales.data_ptr()), numel, group, _raw(out.data_ptr()), _stream(stream)))
+        else:
+            _check(L.agoq_act_dequant_silu_mul(
+                _raw(gate_codes.data_ptr()), _raw(gate_scales.data_ptr()), gate_bits,
+                _raw(up_codes.data_ptr()), _raw(up_scales.data_ptr()), up_bits, numel, group,
+                _raw(out.data_ptr()), _stream(stream)))
     return out
 
 
-def rmsnorm_fwd_quant(x, gamma, eps, group, bits, stream=None):
-    """x bf16 [rows, cols] -> (y bf16 [rows, cols], r float32 [rows], codes uint8, scales float32)."""
+def rmsnorm_fwd_quant(x, gamma, eps, group, bits, stream=None, fp4=False):
+    """x bf16 [rows, cols] -> (y bf16 [rows, cols], r float32 [rows], codes uint8, scales float32).
+    fp4=True: E2M1 codes (bits must be 4)."""
     import torch
     L = load_library()
     x = _dev(x, torch.bfloat16, "x")
@@ -281,15 +303,24 @@ def rmsnorm_fwd_quant(x, gamma, eps, group, bits, stream=None):
     codes = torch.empty(max(n * bits // 8, 1), dtype=torch.uint8, device=x.device)
     scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
     with _on_device(x.device):
-        _check(L.agoq_rmsnorm_fwd_quant(
-            _raw(x.data_ptr()), rows, cols, _raw(gamma.data_ptr()), float(eps), group, bits,
-            _raw(y.data_ptr()), _raw(r.data_ptr()), _raw(codes.data_ptr()), _raw(scales.data_ptr()),
-            _stream(stream)))
+        if fp4:
+            if bits != 4:
+                raise ValueError("E2M1 codes are 4 bits wide")
+            _check(L.agoq_fp4_rmsnorm_fwd_quant(
+                _raw(x.data_ptr()), rows, cols, _raw(gamma.data_ptr()), float(eps), group,
+                _raw(y.data_ptr()), _raw(r.data_ptr()), _raw(codes.data_ptr()),
+                _raw(scales.data_ptr()), _stream(stream)))
+        else:
+            _check(L.agoq_rmsnorm_fwd_quant(
+                _raw(x.data_ptr()), rows, cols, _raw(gamma.data_ptr()), float(eps), group, bits,
+                _raw(y.data_ptr()), _raw(r.data_ptr()), _raw(codes.data_ptr()),
+                _raw(scales.data_ptr()), _stream(stream)))
     return y, r, codes, scales
 
 
-def silu_mul_fwd_quant(gate, up, group, gate_bits, up_bits, stream=None):
-    """gate, up bf16 -> (z bf16, gate_codes, gate_scales, up_codes, up_scales)."""
+def silu_mul_fwd_quant(gate, up, group, gate_bits, up_bits, stream=None, fp4=False):
+    """gate, up bf16 -> (z bf16, gate_codes, gate_scales, up_codes, up_scales).
+    fp4=True: E2M1 codes for both (both widths must be 4)."""
     import torch
     L = load_library()
     gate = _dev(gate, torch.bfloat16, "gate")
@@ -303,10 +334,18 @@ def silu_mul_fwd_quant(gate, up, group, gate_bits, up_bits, stream=None):
     gs = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=gate.device)
     us = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=gate.device)
     with _on_device(gate.device):
-        _check(L.agoq_silu_mul_fwd_quant(
-            _raw(gate.data_ptr()), _raw(up.data_ptr()), n, group, gate_bits, up_bits,
-            _raw(z.data_ptr()), _raw(gc.data_ptr()), _raw(gs.data_ptr()), _raw(uc.data_ptr()),
-            _raw(us.data_ptr()), _stream(stream)))
+        if fp4:
+            if gate_bits != 4 or up_bits != 4:
+                raise ValueError("E2M1 codes are 4 bits wide")
+            _check(L.agoq_fp4_silu_mul_fwd_quant(
+                _raw(gate.data_ptr()), _raw(up.data_ptr()), n, group, _raw(z.data_ptr()),
+                _raw(gc.data_ptr()), _raw(gs.data_ptr()), _raw(uc.data_ptr()), _raw(us.data_ptr()),
+                _stream(stream)))
+        else:
+            _check(L.agoq_silu_mul_fwd_quant(
+                _raw(gate.data_ptr()), _raw(up.data_ptr()), n, group, gate_bits, up_bits,
+                _raw(z.data_ptr()), _raw(gc.data_ptr()), _raw(gs.data_ptr()), _raw(uc.data_ptr()),
+                _raw(us.data_ptr()), _stream(stream)))
     return z, gc, gs, uc, us
 
 

@@ -425,22 +425,29 @@ __device__ __forceinline__ float decode8(const Codes8<BITS>& c, int j)
 }
 
 // x' = bf16(code * scale) for the lane's 8 elements, as four words of two bf16 each
-// (element 2k in the low half of word k).
-template <int BITS>
+// (element 2k in the low half of word k).  FP: the codes are E2M1 nibbles.
+template <int BITS, bool FP = false>
 __device__ __forceinline__ void dequant8_packed(const Codes8<BITS>& c, float scale, u32 (&w)[4])
 {
+    static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
+    float q[8];
+    if constexpr (FP) {
+        decode8_e2m1(c.lo, q);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = decode8<BITS>(c, j);
+    }
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-        w[k] = pack_bf16x2(__fmul_rn(decode8<BITS>(c, 2 * k), scale),
-                           __fmul_rn(decode8<BITS>(c, 2 * k + 1), scale));
+        w[k] = pack_bf16x2(__fmul_rn(q[2 * k], scale), __fmul_rn(q[2 * k + 1], scale));
 }
 
 // The same as fp32 values.
-template <int BITS>
+template <int BITS, bool FP = false>
 __device__ __forceinline__ void dequant8_bf16(const Codes8<BITS>& c, float scale, float (&x)[8])
 {
     u32 w[4];
-    dequant8_packed<BITS>(c, scale, w);
+    dequant8_packed<BITS, FP>(c, scale, w);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         x[2 * k] = as_f32(w[k] << 16);

@@ -85,7 +85,7 @@ __device__ __forceinline__ float sumsq8(const u32 (&xp)[4], float ss)
     return ss;
 }
 
-template <int BITS, int GROUP, int VPT>
+template <int BITS, int GROUP, int VPT, bool FP = false>
 __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kernel(
     const void* __restrict__ codes, const float* __restrict__ scales, int64_t n_vec_total,
     int64_t rows, int vecs_per_row, const f32x4* __restrict__ gamma, float eps, float inv_cols,
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const bool valid = (int)(threadIdx.x + u * blockDim.x) < vecs_per_row;
-            dequant8_packed<BITS>(b.c[u], valid ? b.sc[u] : 0.0f, xp[u]);
+            dequant8_packed<BITS, FP>(b.c[u], valid ? b.sc[u] : 0.0f, xp[u]);
             ss = sumsq8(xp[u], ss);
         }
         fetch(refill, row + (kDepth + 1) * step);
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
 
 // SiLU & Multiply recompute: z = bf16(u' * g' * sigmoid(g')), elementwise over the two
 // stored tensors (which may have different code widths).
-template <int BITS_G, int BITS_U, int GROUP, int UNROLL>
+template <int BITS_G, int BITS_U, int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_SI_BLOCK) void act_dequant_silu_mul_kernel(
     const void* __restrict__ gate_codes, const float* __restrict__ gate_scales,
     const void* __restrict__ up_codes, const float* __restrict__ up_scales, int64_t n_vec,
@@ -220,8 +220,8 @@ __global__ __launch_bounds__(AGOQ_SI_BLOCK) void act_dequant_silu_mul_kernel(
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
         float g[8], up[8], o[8];
-        dequant8_bf16<BITS_G>(gc[u], gs[u], g);
-        dequant8_bf16<BITS_U>(uc[u], us[u], up);
+        dequant8_bf16<BITS_G, FP>(gc[u], gs[u], g);
+        dequant8_bf16<BITS_U, FP>(uc[u], us[u], up);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float e = __expf(-g[j]);                          // may be +inf: 1/(1+inf) = 0
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(AGOQ_SI_BLOCK) void act_dequant_silu_mul_kernel(
 
 // RMSNorm forward + quantize(x): one workgroup per row, shaped like the recompute kernel.
 //   y = bf16(x * (1/r) * gamma), r = sqrt(mean(x^2) + eps);  codes, scales = quantize(x)
-template <int BITS, int GROUP, int VPT>
+template <int BITS, int GROUP, int VPT, bool FP = false>
 __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     const u32x4* __restrict__ x, int64_t n_vec_total, int64_t rows, int vecs_per_row,
     const f32x4* __restrict__ gamma, float eps, float inv_cols, u32x4* __restrict__ y,
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
             v[u] = valid ? b.v[u] : u32x4{0, 0, 0, 0};
             float f[8];
             const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f));
-            quantize_store8<BITS, GROUP, false, true>(f, m, row * vecs_per_row + c, n_vec_total,
+            quantize_store8<BITS, GROUP, FP, true>(f, m, row * vecs_per_row + c, n_vec_total,
                                                       valid, codes, scales);
 #pragma unroll
             for (int j = 0; j < 8; ++j) ss = __fmaf_rn(f[j], f[j], ss);
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
 
 // SiLU & Multiply forward + quantize(gate), quantize(up), elementwise.
 //   z = bf16(up * gate * sigmoid(gate))
-template <int BITS_G, int BITS_U, int GROUP, int UNROLL>
+template <int BITS_G, int BITS_U, int GROUP, int UNROLL, bool FP = false>
 __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void silu_mul_fwd_quant_kernel(
     const u32x4* __restrict__ gate, const u32x4* __restrict__ up, int64_t n_vec,
     u32x4* __restrict__ z, void* __restrict__ gate_codes, float* __restrict__ gate_scales,
@@ -362,8 +362,8 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void silu_mul_fwd_quant_kernel(
         float g[8], w[8], o[8];
         const u32 mg = group_max_bits<LANES>(unpack8_bf16(gv[u], g));
         const u32 mu = group_max_bits<LANES>(unpack8_bf16(uv[u], w));
-        quantize_store8<BITS_G, GROUP, false, true>(g, mg, vi, n_vec, valid, gate_codes, gate_scales);
-        quantize_store8<BITS_U, GROUP, false, true>(w, mu, vi, n_vec, valid, up_codes, up_scales);
+        quantize_store8<BITS_G, GROUP, FP, true>(g, mg, vi, n_vec, valid, gate_codes, gate_scales);
+        quantize_store8<BITS_U, GROUP, FP, true>(w, mu, vi, n_vec, valid, up_codes, up_scales);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float e = __expf(-g[j]);                          // may be +inf: 1/(1+inf) = 0
@@ -401,13 +401,11 @@ inline unsigned norm_grid(int64_t rows, int threads, int depth)
     return (unsigned)(rows < resident ? rows : resident);
 }
 
-}  // namespace
 
-extern "C" {
 
-int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t rows, int64_t cols,
-                             int group, int bits, const float* gamma, float eps, void* y_bf16,
-                             float* r_out, void* stream)
+int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, int64_t cols, int group,
+                         int bits, bool fp, const float* gamma, float eps, void* y_bf16, float* r_out,
+                         void* stream)
 {
     if (!codes || !scales || !gamma || !y_bf16 || !r_out) return AGOQ_ERR_NULL;
     if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
@@ -433,7 +431,15 @@ int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t row
     case 2: act_dequant_rmsnorm_kernel<B, G, 2><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
     default: act_dequant_rmsnorm_kernel<B, G, 4><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
     }
-    if (group == 128) {
+#define AGOQ_LAUNCH_NORM_FP(G)                                                                    \
+    switch (vpt) {                                                                                \
+    case 1: act_dequant_rmsnorm_kernel<4, G, 1, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    case 2: act_dequant_rmsnorm_kernel<4, G, 2, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    default: act_dequant_rmsnorm_kernel<4, G, 4, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    }
+    if (fp) {
+        if (group == 128) { AGOQ_LAUNCH_NORM_FP(128) } else { AGOQ_LAUNCH_NORM_FP(64) }
+    } else if (group == 128) {
         switch (bits) {
         case 4: AGOQ_LAUNCH_NORM(4, 128) break;
         case 5: AGOQ_LAUNCH_NORM(5, 128) break;
@@ -448,13 +454,14 @@ int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t row
         default: AGOQ_LAUNCH_NORM(8, 64) break;
         }
     }
+#undef AGOQ_LAUNCH_NORM_FP
 #undef AGOQ_LAUNCH_NORM
     return launch_status();
 }
 
-int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, int gate_bits,
-                              const void* up_codes, const float* up_scales, int up_bits,
-                              int64_t numel, int group, void* z_bf16, void* stream)
+int dequant_silu_mul_impl(const void* gate_codes, const float* gate_scales, int gate_bits,
+                          const void* up_codes, const float* up_scales, int up_bits, bool fp,
+                          int64_t numel, int group, void* z_bf16, void* stream)
 {
     if (!gate_codes || !gate_scales || !up_codes || !up_scales || !z_bf16) return AGOQ_ERR_NULL;
     if ((gate_bits != 4 && gate_bits != 5 && gate_bits != 6 && gate_bits != 8) ||
@@ -481,19 +488,26 @@ int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, 
     case 6: AGOQ_LAUNCH_SILU(BG, 6) break;                                                        \
     default: AGOQ_LAUNCH_SILU(BG, 8) break;                                                       \
     }
-    switch (gate_bits) {
-    case 4: AGOQ_SILU_UP(4) break;
-    case 5: AGOQ_SILU_UP(5) break;
-    case 6: AGOQ_SILU_UP(6) break;
-    default: AGOQ_SILU_UP(8) break;
+    if (fp) {
+        if (group == 128)
+            act_dequant_silu_mul_kernel<4, 4, 128, U, true><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
+        else
+            act_dequant_silu_mul_kernel<4, 4, 64, U, true><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
+    } else {
+        switch (gate_bits) {
+        case 4: AGOQ_SILU_UP(4) break;
+        case 5: AGOQ_SILU_UP(5) break;
+        case 6: AGOQ_SILU_UP(6) break;
+        default: AGOQ_SILU_UP(8) break;
+        }
     }
 #undef AGOQ_SILU_UP
 #undef AGOQ_LAUNCH_SILU
     return launch_status();
 }
 
-int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const float* gamma,
-                           float eps, int group, int bits, void* y_bf16, float* r_out, void* codes,
+int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const float* gamma, float eps,
+                           int group, int bits, bool fp, void* y_bf16, float* r_out, void* codes,
                            float* scales, void* stream)
 {
     if (!x_bf16 || !gamma || !y_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
@@ -521,7 +535,15 @@ int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const
     case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
     default: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
     }
-    if (group == 128) {
+#define AGOQ_LAUNCH_NORM_FWD_FP(G)                                                                \
+    switch (vpt) {                                                                                \
+    case 1: rmsnorm_fwd_quant_kernel<4, G, 1, true><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 2: rmsnorm_fwd_quant_kernel<4, G, 2, true><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    default: rmsnorm_fwd_quant_kernel<4, G, 4, true><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    }
+    if (fp) {
+        if (group == 128) { AGOQ_LAUNCH_NORM_FWD_FP(128) } else { AGOQ_LAUNCH_NORM_FWD_FP(64) }
+    } else if (group == 128) {
         switch (bits) {
         case 4: AGOQ_LAUNCH_NORM_FWD(4, 128) break;
         case 5: AGOQ_LAUNCH_NORM_FWD(5, 128) break;
@@ -536,12 +558,13 @@ int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const
         default: AGOQ_LAUNCH_NORM_FWD(8, 64) break;
         }
     }
+#undef AGOQ_LAUNCH_NORM_FWD_FP
 #undef AGOQ_LAUNCH_NORM_FWD
     return launch_status();
 }
 
-int agoq_silu_mul_fwd_quant(const void* gate_bf16, const void* up_bf16, int64_t numel, int group,
-                            int gate_bits, int up_bits, void* z_bf16, void* gate_codes,
+int silu_mul_fwd_quant_impl(const void* gate_bf16, const void* up_bf16, int64_t numel, int group,
+                            int gate_bits, int up_bits, bool fp, void* z_bf16, void* gate_codes,
                             float* gate_scales, void* up_codes, float* up_scales, void* stream)
 {
     if (!gate_bf16 || !up_bf16 || !z_bf16 || !gate_codes || !gate_scales || !up_codes || !up_scales)
@@ -573,15 +596,90 @@ int agoq_silu_mul_fwd_quant(const void* gate_bf16, const void* up_bf16, int64_t 
     case 6: AGOQ_LAUNCH_SILU_FWD(BG, 6) break;                                                    \
     default: AGOQ_LAUNCH_SILU_FWD(BG, 8) break;                                                   \
     }
-    switch (gate_bits) {
-    case 4: AGOQ_SILU_FWD_UP(4) break;
-    case 5: AGOQ_SILU_FWD_UP(5) break;
-    case 6: AGOQ_SILU_FWD_UP(6) break;
-    default: AGOQ_SILU_FWD_UP(8) break;
+    if (fp) {
+        if (group == 128)
+            silu_mul_fwd_quant_kernel<4, 4, 128, U, true><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
+        else
+            silu_mul_fwd_quant_kernel<4, 4, 64, U, true><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
+    } else {
+        switch (gate_bits) {
+        case 4: AGOQ_SILU_FWD_UP(4) break;
+        case 5: AGOQ_SILU_FWD_UP(5) break;
+        case 6: AGOQ_SILU_FWD_UP(6) break;
+        default: AGOQ_SILU_FWD_UP(8) break;
+        }
     }
 #undef AGOQ_SILU_FWD_UP
 #undef AGOQ_LAUNCH_SILU_FWD
     return launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int agoq_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t rows, int64_t cols,
+                             int group, int bits, const float* gamma, float eps, void* y_bf16,
+                             float* r_out, void* stream)
+{
+    return dequant_rmsnorm_impl(codes, scales, rows, cols, group, bits, false, gamma, eps, y_bf16,
+                                r_out, stream);
+}
+
+int agoq_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales, int gate_bits,
+                              const void* up_codes, const float* up_scales, int up_bits,
+                              int64_t numel, int group, void* z_bf16, void* stream)
+{
+    return dequant_silu_mul_impl(gate_codes, gate_scales, gate_bits, up_codes, up_scales, up_bits,
+                                 false, numel, group, z_bf16, stream);
+}
+
+int agoq_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const float* gamma,
+                           float eps, int group, int bits, void* y_bf16, float* r_out, void* codes,
+                           float* scales, void* stream)
+{
+    return rmsnorm_fwd_quant_impl(x_bf16, rows, cols, gamma, eps, group, bits, false, y_bf16, r_out,
+                                  codes, scales, stream);
+}
+
+int agoq_silu_mul_fwd_quant(const void* gate_bf16, const void* up_bf16, int64_t numel, int group,
+                            int gate_bits, int up_bits, void* z_bf16, void* gate_codes,
+                            float* gate_scales, void* up_codes, float* up_scales, void* stream)
+{
+    return silu_mul_fwd_quant_impl(gate_bf16, up_bf16, numel, group, gate_bits, up_bits, false,
+                                   z_bf16, gate_codes, gate_scales, up_codes, up_scales, stream);
+}
+
+int agoq_fp4_act_dequant_rmsnorm(const void* codes, const float* scales, int64_t rows, int64_t cols,
+                                 int group, const float* gamma, float eps, void* y_bf16,
+                                 float* r_out, void* stream)
+{
+    return dequant_rmsnorm_impl(codes, scales, rows, cols, group, 4, true, gamma, eps, y_bf16, r_out,
+                                stream);
+}
+
+int agoq_fp4_act_dequant_silu_mul(const void* gate_codes, const float* gate_scales,
+                                  const void* up_codes, const float* up_scales, int64_t numel,
+                                  int group, void* z_bf16, void* stream)
+{
+    return dequant_silu_mul_impl(gate_codes, gate_scales, 4, up_codes, up_scales, 4, true, numel,
+                                 group, z_bf16, stream);
+}
+
+int agoq_fp4_rmsnorm_fwd_quant(const void* x_bf16, int64_t rows, int64_t cols, const float* gamma,
+                               float eps, int group, void* y_bf16, float* r_out, void* codes,
+                               float* scales, void* stream)
+{
+    return rmsnorm_fwd_quant_impl(x_bf16, rows, cols, gamma, eps, group, 4, true, y_bf16, r_out,
+                                  codes, scales, stream);
+}
+
+int agoq_fp4_silu_mul_fwd_quant(const void* gate_bf16, const void* up_bf16, int64_t numel, int group,
+                                void* z_bf16, void* gate_codes, float* gate_scales, void* up_codes,
+                                float* up_scales, void* stream)
+{
+    return silu_mul_fwd_quant_impl(gate_bf16, up_bf16, numel, group, 4, 4, true, z_bf16, gate_codes,
+                                   gate_scales, up_codes, up_scales, stream);
 }
 
 }  // extern "C"

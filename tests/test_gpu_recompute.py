@@ -226,3 +226,78 @@ def test_forward_fused_error_codes(agoq):
     assert L.agoq_silu_mul_fwd_quant(px, px, 1000, 128, 4, 4, py, pc, ps, pc, ps, None) == 4
     torch.cuda.synchronize()
     assert not bool(y.view(torch.int16).any()) and not bool(c.any())
+
+
+# ---- the same four calls on E2M1 codes --------------------------------------------------
+# Oracle: the E2M1 dequantize of the oracle gives x' (bf16), and the layer's binary64
+# definition is applied to x'; the stored form must equal the oracle's E2M1 quantize bit for bit.
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("rows,cols", [(3, 128), (17, 1024), (64, 4096), (33, 5120), (5, 14336), (2, 16384)])
+def test_fp4_dequant_rmsnorm(agoq, ref, rows, cols, group):
+    x = wl.act_host(rows, cols, 11000 + rows + cols, "student_t3", max(1, cols // 100), 50.0)
+    if rows > 4:
+        x[1] = 0
+    codes, scales = ref.fp4_act_quant(x, group)
+    xd = ref.fp4_act_dequant(codes, scales, rows * cols, group)
+    rng = np.random.default_rng(cols + 3)
+    gamma = (1.0 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    eps = 1e-5
+    want_y, want_r = ref.rmsnorm_fwd(xd, rows, cols, gamma, eps)
+    y, r = agoq.act_dequant_rmsnorm(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(),
+                                    rows, cols, group, 4, torch.from_numpy(gamma).cuda(), eps, fp4=True)
+    torch.cuda.synchronize()
+    assert np.allclose(r.cpu().numpy(), want_r, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y), want_y)
+
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("n_groups", [1, 9, 133, 30011])
+def test_fp4_dequant_silu_mul_and_forward(agoq, ref, n_groups, group):
+    n = n_groups * group
+    rng = np.random.default_rng(11500 + n_groups)
+    g = (rng.standard_normal(n) * 4).astype(np.float32)
+    g[::1000] *= 30.0
+    u = rng.standard_normal(n).astype(np.float32)
+    if n_groups > 4:
+        g[group: 2 * group] = 0.0
+        u[2 * group: 3 * group] = -0.0
+    gb = torch.from_numpy(g).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    ub = torch.from_numpy(u).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    # forward: z from the exact inputs, stored form = the oracle's E2M1 quantize
+    z, gc, gs, uc, us = agoq.silu_mul_fwd_quant(dev_bf16(gb), dev_bf16(ub), group, 4, 4, fp4=True)
+    torch.cuda.synchronize()
+    stored = []
+    for got_c, got_s, src in ((gc, gs, gb), (uc, us, ub)):
+        wc, ws = ref.fp4_act_quant(src, group)
+        assert np.array_equal(got_c.cpu().numpy(), wc)
+        assert np.array_equal(got_s.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+        stored.append((wc, ws))
+    check_close_bf16(bits_of(z), ref.silu_mul_fwd(gb, ub))
+    # backward: z recomputed from the stored E2M1 tensors
+    gd = ref.fp4_act_dequant(stored[0][0], stored[0][1], n, group)
+    ud = ref.fp4_act_dequant(stored[1][0], stored[1][1], n, group)
+    z2 = agoq.act_dequant_silu_mul(gc, gs, 4, uc, us, 4, n, group, fp4=True)
+    torch.cuda.synchronize()
+    got = bits_of(z2)
+    assert not np.any((got & 0x7F80) == 0x7F80), "NaN or Inf in the output"
+    check_close_bf16(got, ref.silu_mul_fwd(gd, ud))
+
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("rows,cols", [(3, 128), (64, 4096), (33, 5120), (5, 14336)])
+def test_fp4_rmsnorm_forward_with_quantized_input(agoq, ref, rows, cols, group):
+    x = wl.act_host(rows, cols, 12000 + rows + cols, "student_t3", max(1, cols // 100), 50.0)
+    if rows > 4:
+        x[2] = 0
+    rng = np.random.default_rng(cols + 5)
+    gamma = (1.0 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    eps = 1e-5
+    y, r, codes, scales = agoq.rmsnorm_fwd_quant(dev_bf16(x), torch.from_numpy(gamma).cuda(), eps, group, 4, fp4=True)
+    torch.cuda.synchronize()
+    wc, ws = ref.fp4_act_quant(x, group)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+    want_y, want_r = ref.rmsnorm_fwd(x, rows, cols, gamma, eps)
+    assert np.allclose(r.cpu().numpy(), want_r, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y), want_y)
