@@ -387,9 +387,9 @@ int agoq_act_quant_layer(const agoq_act_slot* slots, int count, int group, void*
     if (int rc = layer_args(slots, count, group, true, a, blocks)) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        act_quant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLds, st>>>(a);
+        act_quant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLq, st>>>(a);
     else
-        act_quant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLds, st>>>(a);
+        act_quant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLq, st>>>(a);
     return launch_status();
 }
 

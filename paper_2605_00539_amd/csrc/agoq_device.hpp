@@ -117,6 +117,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef AGOQ_SI_CAP_KB         // SiLU & Multiply recompute
 #define AGOQ_SI_CAP_KB 0
 #endif
+#ifndef AGOQ_LQ_CAP_KB         // layer quantize
+#define AGOQ_LQ_CAP_KB 0
+#endif
 #ifndef AGOQ_LDQ_CAP_KB        // layer dequantize: 3 workgroups of 512
 #define AGOQ_LDQ_CAP_KB 48
 #endif
@@ -141,6 +144,7 @@ constexpr size_t kCapGa = (size_t)AGOQ_GA_CAP_KB * 1024;
 constexpr size_t kCapSf = (size_t)AGOQ_SF_CAP_KB * 1024;
 constexpr size_t kCapGd = (size_t)AGOQ_GD_CAP_KB * 1024;
 constexpr size_t kCapSi = (size_t)AGOQ_SI_CAP_KB * 1024;
+constexpr size_t kCapLq = (size_t)AGOQ_LQ_CAP_KB * 1024;
 constexpr size_t kCapLdq = (size_t)AGOQ_LDQ_CAP_KB * 1024;
 constexpr size_t kCapDq8 = (size_t)AGOQ_DQ8_CAP_KB * 1024;
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
