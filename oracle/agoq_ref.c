@@ -46,7 +46,13 @@
  *   power-of-two scales, tie cases, byte-level packing fixtures, the
  *   round-trip bound, library cross-checks and the values the paper prints
  *   for the four-stage pipeline).
- *   Non-finite inputs (NaN, Inf) are outside the contract: parity unpinned.
+ *   Non-finite inputs (the paper is silent; reading): they propagate at group
+ *   granularity.  A group that holds +-Inf or a NaN -- in the tensor being
+ *   quantized, or in the fp32 sums of the reduce and of the accumulation, so
+ *   also when a sum overflows or an incoming scale is not finite -- stores the
+ *   scale quiet-NaN (bits 0x7FC00000) and all-zero codes; every element of it
+ *   then dequantizes to a NaN (0 * NaN).  A NaN converts to bf16 as a NaN whose
+ *   payload is not specified.  Pinned by tests/test_oracle_nonfinite_pins.py.
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  * Parallelism is over groups only; a group is always handled by one thread
@@ -80,10 +86,13 @@ static float bf16_bits_to_f32(uint16_t h)
     return f;
 }
 
-/* Round a finite binary32 to bf16, nearest, ties to even. */
+/* Round a binary32 to bf16, nearest, ties to even (an infinity stays one; a NaN becomes
+   the quiet NaN 0x7FC0: which NaN is not part of the contract). */
 static uint16_t f32_to_bf16_bits(float f)
 {
     uint32_t u;
+    if (isnan(f))
+        return 0x7FC0u;
     memcpy(&u, &f, sizeof u);
     uint32_t lsb = (u >> 16) & 1u; /* parity of the bit that survives */
     u += 0x7FFFu + lsb;            /* > half rounds up; == half rounds to even */
@@ -103,9 +112,31 @@ static int bits_supported(int bits)
     return bits == 4 || bits == 5 || bits == 6 || bits == 8;
 }
 
+/* The scale of a group that holds a non-finite value. */
+static float quiet_nan(void)
+{
+    const uint32_t u = 0x7FC00000u;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static int group_is_finite(const float *x, int G)
+{
+    for (int j = 0; j < G; ++j)
+        if (!isfinite(x[j]))
+            return 0;
+    return 1;
+}
+
 /* Quantize G fp32 values to integer codes in [-qmax, qmax]; returns scale. */
 static float quantize_group(const float *x, int G, int qmax, int *q)
 {
+    if (!group_is_finite(x, G)) { /* Inf or NaN anywhere: the whole group reads back as NaN */
+        for (int j = 0; j < G; ++j)
+            q[j] = 0;
+        return quiet_nan();
+    }
     float amax = 0.0f;
     for (int j = 0; j < G; ++j) {
         float a = fabsf(x[j]);
@@ -583,7 +614,9 @@ static uint8_t e4m3_encode(float t)
 
 static float e4m3_decode(uint8_t code)
 {
-    const float v = e4m3_magnitude(code & 0x7F); /* 0x7F itself (NaN) is never produced */
+    if ((code & 0x7F) == 0x7F) /* the format's NaN; the quantizer never produces it */
+        return quiet_nan();
+    const float v = e4m3_magnitude(code & 0x7F);
     return (code & 0x80) ? -v : v;
 }
 
@@ -592,9 +625,15 @@ float agoq_ref_e2m1_decode(uint8_t c) { return e2m1_decode(c); }
 uint8_t agoq_ref_e4m3_encode(float t) { return e4m3_encode(t); }
 float agoq_ref_e4m3_decode(uint8_t c) { return e4m3_decode(c); }
 
-/* scale, inv of a group for a code book with largest magnitude vmax; returns 0 for a dead group */
+/* scale, inv of a group for a code book with largest magnitude vmax; returns 0 for a group
+   whose codes are all zero (a dead group, or one that holds a non-finite value) */
 static int fp_group_scale(const float *x, int G, float vmax, float *scale, float *inv)
 {
+    if (!group_is_finite(x, G)) {
+        *scale = quiet_nan();
+        *inv = 0.0f;
+        return 0;
+    }
     float amax = 0.0f;
     for (int j = 0; j < G; ++j) {
         const float mag = fabsf(x[j]);

@@ -11,6 +11,7 @@ import test_oracle_quant_pins as quant_pins
 import test_oracle_reduce_pins as reduce_pins
 import test_oracle_recompute_pins as recompute_pins
 import test_oracle_fp_pins as fp_pins
+import test_oracle_nonfinite_pins as nonfinite_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "agoq_ref.c")
@@ -94,6 +95,15 @@ MUTANTS = [
     ("dbca_printed_index", "return 3 * n_stages - 2 * stage + 1;", "return n_stages + 2 * stage - 1;"),
     ("dbca_floor_instead_of_round", "int r = (int)floor(b + 0.5);", "int r = (int)floor(b);"),
     ("dbca_no_cap", "if (r > 8)\n        r = 8;", ""),
+    ("nonfinite_group_quantized_like_any_other", "if (!group_is_finite(x, G)) { /* Inf or NaN anywhere",
+     "if (0) { /* Inf or NaN anywhere"),
+    ("only_nan_counts_as_nonfinite", "if (!isfinite(x[j]))", "if (isnan(x[j]))"),
+    ("only_inf_counts_as_nonfinite", "if (!isfinite(x[j]))", "if (isinf(x[j]))"),
+    ("nonfinite_group_gets_scale_zero", "            q[j] = 0;\n        return quiet_nan();", "            q[j] = 0;\n        return 0.0f;"),
+    ("fp_nonfinite_group_keeps_codes", "        *scale = quiet_nan();\n        *inv = 0.0f;\n        return 0;",
+     "        *scale = quiet_nan();\n        *inv = 0.0f;\n        return 1;"),
+    ("fp_nonfinite_group_not_detected", "    if (!group_is_finite(x, G)) {\n        *scale = quiet_nan();", "    if (0) {\n        *scale = quiet_nan();"),
+    ("bf16_nan_rounded_like_a_number", "    if (isnan(f))\n        return 0x7FC0u;\n", ""),
     ("dequant_uses_previous_group_scale", "const float s = scales[g];\n        for (int j = 0; j < group; ++j) {\n            float v",
      "const float s = scales[g > 0 ? g - 1 : 0];\n        for (int j = 0; j < group; ++j) {\n            float v"),
 ]
@@ -102,7 +112,7 @@ MUTANTS = [
 def pin_tests():
     """Every pin test of the two pin modules, expanded over its parametrisation."""
     cases = []
-    for mod in (quant_pins, reduce_pins, recompute_pins, fp_pins):
+    for mod in (quant_pins, reduce_pins, recompute_pins, fp_pins, nonfinite_pins):
         for name, fn in inspect.getmembers(mod, inspect.isfunction):
             if not name.startswith("test_") or "ref" not in inspect.signature(fn).parameters:
                 continue
