@@ -28,7 +28,13 @@
  *         otherwise      :  scale = amax / qmax,  inv = qmax / amax
  *                           code  = rint(x * inv)   (ties to even; |code| <= qmax)
  *     and dequantization is value = (float)code * scale.
- *   - Inputs must be finite; NaN/Inf give unspecified codes (never a fault).
+ *   - Non-finite values propagate per group (the paper does not say; this is
+ *     the library's rule): a group that holds +-Inf or a NaN -- in the tensor
+ *     being quantized, or in the fp32 sums of the reduce and the accumulation,
+ *     so also when such a sum overflows or an incoming scale is not finite --
+ *     is stored with scale = quiet NaN (bits 0x7FC00000) and all-zero codes,
+ *     and therefore dequantizes to NaN in every element.  Which NaN a bf16
+ *     output holds is unspecified.
  *   - Code layout: codes are two's-complement fields of `bits` bits.  8-bit
  *     codes are int8, one per element.  4-bit codes: byte m holds element 2m
  *     in bits 0-3 and element 2m+1 in bits 4-7.  5- and 6-bit codes occupy

@@ -149,6 +149,8 @@ constexpr size_t kCapLdq = (size_t)AGOQ_LDQ_CAP_KB * 1024;
 constexpr size_t kCapDq8 = (size_t)AGOQ_DQ8_CAP_KB * 1024;
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
 constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
+constexpr u32 kInfBits = 0x7F800000u;       // magnitudes from here up are Inf or NaN
+constexpr u32 kQuietNanBits = 0x7FC00000u;  // the scale of a group that holds one
 
 __device__ __forceinline__ float as_f32(u32 u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ u32 as_u32(float f) { return __builtin_bit_cast(u32, f); }
@@ -197,17 +199,23 @@ __device__ __forceinline__ u32 group_max_bits(u32 m)
 
 __device__ __forceinline__ u32 umax(u32 a, u32 b) { return a > b ? a : b; }
 
-// scale and inv of a group from the bits of its abs-max.
+// scale and inv of a group from the bits of its abs-max (integer order of the magnitude
+// bits: Inf and every NaN sort above all finite values).  Returns whether the group keeps
+// its codes: not a dead group (abs-max below 2^-100: scale 0) and not one that holds an Inf
+// or a NaN (scale = quiet NaN, so the whole group reads back as NaN).  Otherwise inv = 0 and
+// the caller stores zeros for the codes (x * 0 is not zero for a non-finite x).
 template <int QMAX>
-__device__ __forceinline__ void scale_and_inv(u32 amax_bits, float& scale, float& inv)
+__device__ __forceinline__ bool scale_and_inv(u32 amax_bits, float& scale, float& inv)
 {
     const float amax = as_f32(amax_bits);
-    const bool live = amax_bits >= kAmaxMinBits;
-    const float den = live ? amax : 1.0f;
+    const bool finite = amax_bits < kInfBits;
+    const bool keep = amax_bits >= kAmaxMinBits && finite;
+    const float den = keep ? amax : 1.0f;
     const float s = __fdiv_rn(amax, (float)QMAX);
     const float r = __fdiv_rn((float)QMAX, den);
-    scale = live ? s : 0.0f;
-    inv = live ? r : 0.0f;
+    scale = keep ? s : finite ? 0.0f : as_f32(kQuietNanBits);
+    inv = keep ? r : 0.0f;
+    return keep;
 }
 
 // round(x * inv) as the low bits of the returned word (two's complement).
@@ -334,16 +342,16 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
     constexpr int LANES = GROUP / 8;
     constexpr int QMAX = FP ? 6 : (1 << (BITS - 1)) - 1;   // largest code magnitude
     float scale, inv;
-    scale_and_inv<QMAX>(amax_bits, scale, inv);
+    const bool keep = scale_and_inv<QMAX>(amax_bits, scale, inv);
     if (!valid) return;
     if (FP) {
         const u32 p = encode8_e2m1(f, inv);
-        st<NTS>((u32*)codes + vi, scale != 0.0f ? p : 0u);   // dead group: no signed zeros
+        st<NTS>((u32*)codes + vi, keep ? p : 0u);   // no signed zeros left in a zeroed group
     } else if (BITS == 4) {
         u32 p = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
-        st<NTS>((u32*)codes + vi, p);
+        st<NTS>((u32*)codes + vi, keep ? p : 0u);
     } else if (BITS == 5 || BITS == 6) {
         u32 p = 0, h = 0;
 #pragma unroll
@@ -352,7 +360,8 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
             p = push_nibble(p, c);
             h = __builtin_amdgcn_alignbit(c >> 4, h, BITS - 4);  // bits 4.. of the code
         }
-        st<NTS>((u32*)codes + vi, p);
+        h = keep ? h : 0u;
+        st<NTS>((u32*)codes + vi, keep ? p : 0u);
         uint8_t* high = (uint8_t*)codes + n_vec * 4;
         if (BITS == 5)
             st<NTS>(high + vi, (uint8_t)(h >> 24));
@@ -364,7 +373,7 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
         for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
 #pragma unroll
         for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
-        st<NTS>((u32x2*)codes + vi, u32x2{p0, p1});
+        st<NTS>((u32x2*)codes + vi, u32x2{keep ? p0 : 0u, keep ? p1 : 0u});
     }
     if ((vi & (LANES - 1)) == 0) st<NTS && AGOQ_SCALE_NT>(scales + vi / LANES, scale);
 }

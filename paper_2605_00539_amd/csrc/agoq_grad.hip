@@ -44,12 +44,12 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* 
             for (int j = 0; j < 4; ++j) m = umax(m, as_u32(v[u][p][j]) & 0x7FFFFFFFu);
         m = group_max_bits<16>(m);
         float scale, inv;
-        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
+        const bool keep = scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (grp < n_groups) {
 #pragma unroll
             for (int p = 0; p < VPL; ++p) {
                 u32 w = encode4_bytes<FP>(v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3], inv);
-                if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
+                if (!keep) w = 0;   // dead group: no signed zeros; non-finite group: no codes
                 st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
             }
             if (lane16 == 0) st<NTS && AGOQ_SCALE_NT>(scales + grp, scale);
@@ -74,13 +74,13 @@ __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi
     for (int j = 0; j < 16; ++j) m = umax(m, as_u32(acc[j]) & 0x7FFFFFFFu);
     m = group_max_bits<LANES>(m);
     float scale, inv;
-    scale_and_inv<FP ? 448 : 127>(m, scale, inv);
+    const bool keep = scale_and_inv<FP ? 448 : 127>(m, scale, inv);
     if (valid) {
         u32x4 w = {0, 0, 0, 0};
 #pragma unroll
         for (int d = 0; d < 4; ++d)
             w[d] = encode4_bytes<FP>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv);
-        if (FP && scale == 0.0f) w = u32x4{0, 0, 0, 0};       // dead group: no signed zeros
+        if (!keep) w = u32x4{0, 0, 0, 0};   // dead group: no signed zeros; non-finite: no codes
         st<AGOQ_RD_NTS>(out_codes + vi, w);
         if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS && AGOQ_SCALE_NT>(out_scales + vi / LANES, scale);
     }
@@ -299,12 +299,12 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
         }
         m = group_max_bits<16>(m);
         float scale, inv;
-        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
+        const bool keep = scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (grp < n_groups) {
 #pragma unroll
             for (int p = 0; p < VPL; ++p) {
                 u32 w = encode4_bytes<FP>(acc[p][0], acc[p][1], acc[p][2], acc[p][3], inv);
-                if (FP && scale == 0.0f) w = 0;               // dead group: no signed zeros
+                if (!keep) w = 0;   // dead group: no signed zeros; non-finite group: no codes
                 st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
             }
             if (lane16 == 0) st<AGOQ_SCALE_NT>(out_scales + grp, scale);
@@ -355,11 +355,11 @@ __global__ __launch_bounds__(AGOQ_GB_BLOCK) void grad_accumulate_bf16_kernel(
         }
         m = group_max_bits<LANES>(m);
         float scale, inv;
-        scale_and_inv<FP ? 448 : 127>(m, scale, inv);
+        const bool keep = scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (vi < n_vec) {
             u32 p0 = encode4_bytes<FP>(acc[0], acc[1], acc[2], acc[3], inv);
             u32 p1 = encode4_bytes<FP>(acc[4], acc[5], acc[6], acc[7], inv);
-            if (FP && scale == 0.0f) p0 = p1 = 0;              // dead group: no signed zeros
+            if (!keep) p0 = p1 = 0;   // dead group: no signed zeros; non-finite group: no codes
             st<true>(out_codes + vi, u32x2{p0, p1});
             if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_SCALE_NT>(out_scales + vi / LANES, scale);
         }
