@@ -220,6 +220,9 @@ int agoq_grad_accumulate(const int8_t *main_codes, const float *main_scales, con
  * Dequantize a stored 8-bit gradient to fp32 (paper: "Precision-Preserved Gradient
  * Quantization": quantized gradients are dequantized before they are used in high
  * precision).  out[i] = (float)code[i] * scale[g], one fp32 rounding.
+ * For a bf16 result (that product rounded once more, to nearest even) call
+ * agoq_act_dequant with bits = 8 on the same buffers: int8 gradient codes and 8-bit
+ * activation codes share one layout.
  */
 int agoq_grad_dequant(const int8_t *codes, const float *scales, int64_t numel, int group,
                       float *out, void *stream);

@@ -351,3 +351,18 @@ def test_accumulate_and_dequant_error_codes(agoq):
     assert L.agoq_grad_dequant(pc, None, 1024, 128, pg, None) == 1
     assert L.agoq_grad_dequant(pc, ps, 1024, 32, pg, None) == 3
     assert L.agoq_grad_dequant(pc, ps, -128, 128, pg, None) == 4
+
+
+def test_gradient_codes_dequantize_to_bf16_through_the_activation_call(agoq, ref):
+    """int8 gradient codes and 8-bit activation codes share a layout: the activation
+    dequantize gives bf16(code * scale) of a stored gradient."""
+    group, n = 128, 128 * 7001
+    g = wl.grad_host(n, 77, 1e-4, 0.001, 100.0)
+    codes, scales = agoq.grad_quant(torch.from_numpy(g).cuda(), group)
+    y = agoq.act_dequant(codes.view(torch.uint8), scales, n, group, 8)
+    torch.cuda.synchronize()
+    wc, ws = ref.grad_quant(g, group)
+    f32 = ref.grad_dequant(wc, ws, group)
+    want = torch.from_numpy(f32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(host_bits(y), want)
+    assert np.array_equal(host_bits(y), ref.act_dequant(wc.view(np.uint8), ws, n, group, 8))
