@@ -82,8 +82,11 @@ def main():
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--configs", default="1,2,3,4,5",
                     help="comma-separated configuration numbers to run (default: all five)")
+    ap.add_argument("--messages", action="store_true",
+                    help="also time the per-GPU quantize/reduce/dequantize work of one 8-bit "
+                         "All-Reduce at message sizes 2^15 .. 2^30 elements")
     args = ap.parse_args()
-    wanted = {int(c) for c in args.configs.split(",")}
+    wanted = {int(c) for c in args.configs.split(",") if c}
     import workloads as wl
 
     import ctypes
@@ -385,6 +388,46 @@ def main():
                 seen.append(bitmap)
                 layer_case("5-stage", "stage %d (B=%d)" % (stage, b), c["rows"], c["hidden"], c["ffn"],
                            c["dist"], c["outlier_frac"], c["outlier_scale"], c["seed"], c["group"], bitmap)
+    # message-size sweep: the quantize / reduce / dequantize work one GPU does for one
+    # decomposed 8-bit All-Reduce over P = 8 peers on a gradient bucket of n elements
+    # (store n as int8; reduce the 8 received chunks of its n/8 shard; dequantize the n
+    # gathered elements) -- the work the paper's communication breakdown (Table
+    # comm_savings, column "Quant/Dequant") times at message sizes 2^15 .. 2^30
+    if args.messages:
+        group, K = 128, 8
+        for log2n in (15, 20, 25, 28, 30):
+            n = 1 << log2n
+            ns = n // K
+            nrot = max(2, min(16, -(-(GiB + GiB // 2) // (4 * n))))
+            g = [wl.grad_device(n, 700 + i, 1e-4, 0.001, 100.0) for i in range(nrot)]
+            codes = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nrot)]
+            scales = [torch.empty(n // group, dtype=torch.float32, device=dev) for _ in range(nrot)]
+            out = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]
+            rc = torch.randint(-127, 128, (K, ns), device=dev, dtype=torch.int8)
+            rs = torch.rand((K, ns // group), device=dev, dtype=torch.float32) * 1e-5 + 1e-8
+            oc = torch.empty(ns, dtype=torch.int8, device=dev)
+            osc = torch.empty(ns // group, dtype=torch.float32, device=dev)
+
+            # pointers marshalled once: at the small sizes the binding's per-call checks
+            # would otherwise be most of the time
+            pg = [P(t.data_ptr()) for t in g]
+            pc = [P(t.data_ptr()) for t in codes]
+            ps = [P(t.data_ptr()) for t in scales]
+            po = [P(t.data_ptr()) for t in out]
+            prc, prs, poc, pos = P(rc.data_ptr()), P(rs.data_ptr()), P(oc.data_ptr()), P(osc.data_ptr())
+
+            def message(i):
+                r = i % nrot
+                bad = L.agoq_grad_quant(pg[r], n, group, pc[r], ps[r], st)
+                bad |= L.agoq_grad_reduce_requant(prc, ns, prs, ns // group, K, ns, group, poc, pos, st)
+                bad |= L.agoq_grad_dequant(pc[r], ps[r], n, group, po[i % 2], st)
+                assert bad == 0
+            launches = max(5, min(args.launches, int(4e9 / n)))
+            us = timed(message, launches, args.reps)
+            report("messages", "quant+reduce+dequant", "n=2^%d elements (fp32 %d MiB), K=8" % (log2n, 4 * n >> 20),
+                   us, 2 * algo_gq(n, group) + algo_red(ns, K, group))
+            del g, codes, scales, out, rc, rs, oc, osc
+            torch.cuda.empty_cache()
     print(json.dumps(rows))
     return 0
 
