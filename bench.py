@@ -235,8 +235,9 @@ def main():
 def cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_codes, g_scales,
                  in_codes, in_scales, r_codes, r_scales, n_grad):
     """Time the oracle (as it stands) on the host, with all its threads, on one whole step of
-    the same inputs (a few seconds of work), and check the GPU outputs of the last timed
-    step against it, every byte.  A one-thread figure on 1/16 of the step follows."""
+    the same inputs (three passes, the median counts: some 20 core-seconds of work), and
+    check the GPU outputs of the last timed step against it, every byte.  A one-thread
+    figure on 1/16 of the step follows."""
     import numpy as np
     import oracle
 
@@ -244,37 +245,42 @@ def cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_
         return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
     threads = oracle.max_threads()
-    nbytes, secs, ok = 0, 0.0, True
-    for x, b, c, s, y in zip(acts, act_bits, act_codes, act_scales, act_out):
-        xb = bits_of(x)
-        t = time.perf_counter()
-        oc, os_ = oracle.act_quant(xb, GROUP, b)
-        oy = oracle.act_dequant(oc, os_, xb.size, GROUP, b)
-        secs += time.perf_counter() - t
-        nbytes += 2 * algo_bytes_act(xb.size, b)
-        ok &= np.array_equal(c.cpu().numpy(), oc) and np.array_equal(
-            s.cpu().numpy().view(np.uint32), os_.view(np.uint32)) and np.array_equal(bits_of(y), oy)
-    ng = n_grad
+    host_acts = [bits_of(x) for x in acts]
+    ng = nr = n_grad
     gh = grad[:ng].cpu().numpy()
-    t = time.perf_counter()
-    oc, os_ = oracle.grad_quant(gh, GROUP)
-    secs += time.perf_counter() - t
-    nbytes += algo_bytes_grad_quant(ng)
-    ok &= np.array_equal(g_codes[:ng].cpu().numpy(), oc) and np.array_equal(
-        g_scales[:ng // GROUP].cpu().numpy().view(np.uint32), os_.view(np.uint32))
-    nr = n_grad
     ch = np.ascontiguousarray(in_codes[:, :nr].cpu().numpy())
     sh = np.ascontiguousarray(in_scales[:, :nr // GROUP].cpu().numpy())
-    t = time.perf_counter()
-    oc, os_ = oracle.grad_reduce_requant(ch, sh, nr, GROUP)
-    secs += time.perf_counter() - t
-    nbytes += algo_bytes_reduce(nr, K_CHUNKS)
-    ok &= np.array_equal(r_codes[:nr].cpu().numpy(), oc) and np.array_equal(
-        r_scales[:nr // GROUP].cpu().numpy().view(np.uint32), os_.view(np.uint32))
+
+    def one_pass():
+        nbytes, secs, outs = 0, 0.0, []
+        for xb, b in zip(host_acts, act_bits):
+            t = time.perf_counter()
+            oc, os_ = oracle.act_quant(xb, GROUP, b)
+            oy = oracle.act_dequant(oc, os_, xb.size, GROUP, b)
+            secs += time.perf_counter() - t
+            nbytes += 2 * algo_bytes_act(xb.size, b)
+            outs.append((oc, os_, oy))
+        t = time.perf_counter()
+        gq = oracle.grad_quant(gh, GROUP)
+        red = oracle.grad_reduce_requant(ch, sh, nr, GROUP)
+        secs += time.perf_counter() - t
+        nbytes += algo_bytes_grad_quant(ng) + algo_bytes_reduce(nr, K_CHUNKS)
+        return nbytes, secs, outs, gq, red
+
+    passes = sorted((one_pass() for _ in range(3)), key=lambda p: p[1])
+    nbytes, secs, outs, gq, red = passes[1]                  # the median pass
+    ok = True
+    for (oc, os_, oy), c, s, y in zip(outs, act_codes, act_scales, act_out):
+        ok &= np.array_equal(c.cpu().numpy(), oc) and np.array_equal(
+            s.cpu().numpy().view(np.uint32), os_.view(np.uint32)) and np.array_equal(bits_of(y), oy)
+    ok &= np.array_equal(g_codes[:ng].cpu().numpy(), gq[0]) and np.array_equal(
+        g_scales[:ng // GROUP].cpu().numpy().view(np.uint32), gq[1].view(np.uint32))
+    ok &= np.array_equal(r_codes[:nr].cpu().numpy(), red[0]) and np.array_equal(
+        r_scales[:nr // GROUP].cpu().numpy().view(np.uint32), red[1].view(np.uint32))
     # one thread: the first stored activation (quantize + dequantize), 1/16 of the gradient
     # store and 1/16 of the reduce
     oracle.set_threads(1)
-    xb = bits_of(acts[0])
+    xb = host_acts[0]
     n16 = (n_grad // 16) // GROUP * GROUP
     ch16 = np.ascontiguousarray(ch[:, :n16])
     sh16 = np.ascontiguousarray(sh[:, :n16 // GROUP])
@@ -291,7 +297,8 @@ def cpu_baseline(torch, acts, act_bits, act_codes, act_scales, act_out, grad, g_
         "value": round(nbytes / secs / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
         "one_thread_GB/s": round(nbytes1 / secs1 / 1e9, 3),
         "sample": "one whole step (5 activations quant+dequant, gradient store, 8-chunk reduce): "
-                  "%.0f MB algorithmic in %.2f s wall on %d threads" % (nbytes / 1e6, secs, threads),
+                  "%.0f MB algorithmic in %.2f s wall on %d threads (median of 3 passes)"
+                  % (nbytes / 1e6, secs, threads),
         "gpu_matches_oracle_on_sample": bool(ok),
     }
 
