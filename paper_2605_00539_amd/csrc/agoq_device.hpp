@@ -383,9 +383,22 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
 // 64-bit integer the load fills (copying its halves out right after the load, or keeping
 // it as a two-element vector that the compiler splits, makes the lane wait for the data
 // before it can issue its next load).
+// The high-bit field keeps the width it is loaded with: widening it to 32 bits where it is
+// loaded is an operation on the loaded value, which the compiler places right behind the
+// load -- and the lane then waits there for the data instead of where it decodes them.
 template <int BITS>
 struct Codes8 {
-    u32 lo = 0, hi = 0;
+    u32 lo = 0;
+};
+template <>
+struct Codes8<5> {
+    u32 lo = 0;
+    uint8_t hi = 0;
+};
+template <>
+struct Codes8<6> {
+    u32 lo = 0;
+    uint16_t hi = 0;
 };
 template <>
 struct Codes8<8> {
@@ -405,7 +418,7 @@ __device__ __forceinline__ void need_now(const Codes8<BITS>& c)
         asm volatile("" ::"v"(c.w));
     } else {
         asm volatile("" ::"v"(c.lo));
-        if (BITS != 4) asm volatile("" ::"v"(c.hi));
+        if constexpr (BITS != 4) asm volatile("" ::"v"((u32)c.hi));
     }
 }
 
@@ -418,8 +431,8 @@ __device__ __forceinline__ Codes8<BITS> load_codes8(const void* codes, int64_t n
     } else {
         c.lo = ld<NT>((const u32*)codes + vi);
         const uint8_t* high = (const uint8_t*)codes + n_vec * 4;
-        if (BITS == 5) c.hi = ld<NT>(high + vi);
-        if (BITS == 6) c.hi = ld<NT>((const uint16_t*)high + vi);
+        if constexpr (BITS == 5) c.hi = ld<NT>(high + vi);
+        if constexpr (BITS == 6) c.hi = ld<NT>((const uint16_t*)high + vi);
     }
     return c;
 }
@@ -432,7 +445,7 @@ __device__ __forceinline__ float decode8(const Codes8<BITS>& c, int j)
     } else if constexpr (BITS == 4) {
         return (float)(int)__builtin_amdgcn_sbfe((int)c.lo, 4 * j, 4);
     } else {
-        const int h = (int)__builtin_amdgcn_sbfe((int)c.hi, (BITS - 4) * j, BITS - 4);
+        const int h = (int)__builtin_amdgcn_sbfe((int)(u32)c.hi, (BITS - 4) * j, BITS - 4);
         return (float)(int)(((u32)h << 4) | __builtin_amdgcn_ubfe(c.lo, 4 * j, 4));
     }
 }

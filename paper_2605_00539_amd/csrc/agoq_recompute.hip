@@ -2,6 +2,8 @@
 // Multiply).  Backward side: dequantize and recompute the layer's forward from the
 // dequantized value, which never goes to memory.  Forward side: compute the layer and store
 // its quantized input in one pass over the input.
+#include <type_traits>
+
 #include "agoq_device.hpp"
 
 namespace {
@@ -14,6 +16,7 @@ namespace {
 // store chain would otherwise leave the memory pipes idle for most of a workgroup's life.
 // The row waits in registers as the bf16 pairs it consists of.
 constexpr int kNormMaxBlock = 1024;
+constexpr int kNormPipeRows = 8;                 // rows per workgroup from which the steady loop pays
 constexpr int64_t kNormMaxCols = 16384;          // widest row the row kernels take
 // Most lanes a row kernel with VPT vectors per lane is ever launched with (the register
 // budget per lane follows from it).
@@ -85,7 +88,10 @@ __device__ __forceinline__ float sumsq8(const u32 (&xp)[4], float ss)
     return ss;
 }
 
-template <int BITS, int GROUP, int VPT, bool FP = false>
+// PIPE: chosen by the host when every workgroup has many rows and the row has exactly
+// VPT * blockDim.x vectors.  No lane is then ever past the end of a row, nothing in the row
+// loop sits under a lane test, and the walk has a steady part (below).
+template <int BITS, int GROUP, int VPT, bool FP = false, bool PIPE = false>
 __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kernel(
     const void* __restrict__ codes, const float* __restrict__ scales, int64_t n_vec_total,
     int64_t rows, int vecs_per_row, const f32x4* __restrict__ gamma, float eps, float inv_cols,
@@ -98,15 +104,15 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     for (int u = 0; u < VPT; ++u) {
         const int v = threadIdx.x + u * blockDim.x;
         g0[u] = g1[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (v < vecs_per_row) {
+        if (PIPE || v < vecs_per_row) {
             g0[u] = gamma[2 * v];
             g1[u] = gamma[2 * v + 1];
         }
     }
-    // Three row buffers in rotation: while one row is reduced and stored, the loads of the
-    // workgroup's next two rows are in flight.  The rotation is written out (no buffer is
+    // Row buffers in rotation: while one row is reduced and stored, the loads of the
+    // workgroup's next kDepth rows are in flight.  The rotation is written out (no buffer is
     // ever copied into another: a copy would have to wait for the load that fills it).
-    // Loads are unconditional (a lane past the end of the row re-reads the row's last vector
+    // Loads take no lane test (a lane past the end of the row re-reads the row's last vector
     // and uses scale 0, so it adds nothing to the row sum): a load under a branch would have
     // to be merged with the register's old value, which again waits for the data.
     constexpr int kDepth = BITS == 8 ? AGOQ_NORM_DEPTH8 : BITS == 4 ? AGOQ_NORM_DEPTH : AGOQ_NORM_DEPTH56;
@@ -116,27 +122,28 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     };
     const int64_t step = gridDim.x;
     auto fetch = [&](RowBuf& b, int64_t row) {
-        if (row >= rows) return;                    // the same for every lane of the workgroup
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const int v = threadIdx.x + u * blockDim.x;
-            const int64_t vi = row * vecs_per_row + (v < vecs_per_row ? v : vecs_per_row - 1);
+            const int64_t vi = row * vecs_per_row + (PIPE || v < vecs_per_row ? v : vecs_per_row - 1);
             b.c[u] = load_codes8<BITS, true>(codes, n_vec_total, vi);
             b.sc[u] = ld<false>(scales + vi / LANES);
         }
     };
     // One row from its buffer to memory; `refill` (the same buffer, free once the row has
-    // been decoded) then receives the row that is kDepth + 1 steps on.
-    auto finish = [&](const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
+    // been decoded) then receives the row that is kDepth + 1 steps on.  SURE: the caller
+    // knows that row to exist, and the refill is issued without a test.
+    auto finish = [&](auto sure, const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
         u32 xp[VPT][4];
         float ss = 0.0f;
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
-            const bool valid = (int)(threadIdx.x + u * blockDim.x) < vecs_per_row;
+            const bool valid = PIPE || (int)(threadIdx.x + u * blockDim.x) < vecs_per_row;
             dequant8_packed<BITS, FP>(b.c[u], valid ? b.sc[u] : 0.0f, xp[u]);
             ss = sumsq8(xp[u], ss);
         }
-        fetch(refill, row + (kDepth + 1) * step);
+        const int64_t next = row + (kDepth + 1) * step;
+        if (decltype(sure)::value || next < rows) fetch(refill, next);   // the same for every lane
         const float total = block_sum(wave_sum(ss), wave_part[phase]);
         const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
         const float rinv = __fdiv_rn(1.0f, r);
@@ -144,40 +151,74 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const int v = threadIdx.x + u * blockDim.x;
-            if (v < vecs_per_row)
+            if (PIPE || v < vecs_per_row)
                 st<true>(y + row * vecs_per_row + v, norm_out8(xp[u], rinv, g0[u], g1[u]));
         }
     };
+    constexpr std::true_type kSure{};
+    constexpr std::false_type kTested{};
     // wave_part has two buffers used alternately: a wavefront is never more than one
     // barrier ahead of another, so a buffer is rewritten only after everyone has read it.
+    //
+    // PIPE: the walk has a steady part, in which every refill is known to lie inside the
+    // tensor and no load of the loop sits under a branch, and a tail of at most
+    // 2 * (kDepth + 1) - 1 rows with tested refills.  With a test around the loads the compiler
+    // cannot count the loads issued since the one it waits for and waits for ALL outstanding
+    // memory operations instead -- the younger rows' loads and the last row's stores included
+    // -- once per rotation of the buffers.  Without PIPE (few rows per workgroup, where the
+    // longer code costs more than the waits) the tail loop is the whole walk.
     int64_t row = blockIdx.x;                       // the grid never exceeds the row count
+    int phase = 0;
     if constexpr (kDepth == 2) {
         RowBuf b0, b1, b2;
-        fetch(b0, row);
-        fetch(b1, row + step);
-        fetch(b2, row + 2 * step);
+        if (PIPE && row + 5 * step < rows) {
+            fetch(b0, row);
+            fetch(b1, row + step);
+            fetch(b2, row + 2 * step);
+            do {
+                finish(kSure, b0, row, b0, phase);
+                finish(kSure, b1, row + step, b1, phase ^ 1);
+                finish(kSure, b2, row + 2 * step, b2, phase);
+                row += 3 * step;
+                phase ^= 1;
+            } while (row + 5 * step < rows);
+        } else {
+            fetch(b0, row);
+            if (row + step < rows) fetch(b1, row + step);
+            if (row + 2 * step < rows) fetch(b2, row + 2 * step);
+        }
         while (true) {
-            finish(b0, row, b0, 0);
+            finish(kTested, b0, row, b0, phase);
             if ((row += step) >= rows) break;
-            finish(b1, row, b1, 1);
+            finish(kTested, b1, row, b1, phase ^ 1);
             if ((row += step) >= rows) break;
-            finish(b2, row, b2, 0);
+            finish(kTested, b2, row, b2, phase);
             if ((row += step) >= rows) break;
-            finish(b0, row, b0, 1);
+            finish(kTested, b0, row, b0, phase ^ 1);
             if ((row += step) >= rows) break;
-            finish(b1, row, b1, 0);
+            finish(kTested, b1, row, b1, phase);
             if ((row += step) >= rows) break;
-            finish(b2, row, b2, 1);
+            finish(kTested, b2, row, b2, phase ^ 1);
             if ((row += step) >= rows) break;
         }
     } else {
         RowBuf b0, b1;
-        fetch(b0, row);
-        fetch(b1, row + step);
+        if (PIPE && row + 3 * step < rows) {
+            fetch(b0, row);
+            fetch(b1, row + step);
+            do {
+                finish(kSure, b0, row, b0, 0);
+                finish(kSure, b1, row + step, b1, 1);
+                row += 2 * step;
+            } while (row + 3 * step < rows);
+        } else {
+            fetch(b0, row);
+            if (row + step < rows) fetch(b1, row + step);
+        }
         while (true) {
-            finish(b0, row, b0, 0);
+            finish(kTested, b0, row, b0, 0);
             if ((row += step) >= rows) break;
-            finish(b1, row, b1, 1);
+            finish(kTested, b1, row, b1, 1);
             if ((row += step) >= rows) break;
         }
     }
@@ -241,20 +282,21 @@ __global__ __launch_bounds__(AGOQ_SI_BLOCK) void act_dequant_silu_mul_kernel(
 
 // RMSNorm forward + quantize(x): one workgroup per row, shaped like the recompute kernel.
 //   y = bf16(x * (1/r) * gamma), r = sqrt(mean(x^2) + eps);  codes, scales = quantize(x)
-template <int BITS, int GROUP, int VPT, bool FP = false>
+template <int BITS, int GROUP, int VPT, bool FP = false, bool PIPE = false>
 __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     const u32x4* __restrict__ x, int64_t n_vec_total, int64_t rows, int vecs_per_row,
     const f32x4* __restrict__ gamma, float eps, float inv_cols, u32x4* __restrict__ y,
     float* __restrict__ r_out, void* __restrict__ codes, float* __restrict__ scales)
 {
     constexpr int LANES = GROUP / 8;
+    constexpr int kDepth = AGOQ_NORM_FWD_DEPTH;
     __shared__ float wave_part[2][kNormMaxBlock / 64];
     f32x4 g0[VPT], g1[VPT];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
         const int c = threadIdx.x + u * blockDim.x;
         g0[u] = g1[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (c < vecs_per_row) {
+        if (PIPE || c < vecs_per_row) {
             g0[u] = gamma[2 * c];
             g1[u] = gamma[2 * c + 1];
         }
@@ -266,20 +308,19 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     };
     const int64_t step = gridDim.x;
     auto fetch = [&](RowBuf& b, int64_t row) {
-        if (row >= rows) return;
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const int c = threadIdx.x + u * blockDim.x;
-            b.v[u] = ld<true>(x + row * vecs_per_row + (c < vecs_per_row ? c : vecs_per_row - 1));
+            b.v[u] = ld<true>(x + row * vecs_per_row + (PIPE || c < vecs_per_row ? c : vecs_per_row - 1));
         }
     };
-    auto finish = [&](const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
+    auto finish = [&](auto sure, const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
         u32x4 v[VPT];
         float ss = 0.0f;
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const int c = threadIdx.x + u * blockDim.x;
-            const bool valid = c < vecs_per_row;
+            const bool valid = PIPE || c < vecs_per_row;
             v[u] = valid ? b.v[u] : u32x4{0, 0, 0, 0};
             float f[8];
             const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f));
@@ -288,7 +329,8 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
 #pragma unroll
             for (int j = 0; j < 8; ++j) ss = __fmaf_rn(f[j], f[j], ss);
         }
-        fetch(refill, row + (AGOQ_NORM_FWD_DEPTH + 1) * step);
+        const int64_t next = row + (kDepth + 1) * step;
+        if (decltype(sure)::value || next < rows) fetch(refill, next);   // the same for every lane
         const float total = block_sum(wave_sum(ss), wave_part[phase]);
         const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
         const float rinv = __fdiv_rn(1.0f, r);
@@ -297,41 +339,68 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
         for (int u = 0; u < VPT; ++u) {
             const int c = threadIdx.x + u * blockDim.x;
             const u32 xp[4] = {v[u][0], v[u][1], v[u][2], v[u][3]};
-            if (c < vecs_per_row)
+            if (PIPE || c < vecs_per_row)
                 st<true>(y + row * vecs_per_row + c, norm_out8(xp, rinv, g0[u], g1[u]));
         }
     };
+    constexpr std::true_type kSure{};
+    constexpr std::false_type kTested{};
+    // steady part with untested refills, then the tail: see the recompute kernel
     int64_t row = blockIdx.x;                       // the grid never exceeds the row count
-#if AGOQ_NORM_FWD_DEPTH == 2
-    RowBuf b0, b1, b2;
-    fetch(b0, row);
-    fetch(b1, row + step);
-    fetch(b2, row + 2 * step);
-    while (true) {
-        finish(b0, row, b0, 0);
-        if ((row += step) >= rows) break;
-        finish(b1, row, b1, 1);
-        if ((row += step) >= rows) break;
-        finish(b2, row, b2, 0);
-        if ((row += step) >= rows) break;
-        finish(b0, row, b0, 1);
-        if ((row += step) >= rows) break;
-        finish(b1, row, b1, 0);
-        if ((row += step) >= rows) break;
-        finish(b2, row, b2, 1);
-        if ((row += step) >= rows) break;
+    int phase = 0;
+    if constexpr (kDepth == 2) {
+        RowBuf b0, b1, b2;
+        if (PIPE && row + 5 * step < rows) {
+            fetch(b0, row);
+            fetch(b1, row + step);
+            fetch(b2, row + 2 * step);
+            do {
+                finish(kSure, b0, row, b0, phase);
+                finish(kSure, b1, row + step, b1, phase ^ 1);
+                finish(kSure, b2, row + 2 * step, b2, phase);
+                row += 3 * step;
+                phase ^= 1;
+            } while (row + 5 * step < rows);
+        } else {
+            fetch(b0, row);
+            if (row + step < rows) fetch(b1, row + step);
+            if (row + 2 * step < rows) fetch(b2, row + 2 * step);
+        }
+        while (true) {
+            finish(kTested, b0, row, b0, phase);
+            if ((row += step) >= rows) break;
+            finish(kTested, b1, row, b1, phase ^ 1);
+            if ((row += step) >= rows) break;
+            finish(kTested, b2, row, b2, phase);
+            if ((row += step) >= rows) break;
+            finish(kTested, b0, row, b0, phase ^ 1);
+            if ((row += step) >= rows) break;
+            finish(kTested, b1, row, b1, phase);
+            if ((row += step) >= rows) break;
+            finish(kTested, b2, row, b2, phase ^ 1);
+            if ((row += step) >= rows) break;
+        }
+    } else {
+        RowBuf b0, b1;
+        if (PIPE && row + 3 * step < rows) {
+            fetch(b0, row);
+            fetch(b1, row + step);
+            do {
+                finish(kSure, b0, row, b0, 0);
+                finish(kSure, b1, row + step, b1, 1);
+                row += 2 * step;
+            } while (row + 3 * step < rows);
+        } else {
+            fetch(b0, row);
+            if (row + step < rows) fetch(b1, row + step);
+        }
+        while (true) {
+            finish(kTested, b0, row, b0, 0);
+            if ((row += step) >= rows) break;
+            finish(kTested, b1, row, b1, 1);
+            if ((row += step) >= rows) break;
+        }
     }
-#else
-    RowBuf b0, b1;
-    fetch(b0, row);
-    fetch(b1, row + step);
-    while (true) {
-        finish(b0, row, b0, 0);
-        if ((row += step) >= rows) break;
-        finish(b1, row, b1, 1);
-        if ((row += step) >= rows) break;
-    }
-#endif
 }
 
 // SiLU & Multiply forward + quantize(gate), quantize(up), elementwise.
@@ -425,18 +494,21 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
     norm_launch_shape(vecs_per_row, bits == 8 ? AGOQ_NORM_VPT8 : AGOQ_NORM_VPT, vpt, threads);
     const int depth = bits == 8 ? AGOQ_NORM_DEPTH8 : bits == 4 ? AGOQ_NORM_DEPTH : AGOQ_NORM_DEPTH56;
     const dim3 grid(norm_grid(rows, threads, depth)), block(threads);
-#define AGOQ_LAUNCH_NORM(B, G)                                                                    \
+    const bool pipe = vecs_per_row == vpt * threads && rows >= (int64_t)grid.x * kNormPipeRows;
+#define AGOQ_NORM_ARGS codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out
+#define AGOQ_LAUNCH_NORM_V(B, G, V, F)                                                             \
+    if (pipe)                                                                                     \
+        act_dequant_rmsnorm_kernel<B, G, V, F, true><<<grid, block, kCapLds, st>>>(AGOQ_NORM_ARGS); \
+    else                                                                                          \
+        act_dequant_rmsnorm_kernel<B, G, V, F, false><<<grid, block, kCapLds, st>>>(AGOQ_NORM_ARGS);
+#define AGOQ_LAUNCH_NORM_F(B, G, F)                                                                \
     switch (vpt) {                                                                                \
-    case 1: act_dequant_rmsnorm_kernel<B, G, 1><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    case 2: act_dequant_rmsnorm_kernel<B, G, 2><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    default: act_dequant_rmsnorm_kernel<B, G, 4><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
+    case 1: AGOQ_LAUNCH_NORM_V(B, G, 1, F) break;                                                 \
+    case 2: AGOQ_LAUNCH_NORM_V(B, G, 2, F) break;                                                 \
+    default: AGOQ_LAUNCH_NORM_V(B, G, 4, F) break;                                                \
     }
-#define AGOQ_LAUNCH_NORM_FP(G)                                                                    \
-    switch (vpt) {                                                                                \
-    case 1: act_dequant_rmsnorm_kernel<4, G, 1, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    case 2: act_dequant_rmsnorm_kernel<4, G, 2, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    default: act_dequant_rmsnorm_kernel<4, G, 4, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out); break; \
-    }
+#define AGOQ_LAUNCH_NORM(B, G) AGOQ_LAUNCH_NORM_F(B, G, false)
+#define AGOQ_LAUNCH_NORM_FP(G) AGOQ_LAUNCH_NORM_F(4, G, true)
     if (fp) {
         if (group == 128) { AGOQ_LAUNCH_NORM_FP(128) } else { AGOQ_LAUNCH_NORM_FP(64) }
     } else if (group == 128) {
@@ -456,6 +528,9 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
     }
 #undef AGOQ_LAUNCH_NORM_FP
 #undef AGOQ_LAUNCH_NORM
+#undef AGOQ_LAUNCH_NORM_F
+#undef AGOQ_LAUNCH_NORM_V
+#undef AGOQ_NORM_ARGS
     return launch_status();
 }
 
@@ -529,18 +604,21 @@ int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const
     const u32x4* x = (const u32x4*)x_bf16;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
-#define AGOQ_LAUNCH_NORM_FWD(B, G)                                                                \
+    const bool pipe = vecs_per_row == vpt * threads && rows >= (int64_t)grid.x * kNormPipeRows;
+#define AGOQ_NORM_FWD_ARGS x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales
+#define AGOQ_LAUNCH_NORM_FWD_V(B, G, V, F)                                                         \
+    if (pipe)                                                                                     \
+        rmsnorm_fwd_quant_kernel<B, G, V, F, true><<<grid, block, kCapLds, st>>>(AGOQ_NORM_FWD_ARGS); \
+    else                                                                                          \
+        rmsnorm_fwd_quant_kernel<B, G, V, F, false><<<grid, block, kCapLds, st>>>(AGOQ_NORM_FWD_ARGS);
+#define AGOQ_LAUNCH_NORM_FWD_F(B, G, F)                                                            \
     switch (vpt) {                                                                                \
-    case 1: rmsnorm_fwd_quant_kernel<B, G, 1><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    case 2: rmsnorm_fwd_quant_kernel<B, G, 2><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    default: rmsnorm_fwd_quant_kernel<B, G, 4><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
+    case 1: AGOQ_LAUNCH_NORM_FWD_V(B, G, 1, F) break;                                             \
+    case 2: AGOQ_LAUNCH_NORM_FWD_V(B, G, 2, F) break;                                             \
+    default: AGOQ_LAUNCH_NORM_FWD_V(B, G, 4, F) break;                                            \
     }
-#define AGOQ_LAUNCH_NORM_FWD_FP(G)                                                                \
-    switch (vpt) {                                                                                \
-    case 1: rmsnorm_fwd_quant_kernel<4, G, 1, true><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    case 2: rmsnorm_fwd_quant_kernel<4, G, 2, true><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    default: rmsnorm_fwd_quant_kernel<4, G, 4, true><<<grid, block, kCapLds, st>>>(x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales); break; \
-    }
+#define AGOQ_LAUNCH_NORM_FWD(B, G) AGOQ_LAUNCH_NORM_FWD_F(B, G, false)
+#define AGOQ_LAUNCH_NORM_FWD_FP(G) AGOQ_LAUNCH_NORM_FWD_F(4, G, true)
     if (fp) {
         if (group == 128) { AGOQ_LAUNCH_NORM_FWD_FP(128) } else { AGOQ_LAUNCH_NORM_FWD_FP(64) }
     } else if (group == 128) {
@@ -560,6 +638,9 @@ int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const
     }
 #undef AGOQ_LAUNCH_NORM_FWD_FP
 #undef AGOQ_LAUNCH_NORM_FWD
+#undef AGOQ_LAUNCH_NORM_FWD_F
+#undef AGOQ_LAUNCH_NORM_FWD_V
+#undef AGOQ_NORM_FWD_ARGS
     return launch_status();
 }
 

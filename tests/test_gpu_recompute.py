@@ -301,3 +301,33 @@ def test_fp4_rmsnorm_forward_with_quantized_input(agoq, ref, rows, cols, group):
     want_y, want_r = ref.rmsnorm_fwd(x, rows, cols, gamma, eps)
     assert np.allclose(r.cpu().numpy(), want_r, rtol=2e-6, atol=0)
     check_close_bf16(bits_of(y), want_y)
+
+
+# Shapes with enough rows per workgroup for the row kernels' steady loop (refills issued
+# without a test) plus a tail of every length: the grid is one or two workgroups per compute
+# unit on 14336-wide rows, eight on 4096-wide ones.
+MANY_ROWS = [(2048 + 52, 14336, 4), (2048 + 52, 14336, 8), (4096 + 700, 14336, 5), (4096 + 700, 14336, 6),
+             (16384 + 1031, 4096, 4), (8192 + 515, 4096, 8), (6 * 768 + 5, 5120, 8)]
+
+
+@pytest.mark.parametrize("rows,cols,bits", MANY_ROWS)
+def test_row_kernels_with_many_rows_per_workgroup(agoq, ref, rows, cols, bits):
+    group = 128
+    x = wl.act_host(rows, cols, 31000 + rows, "normal", max(1, cols // 200), 30.0)
+    x[rows // 2] = 0
+    rng = np.random.default_rng(rows)
+    gamma = (1.0 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    eps = 1e-5
+    y, r, codes, scales = agoq.rmsnorm_fwd_quant(dev_bf16(x), torch.from_numpy(gamma).cuda(), eps, group, bits)
+    torch.cuda.synchronize()
+    wc, ws = ref.act_quant(x, group, bits)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+    want_y, want_r = ref.rmsnorm_fwd(x, rows, cols, gamma, eps)
+    assert np.allclose(r.cpu().numpy(), want_r, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y), want_y)
+    want_y2, want_r2 = ref.act_dequant_rmsnorm(wc, ws, rows, cols, group, bits, gamma, eps)
+    y2, r2 = agoq.act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, torch.from_numpy(gamma).cuda(), eps)
+    torch.cuda.synchronize()
+    assert np.allclose(r2.cpu().numpy(), want_r2, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y2), want_y2)
