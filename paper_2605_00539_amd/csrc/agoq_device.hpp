@@ -24,6 +24,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "agoq.h"
 namespace {
 
@@ -516,20 +518,21 @@ inline unsigned blocks_for(int64_t items, int per_block)
     return (unsigned)((items + per_block - 1) / per_block);
 }
 
-// Compute units of the current device (cached per device ordinal).
+// Compute units of the current device (cached per device ordinal; threads that race on
+// the first call all store the same value).
 inline int compute_units()
 {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int cus = 0;
+    int cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             cus <= 0)
             cus = 256;
-        cached[dev] = cus;
+        cached[dev].store(cus, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return cus;
 }
 
 // True when a one-shot grid of `block`-thread workgroups with `unroll` vectors per lane needs
