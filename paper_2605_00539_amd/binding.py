@@ -105,6 +105,21 @@ def _dev(t, dtype, name):
     return t
 
 
+def _holds(t, count, name):
+    """The kernels take plain pointers and trust the sizes they are given: a buffer too small
+    for the call is refused here, where its size is still known."""
+    if t.numel() < count:
+        raise ValueError("%s holds %d elements, this call needs %d" % (name, t.numel(), count))
+
+
+def _code_bytes(n, bits):
+    return n * bits // 8 if bits in (4, 5, 6, 8) else 0
+
+
+def _groups(n, group):
+    return n // group if group > 0 else 0
+
+
 def _stream(stream):
     import torch
     if stream is None:
@@ -146,6 +161,8 @@ def act_quant(x, group, bits, codes=None, scales=None, stream=None):
         scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
     _dev(codes, torch.uint8, "codes")
     _dev(scales, torch.float32, "scales")
+    _holds(codes, _code_bytes(n, bits), "codes")
+    _holds(scales, _groups(n, group), "scales")
     with _on_device(x.device):
         _check(L.agoq_act_quant(_raw(x.data_ptr()), n, group, bits, _raw(codes.data_ptr()),
                                 _raw(scales.data_ptr()), _stream(stream)))
@@ -161,16 +178,19 @@ def act_dequant(codes, scales, numel, group, bits, out=None, stream=None):
     if out is None:
         out = torch.empty(numel, dtype=torch.bfloat16, device=codes.device)
     _dev(out, torch.bfloat16, "out")
+    _holds(codes, _code_bytes(numel, bits), "codes")
+    _holds(scales, _groups(numel, group), "scales")
+    _holds(out, numel, "out")
     with _on_device(codes.device):
         _check(L.agoq_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
                                   bits, _raw(out.data_ptr()), _stream(stream)))
     return out
 
 
-def layer_slots(xs, bits_list, codes_list, scales_list):
+def layer_slots(xs, bits_list, codes_list, scales_list, group=None):
     """Descriptor array (host memory) for a layer call from lists of device tensors: xs bf16,
     codes_list uint8, scales_list float32, bits_list ints.  Reusable across calls for as long as
-    the tensors live."""
+    the tensors live.  With `group` given, the sizes of the scale buffers are checked too."""
     import torch
     count = len(xs)
     if not (len(bits_list) == len(codes_list) == len(scales_list) == count):
@@ -182,6 +202,9 @@ def layer_slots(xs, bits_list, codes_list, scales_list):
         _dev(s, torch.float32, "scales[%d]" % i)
         if c.device != x.device or s.device != x.device:
             raise ValueError("layer call: all tensors must be on one device")
+        _holds(c, _code_bytes(x.numel(), int(b)), "codes[%d]" % i)
+        if group is not None:
+            _holds(s, _groups(x.numel(), group), "scales[%d]" % i)
         arr[i] = ActSlot(x.data_ptr(), c.data_ptr(), s.data_ptr(), x.numel(), int(b))
     return arr, count
 
@@ -199,7 +222,7 @@ def act_quant_layer(xs, group, bits_list, codes_list=None, scales_list=None, slo
         if scales_list is None:
             scales_list = [torch.empty(max(x.numel() // max(group, 1), 1), dtype=torch.float32,
                                        device=x.device) for x in xs]
-        slots = layer_slots(xs, bits_list, codes_list, scales_list)
+        slots = layer_slots(xs, bits_list, codes_list, scales_list, group)
     arr, count = slots
     with _on_device(xs[0].device):
         _check(L.agoq_act_quant_layer(arr, count, group, _stream(stream)))
@@ -219,7 +242,7 @@ def act_dequant_layer(codes_list, scales_list, numels, group, bits_list, outs=No
         for n, o in zip(numels, outs):
             if o.numel() != n:
                 raise ValueError("layer call: output size differs from numel")
-        slots = layer_slots(outs, bits_list, codes_list, scales_list)
+        slots = layer_slots(outs, bits_list, codes_list, scales_list, group)
     arr, count = slots
     with _on_device(codes_list[0].device):
         _check(L.agoq_act_dequant_layer(arr, count, group, _stream(stream)))
@@ -243,6 +266,10 @@ def act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, gamma, eps, out=
         r_out = torch.empty(rows, dtype=torch.float32, device=codes.device)
     _dev(out, torch.bfloat16, "out")
     _dev(r_out, torch.float32, "r_out")
+    _holds(codes, _code_bytes(rows * cols, bits), "codes")
+    _holds(scales, _groups(rows * cols, group), "scales")
+    _holds(out, rows * cols, "out")
+    _holds(r_out, rows, "r_out")
     with _on_device(codes.device):
         if fp4:
             if bits != 4:
@@ -272,6 +299,11 @@ def act_dequant_silu_mul(gate_codes, gate_scales, gate_bits, up_codes, up_scales
     if out is None:
         out = torch.empty(numel, dtype=torch.bfloat16, device=gate_codes.device)
     _dev(out, torch.bfloat16, "out")
+    _holds(gate_codes, _code_bytes(numel, gate_bits), "gate_codes")
+    _holds(up_codes, _code_bytes(numel, up_bits), "up_codes")
+    _holds(gate_scales, _groups(numel, group), "gate_scales")
+    _holds(up_scales, _groups(numel, group), "up_scales")
+    _holds(out, numel, "out")
     with _on_device(gate_codes.device):
         if fp4:
             if gate_bits != 4 or up_bits != 4:
@@ -361,6 +393,8 @@ def grad_quant(grad, group, codes=None, scales=None, stream=None):
         scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=grad.device)
     _dev(codes, torch.int8, "codes")
     _dev(scales, torch.float32, "scales")
+    _holds(codes, n, "codes")
+    _holds(scales, _groups(n, group), "scales")
     with _on_device(grad.device):
         _check(L.agoq_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
                                  _raw(scales.data_ptr()), _stream(stream)))
@@ -385,6 +419,8 @@ def grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_s
                                  device=in_codes.device)
     _dev(out_codes, torch.int8, "out_codes")
     _dev(out_scales, torch.float32, "out_scales")
+    _holds(out_codes, numel, "out_codes")
+    _holds(out_scales, _groups(numel, group), "out_scales")
     with _on_device(in_codes.device):
         _check(L.agoq_grad_reduce_requant(
             _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
@@ -413,6 +449,9 @@ def grad_accumulate(main_codes, main_scales, g_new, group, out_codes=None, out_s
         out_scales = main_scales
     _dev(out_codes, torch.int8, "out_codes")
     _dev(out_scales, torch.float32, "out_scales")
+    _holds(main_scales, _groups(n, group), "main_scales")
+    _holds(out_codes, n, "out_codes")
+    _holds(out_scales, _groups(n, group), "out_scales")
     with _on_device(main_codes.device):
         _check(L.agoq_grad_accumulate(
             _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
@@ -431,6 +470,8 @@ def grad_dequant(codes, scales, group, out=None, stream=None):
     if out is None:
         out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)
     _dev(out, torch.float32, "out")
+    _holds(scales, _groups(n, group), "scales")
+    _holds(out, n, "out")
     with _on_device(codes.device):
         _check(L.agoq_grad_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), n, group,
                                    _raw(out.data_ptr()), _stream(stream)))
@@ -450,6 +491,8 @@ def fp4_act_quant(x, group, codes=None, scales=None, stream=None):
         scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=x.device)
     _dev(codes, torch.uint8, "codes")
     _dev(scales, torch.float32, "scales")
+    _holds(codes, n // 2, "codes")
+    _holds(scales, _groups(n, group), "scales")
     with _on_device(x.device):
         _check(L.agoq_fp4_act_quant(_raw(x.data_ptr()), n, group, _raw(codes.data_ptr()),
                                     _raw(scales.data_ptr()), _stream(stream)))
@@ -464,6 +507,9 @@ def fp4_act_dequant(codes, scales, numel, group, out=None, stream=None):
     if out is None:
         out = torch.empty(numel, dtype=torch.bfloat16, device=codes.device)
     _dev(out, torch.bfloat16, "out")
+    _holds(codes, numel // 2, "codes")
+    _holds(scales, _groups(numel, group), "scales")
+    _holds(out, numel, "out")
     with _on_device(codes.device):
         _check(L.agoq_fp4_act_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), numel, group,
                                       _raw(out.data_ptr()), _stream(stream)))
@@ -481,6 +527,8 @@ def fp8_grad_quant(grad, group, codes=None, scales=None, stream=None):
         scales = torch.empty(max(n // max(group, 1), 1), dtype=torch.float32, device=grad.device)
     _dev(codes, torch.uint8, "codes")
     _dev(scales, torch.float32, "scales")
+    _holds(codes, n, "codes")
+    _holds(scales, _groups(n, group), "scales")
     with _on_device(grad.device):
         _check(L.agoq_fp8_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
                                      _raw(scales.data_ptr()), _stream(stream)))
@@ -496,6 +544,8 @@ def fp8_grad_dequant(codes, scales, group, out=None, stream=None):
     if out is None:
         out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)
     _dev(out, torch.float32, "out")
+    _holds(scales, _groups(n, group), "scales")
+    _holds(out, n, "out")
     with _on_device(codes.device):
         _check(L.agoq_fp8_grad_dequant(_raw(codes.data_ptr()), _raw(scales.data_ptr()), n, group,
                                        _raw(out.data_ptr()), _stream(stream)))
@@ -518,6 +568,8 @@ def fp8_grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, o
                                  device=in_codes.device)
     _dev(out_codes, torch.uint8, "out_codes")
     _dev(out_scales, torch.float32, "out_scales")
+    _holds(out_codes, numel, "out_codes")
+    _holds(out_scales, _groups(numel, group), "out_scales")
     with _on_device(in_codes.device):
         _check(L.agoq_fp8_grad_reduce_requant(
             _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
@@ -543,6 +595,9 @@ def fp8_grad_accumulate(main_codes, main_scales, g_new, group, out_codes=None, o
     out_scales = main_scales if out_scales is None else out_scales
     _dev(out_codes, torch.uint8, "out_codes")
     _dev(out_scales, torch.float32, "out_scales")
+    _holds(main_scales, _groups(n, group), "main_scales")
+    _holds(out_codes, n, "out_codes")
+    _holds(out_scales, _groups(n, group), "out_scales")
     with _on_device(main_codes.device):
         _check(L.agoq_fp8_grad_accumulate(
             _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
