@@ -28,7 +28,7 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBPS = 8000.0
 # HBM bytes per launch of the K=8 reduce kernel on this workload, from hardware counters
 # (FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy; summary under profiles/)
-TRAFFIC_REDUCE_K8_BYTES = 2024940725
+TRAFFIC_REDUCE_K8_BYTES = 2024878722
 GROUP = 128
 K_CHUNKS = 8
 SLOT_NAMES = ("norm1_in", "oproj_in", "norm2_in", "gate", "up")
