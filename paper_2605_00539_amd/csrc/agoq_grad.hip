@@ -199,9 +199,18 @@ int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_
                   float* out_scales, hipStream_t st)
 {
     const bool two = n_vec >= kReduceTwoVectorsFrom;
+#ifndef AGOQ_RD2_BLOCK         // the large-tensor shape of the compile-time-K reduce
+#define AGOQ_RD2_BLOCK 256
+#endif
+#ifndef AGOQ_RD2_RU
+#define AGOQ_RD2_RU 2
+#endif
+#ifndef AGOQ_RD2_CAP_KB
+#define AGOQ_RD2_CAP_KB 64
+#endif
 #define AGOQ_LAUNCH_REDUCE(G, KT)                                                               \
     if (two)                                                                                    \
-        grad_reduce_kernel<G, KT, FP, 256, 2><<<dim3(blocks_for(n_vec, 512)), dim3(256), kTwoPerCuLds, st>>>( \
+        grad_reduce_kernel<G, KT, FP, AGOQ_RD2_BLOCK, AGOQ_RD2_RU><<<dim3(blocks_for(n_vec, AGOQ_RD2_BLOCK * AGOQ_RD2_RU)), dim3(AGOQ_RD2_BLOCK), (size_t)AGOQ_RD2_CAP_KB * 1024, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales);           \
     else                                                                                        \
         grad_reduce_kernel<G, KT, FP, 512, 1><<<dim3(blocks_for(n_vec, 512)), dim3(512), kTwoPerCuLds, st>>>( \
