@@ -101,6 +101,9 @@ __device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, fl
 // K known at compile time (4, 8, 16): RU 16-byte vectors per lane, all RU*K code loads and
 // scale loads of the lane issued before the first is needed, then one vector after the
 // other is summed, requantized and stored.
+#ifndef AGOQ_RD_PRIO_FROM_K     // chunk count from which the loads are issued at raised priority; 0 = never
+#define AGOQ_RD_PRIO_FROM_K 16
+#endif
 template <int GROUP, int KT, bool FP, int BLOCK, int RU>
 __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
                                                      int64_t stride_codes,
@@ -114,6 +117,11 @@ __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __rest
     const int64_t base = (int64_t)blockIdx.x * (BLOCK * RU) + threadIdx.x;
     u32x4 c[RU][KT];
     float s[RU][KT];
+    // With 16 chunks and two vectors per lane a wavefront issues 64 loads; at raised priority
+    // it issues them in one go instead of taking turns with the wavefront that is summing
+    // (measured: +4 % at K = 16, nothing at K = 8, -1 % on the one-vector shape).
+    constexpr bool kLoadsFirst = AGOQ_RD_PRIO_FROM_K > 0 && RU > 1 && KT >= AGOQ_RD_PRIO_FROM_K;
+    if (kLoadsFirst) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
         const int64_t vi = base + (int64_t)u * BLOCK;
@@ -123,6 +131,10 @@ __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __rest
             c[u][k] = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
             s[u][k] = ld<NTSC>(in_scales + (int64_t)k * stride_scales + vc / LANES);
         }
+    }
+    if (kLoadsFirst) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
     }
     if (RU > 1) {
         // no load may be waited for after the first store has been issued
