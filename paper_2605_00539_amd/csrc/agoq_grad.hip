@@ -211,6 +211,15 @@ int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_
                   float* out_scales, hipStream_t st)
 {
     const bool two = n_vec >= kReduceTwoVectorsFrom;
+#ifndef AGOQ_RD1_BLOCK         // the small-tensor shape of the compile-time-K reduce
+#define AGOQ_RD1_BLOCK 512
+#endif
+#ifndef AGOQ_RD1_RU
+#define AGOQ_RD1_RU 1
+#endif
+#ifndef AGOQ_RD1_CAP_KB
+#define AGOQ_RD1_CAP_KB 64
+#endif
 #ifndef AGOQ_RD2_BLOCK         // the large-tensor shape of the compile-time-K reduce
 #define AGOQ_RD2_BLOCK 256
 #endif
@@ -225,7 +234,7 @@ int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_
         grad_reduce_kernel<G, KT, FP, AGOQ_RD2_BLOCK, AGOQ_RD2_RU><<<dim3(blocks_for(n_vec, AGOQ_RD2_BLOCK * AGOQ_RD2_RU)), dim3(AGOQ_RD2_BLOCK), (size_t)AGOQ_RD2_CAP_KB * 1024, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales);           \
     else                                                                                        \
-        grad_reduce_kernel<G, KT, FP, 512, 1><<<dim3(blocks_for(n_vec, 512)), dim3(512), kTwoPerCuLds, st>>>( \
+        grad_reduce_kernel<G, KT, FP, AGOQ_RD1_BLOCK, AGOQ_RD1_RU><<<dim3(blocks_for(n_vec, AGOQ_RD1_BLOCK * AGOQ_RD1_RU)), dim3(AGOQ_RD1_BLOCK), (size_t)AGOQ_RD1_CAP_KB * 1024, st>>>( \
             in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales)
 #ifndef AGOQ_RD_SMALLK_BLOCK
 #define AGOQ_RD_SMALLK_BLOCK 256
