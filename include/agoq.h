@@ -62,7 +62,7 @@ enum {
     AGOQ_ERR_SHAPE = 4, /* numel <= 0, numel % group != 0, or a stride below its extent */
     AGOQ_ERR_ALIGN = 5, /* a pointer (or a chunk stride) breaks 16-byte alignment */
     AGOQ_ERR_K = 6,     /* K outside 1..64 */
-    AGOQ_ERR_HIP = 7,   /* the HIP runtime refused the launch */
+    AGOQ_ERR_HIP = 7,   /* the HIP runtime refused this launch (the launch call's own status) */
     AGOQ_ERR_COUNT = 8  /* a layer call with fewer than 1 or more than AGOQ_MAX_LAYER_SLOTS tensors */
 };
 
@@ -320,6 +320,22 @@ int64_t agoq_layer_stored_bytes(int64_t tokens, int64_t hidden, int64_t ffn, int
 
 /* Static string for a status code. */
 const char *agoq_strerror(int status);
+
+/*
+ * Measurement aid (no passage of the paper: this is not part of the method).  A streaming
+ * kernel with the memory traffic of an encode or decode kernel and none of its arithmetic:
+ * lane item i loads load_bytes bytes from src + i*load_bytes and stores store_bytes bytes to
+ * dst + i*store_bytes.  Its run time on a tensor's footprint is the floor that a single
+ * launch with this access pattern can reach at all (ramp and drain of a launch and the
+ * memory system's read/write mix included); the benchmark reports it beside the real
+ * kernels on tensors small enough for that fixed cost to matter.
+ *   load_bytes  : 4, 8 or 16            store_bytes : 0 (read only), 4, 8 or 16
+ *   src : in,  items*load_bytes bytes   dst : out, items*store_bytes bytes (at least 4)
+ *   (16 B -> 4 B is the traffic of the 4-bit quantize, 4 B -> 16 B of the 4-bit dequantize)
+ * Errors: AGOQ_ERR_BITS for an unsupported width, AGOQ_ERR_SHAPE for items outside 1..2^36.
+ */
+int agoq_probe_stream(const void *src, int load_bytes, void *dst, int store_bytes, int64_t items,
+                      void *stream);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int agoq_version(void);

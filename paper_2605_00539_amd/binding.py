@@ -3,8 +3,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# AGOQ_LIBRARY names another build of the same library (a tuning variant); default: in-tree
-_LIB_PATH = os.environ.get("AGOQ_LIBRARY") or os.path.join(_HERE, "libagoq.so")
+_LIB_PATH = os.path.join(_HERE, "libagoq.so")      # the in-tree build, the only one ever loaded
 _lib = None
 
 _I64 = ctypes.c_int64
@@ -64,6 +63,7 @@ def load_library():
     L.agoq_fp8_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P, _P]
     L.agoq_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_fp8_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
+    L.agoq_probe_stream.argtypes = [_P, _INT, _P, _INT, _I64, _P]
     L.agoq_codes_bytes.argtypes = [_I64, _INT]
     L.agoq_codes_bytes.restype = _I64
     L.agoq_num_groups.argtypes = [_I64, _INT]
@@ -187,10 +187,22 @@ def act_dequant(codes, scales, numel, group, bits, out=None, stream=None):
     return out
 
 
-def layer_slots(xs, bits_list, codes_list, scales_list, group=None):
-    """Descriptor array (host memory) for a layer call from lists of device tensors: xs bf16,
-    codes_list uint8, scales_list float32, bits_list ints.  Reusable across calls for as long as
-    the tensors live.  With `group` given, the sizes of the scale buffers are checked too."""
+class LayerSlots:
+    """Descriptor array of a layer call (host memory, raw device pointers) together with the
+    tensors those pointers belong to, which it keeps alive for as long as it lives."""
+
+    def __init__(self, array, count, group, device, tensors):
+        self.array, self.count, self.group, self.device = array, count, group, device
+        self._tensors = tensors
+
+    def __iter__(self):                     # (array, count) = slots
+        return iter((self.array, self.count))
+
+
+def layer_slots(xs, bits_list, codes_list, scales_list, group):
+    """Descriptor array for a layer call from lists of device tensors: xs bf16, codes_list uint8,
+    scales_list float32, bits_list ints.  Every buffer's size is checked against what a call
+    with this `group` reads or writes.  Reusable across calls; holds references to the tensors."""
     import torch
     count = len(xs)
     if not (len(bits_list) == len(codes_list) == len(scales_list) == count):
@@ -200,13 +212,21 @@ def layer_slots(xs, bits_list, codes_list, scales_list, group=None):
         _dev(x, torch.bfloat16, "bf16[%d]" % i)
         _dev(c, torch.uint8, "codes[%d]" % i)
         _dev(s, torch.float32, "scales[%d]" % i)
-        if c.device != x.device or s.device != x.device:
+        if c.device != x.device or s.device != x.device or x.device != xs[0].device:
             raise ValueError("layer call: all tensors must be on one device")
         _holds(c, _code_bytes(x.numel(), int(b)), "codes[%d]" % i)
-        if group is not None:
-            _holds(s, _groups(x.numel(), group), "scales[%d]" % i)
+        _holds(s, _groups(x.numel(), group), "scales[%d]" % i)
         arr[i] = ActSlot(x.data_ptr(), c.data_ptr(), s.data_ptr(), x.numel(), int(b))
-    return arr, count
+    device = xs[0].device if count else None
+    return LayerSlots(arr, count, group, device, (list(xs), list(codes_list), list(scales_list)))
+
+
+def _slots_for(slots, group):
+    if not isinstance(slots, LayerSlots):
+        raise TypeError("slots must come from layer_slots()")
+    if slots.group != group:
+        raise ValueError("slots were made for group %d, this call uses %d" % (slots.group, group))
+    return slots
 
 
 def act_quant_layer(xs, group, bits_list, codes_list=None, scales_list=None, slots=None, stream=None):
@@ -223,9 +243,9 @@ def act_quant_layer(xs, group, bits_list, codes_list=None, scales_list=None, slo
             scales_list = [torch.empty(max(x.numel() // max(group, 1), 1), dtype=torch.float32,
                                        device=x.device) for x in xs]
         slots = layer_slots(xs, bits_list, codes_list, scales_list, group)
-    arr, count = slots
-    with _on_device(xs[0].device):
-        _check(L.agoq_act_quant_layer(arr, count, group, _stream(stream)))
+    slots = _slots_for(slots, group)
+    with _on_device(slots.device):
+        _check(L.agoq_act_quant_layer(slots.array, slots.count, group, _stream(stream)))
     return codes_list, scales_list
 
 
@@ -243,9 +263,9 @@ def act_dequant_layer(codes_list, scales_list, numels, group, bits_list, outs=No
             if o.numel() != n:
                 raise ValueError("layer call: output size differs from numel")
         slots = layer_slots(outs, bits_list, codes_list, scales_list, group)
-    arr, count = slots
-    with _on_device(codes_list[0].device):
-        _check(L.agoq_act_dequant_layer(arr, count, group, _stream(stream)))
+    slots = _slots_for(slots, group)
+    with _on_device(slots.device):
+        _check(L.agoq_act_dequant_layer(slots.array, slots.count, group, _stream(stream)))
     return outs
 
 

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagoq.so")
 SOURCES = [os.path.join(CSRC, name) for name in
-           ("agoq_act.hip", "agoq_grad.hip", "agoq_recompute.hip", "agoq_host.cpp")]
+           ("agoq_act.hip", "agoq_grad.hip", "agoq_recompute.hip", "agoq_probe.hip", "agoq_host.cpp")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

@@ -26,8 +26,8 @@ __device__ __forceinline__ void act_quant_body(const u32x4* __restrict__ x, int6
                                                unsigned block)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = AGOQ_AQ_BLOCK;
-    constexpr bool NTL = AGOQ_AQ_NTL, NTS = AGOQ_AQ_NTS;
+    constexpr int kBlock = kAqBlock;
+    constexpr bool NTL = true, NTS = true;
     const int64_t base = (int64_t)block * (kBlock * UNROLL) + threadIdx.x;
 
     u32x4 v[UNROLL];
@@ -53,14 +53,14 @@ __device__ __forceinline__ void act_quant_tile(const u32x4* __restrict__ x, int6
                                                void* __restrict__ codes, float* __restrict__ scales,
                                                unsigned block)
 {
-    if (((int64_t)block + 1) * (AGOQ_AQ_BLOCK * UNROLL) <= n_vec)
+    if (((int64_t)block + 1) * (kAqBlock * UNROLL) <= n_vec)
         act_quant_body<BITS, GROUP, UNROLL, FP, true>(x, n_vec, codes, scales, block);
     else
         act_quant_body<BITS, GROUP, UNROLL, FP, false>(x, n_vec, codes, scales, block);
 }
 
 template <int BITS, int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_kernel(const u32x4* __restrict__ x,
+__global__ __launch_bounds__(kAqBlock) void act_quant_kernel(const u32x4* __restrict__ x,
                                                            int64_t n_vec, void* __restrict__ codes,
                                                            float* __restrict__ scales)
 {
@@ -82,8 +82,8 @@ __device__ __forceinline__ void act_dequant_body(const void* __restrict__ codes,
 {
     static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = AGOQ_DQ_BLOCK;
-    constexpr bool NTC = AGOQ_DQ_NTC, NTSC = AGOQ_DQ_NTSC, NTS = AGOQ_DQ_NTS;
+    constexpr int kBlock = kDqBlock;
+    constexpr bool NTC = true, NTSC = false, NTS = true;
     const int64_t base = (int64_t)block * (kBlock * UNROLL) + threadIdx.x;
 
     // loads; decode (uses every loaded value); pack and store -- see act_quant_body
@@ -128,14 +128,14 @@ __device__ __forceinline__ void act_dequant_tile(const void* __restrict__ codes,
                                                  const float* __restrict__ scales, int64_t n_vec,
                                                  u32x4* __restrict__ y, unsigned block)
 {
-    if (((int64_t)block + 1) * (AGOQ_DQ_BLOCK * UNROLL) <= n_vec)
+    if (((int64_t)block + 1) * (kDqBlock * UNROLL) <= n_vec)
         act_dequant_body<BITS, GROUP, UNROLL, FP, true, PACE>(codes, scales, n_vec, y, block);
     else
         act_dequant_body<BITS, GROUP, UNROLL, FP, false, PACE>(codes, scales, n_vec, y, block);
 }
 
 template <int BITS, int GROUP, int UNROLL, bool FP = false, bool PACE = false>
-__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_kernel(const void* __restrict__ codes,
+__global__ __launch_bounds__(kDqBlock) void act_dequant_kernel(const void* __restrict__ codes,
                                                              const float* __restrict__ scales,
                                                              int64_t n_vec, u32x4* __restrict__ y)
 {
@@ -168,17 +168,11 @@ __device__ __forceinline__ int layer_slot_of(const LayerArgs& a, unsigned block)
 
 // Vectors per lane in the layer dequantize (measured on 8B-shaped layers at seq 4096 and
 // 8192 under every stage map: two for every width is best or within 1% of best).
-#ifndef AGOQ_LDQ_UNROLL8
-#define AGOQ_LDQ_UNROLL8 2
-#endif
-#ifndef AGOQ_LDQ_UNROLL
-#define AGOQ_LDQ_UNROLL 2
-#endif
-constexpr int kLayerDqUnroll8 = AGOQ_LDQ_UNROLL8;   // 8-bit codes
-constexpr int kLayerDqUnroll = AGOQ_LDQ_UNROLL;     // 4-, 5- and 6-bit codes
+constexpr int kLayerDqUnroll8 = 2;   // 8-bit codes
+constexpr int kLayerDqUnroll = 2;    // 4-, 5- and 6-bit codes
 
 template <int GROUP>
-__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_layer_kernel(const LayerArgs a)
+__global__ __launch_bounds__(kAqBlock) void act_quant_layer_kernel(const LayerArgs a)
 {
     const int t = layer_slot_of(a, blockIdx.x);
     const unsigned block = blockIdx.x - a.first_block[t];
@@ -187,15 +181,15 @@ __global__ __launch_bounds__(AGOQ_AQ_BLOCK) void act_quant_layer_kernel(const La
     float* scales = a.scales[t];
     const int64_t n_vec = a.n_vec[t];
     switch (a.bits[t]) {
-    case 4: act_quant_tile<4, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
-    case 5: act_quant_tile<5, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
-    case 6: act_quant_tile<6, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
-    default: act_quant_tile<8, GROUP, AGOQ_AQ_UNROLL, false>(x, n_vec, codes, scales, block); break;
+    case 4: act_quant_tile<4, GROUP, kAqUnroll, false>(x, n_vec, codes, scales, block); break;
+    case 5: act_quant_tile<5, GROUP, kAqUnroll, false>(x, n_vec, codes, scales, block); break;
+    case 6: act_quant_tile<6, GROUP, kAqUnroll, false>(x, n_vec, codes, scales, block); break;
+    default: act_quant_tile<8, GROUP, kAqUnroll, false>(x, n_vec, codes, scales, block); break;
     }
 }
 
 template <int GROUP>
-__global__ __launch_bounds__(AGOQ_DQ_BLOCK) void act_dequant_layer_kernel(const LayerArgs a)
+__global__ __launch_bounds__(kDqBlock) void act_dequant_layer_kernel(const LayerArgs a)
 {
     const int t = layer_slot_of(a, blockIdx.x);
     const unsigned block = blockIdx.x - a.first_block[t];
@@ -234,8 +228,8 @@ int layer_args(const agoq_act_slot* slots, int count, int group, bool quantize, 
         if (int rc = check_common(s.numel, group)) return rc;
         if (misaligned(s.bf16) || misaligned(s.codes) || misaligned(s.scales)) return AGOQ_ERR_ALIGN;
         const int64_t n_vec = s.numel / 8;
-        const int per_block = quantize ? AGOQ_AQ_BLOCK * AGOQ_AQ_UNROLL
-                                       : AGOQ_DQ_BLOCK * (s.bits == 8 ? kLayerDqUnroll8 : kLayerDqUnroll);
+        const int per_block = quantize ? kAqBlock * kAqUnroll
+                                       : kDqBlock * (s.bits == 8 ? kLayerDqUnroll8 : kLayerDqUnroll);
         a.src[i] = quantize ? (const void*)s.bf16 : (const void*)s.codes;
         a.dst[i] = quantize ? s.codes : s.bf16;
         a.scales[i] = s.scales;
@@ -261,29 +255,11 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    const int unroll = AGOQ_AQ_UNROLL;
-    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * unroll)), block(AGOQ_AQ_BLOCK);
-    hipStream_t st = (hipStream_t)stream;
-    const u32x4* x = (const u32x4*)x_bf16;
-#define AGOQ_LAUNCH_AQ(B, G)                                                                     \
-    act_quant_kernel<B, G, AGOQ_AQ_UNROLL><<<grid, block, kCapLds, st>>>(x, n_vec, codes, scales);
-    if (group == 128) {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_AQ(4, 128) break;
-        case 5: AGOQ_LAUNCH_AQ(5, 128) break;
-        case 6: AGOQ_LAUNCH_AQ(6, 128) break;
-        default: AGOQ_LAUNCH_AQ(8, 128) break;
-        }
-    } else {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_AQ(4, 64) break;
-        case 5: AGOQ_LAUNCH_AQ(5, 64) break;
-        case 6: AGOQ_LAUNCH_AQ(6, 64) break;
-        default: AGOQ_LAUNCH_AQ(8, 64) break;
-        }
-    }
-#undef AGOQ_LAUNCH_AQ
-    return launch_status();
+    const dim3 grid(blocks_for(n_vec, kAqBlock * kAqUnroll)), block(kAqBlock);
+    return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+        return launch(act_quant_kernel<decltype(b)::value, decltype(g)::value, kAqUnroll>, grid, block, 0,
+                      (hipStream_t)stream, (const u32x4*)x_bf16, n_vec, codes, scales);
+    });
 }
 
 int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int group, int bits,
@@ -298,43 +274,20 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     // best with four vectors per lane, 8-bit codes then with paced stores; larger tensors
     // with two
     // ("about": up to one and a half rounds; for 8-bit codes exactly one)
-    int unroll = AGOQ_DQ_FORCE_UNROLL;
-    const bool small = bits == 8 ? fits_rounds(n_vec, AGOQ_DQ_BLOCK, 4, 1, 1)
-                                 : fits_rounds(n_vec, AGOQ_DQ_BLOCK, 4, 3, 2);
-    if (unroll == 0) unroll = small ? 4 : 2;
-    const bool pace = small && bits == 8;
-    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
+    const bool small = bits == 8 ? fits_rounds(n_vec, kDqBlock, 4, 1, 1)
+                                 : fits_rounds(n_vec, kDqBlock, 4, 3, 2);
+    const int unroll = small ? 4 : 2;
+    const dim3 grid(blocks_for(n_vec, kDqBlock * unroll)), block(kDqBlock);
+    const size_t cap = (bits == 8 && !small) ? kCapDq8 : 0;
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
-    const size_t cap = (bits == 8 && !small) ? kCapDq8 : kCapLds;
-#define AGOQ_LAUNCH_DQ(B, G)                                                                      \
-    switch (unroll) {                                                                             \
-    case 4: act_dequant_kernel<B, G, 4><<<grid, block, cap, st>>>(codes, scales, n_vec, y); break;  \
-    case 2: act_dequant_kernel<B, G, 2><<<grid, block, cap, st>>>(codes, scales, n_vec, y); break;  \
-    default: act_dequant_kernel<B, G, 1><<<grid, block, cap, st>>>(codes, scales, n_vec, y); break; \
-    }
-    if (pace && unroll == 4) {
-        if (group == 128)
-            act_dequant_kernel<8, 128, 4, false, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
-        else
-            act_dequant_kernel<8, 64, 4, false, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
-    } else if (group == 128) {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_DQ(4, 128) break;
-        case 5: AGOQ_LAUNCH_DQ(5, 128) break;
-        case 6: AGOQ_LAUNCH_DQ(6, 128) break;
-        default: AGOQ_LAUNCH_DQ(8, 128) break;
-        }
-    } else {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_DQ(4, 64) break;
-        case 5: AGOQ_LAUNCH_DQ(5, 64) break;
-        case 6: AGOQ_LAUNCH_DQ(6, 64) break;
-        default: AGOQ_LAUNCH_DQ(8, 64) break;
-        }
-    }
-#undef AGOQ_LAUNCH_DQ
-    return launch_status();
+    return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+        constexpr int B = decltype(b)::value, G = decltype(g)::value;
+        if (small && B == 8)
+            return launch(act_dequant_kernel<B, G, 4, false, B == 8>, grid, block, cap, st, codes, scales, n_vec, y);
+        if (small) return launch(act_dequant_kernel<B, G, 4>, grid, block, cap, st, codes, scales, n_vec, y);
+        return launch(act_dequant_kernel<B, G, 2>, grid, block, cap, st, codes, scales, n_vec, y);
+    });
 }
 
 int agoq_fp4_act_quant(const void* x_bf16, int64_t numel, int group, void* codes, float* scales,
@@ -344,15 +297,12 @@ int agoq_fp4_act_quant(const void* x_bf16, int64_t numel, int group, void* codes
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    constexpr int U = AGOQ_AQ_UNROLL;
-    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+    const dim3 grid(blocks_for(n_vec, kAqBlock * kAqUnroll)), block(kAqBlock);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     if (group == 128)
-        act_quant_kernel<4, 128, U, true><<<grid, block, kCapLds, st>>>(x, n_vec, codes, scales);
-    else
-        act_quant_kernel<4, 64, U, true><<<grid, block, kCapLds, st>>>(x, n_vec, codes, scales);
-    return launch_status();
+        return launch(act_quant_kernel<4, 128, kAqUnroll, true>, grid, block, 0, st, x, n_vec, codes, scales);
+    return launch(act_quant_kernel<4, 64, kAqUnroll, true>, grid, block, 0, st, x, n_vec, codes, scales);
 }
 
 int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, int group,
@@ -362,22 +312,16 @@ int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, 
     if (int rc = check_common(numel, group)) return rc;
     if (misaligned(codes) || misaligned(scales) || misaligned(y_bf16)) return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    const int unroll = fits_rounds(n_vec, AGOQ_DQ_BLOCK, 4, 3, 2) ? 4 : 2;   // as for 4-bit integer codes
-    const dim3 grid(blocks_for(n_vec, AGOQ_DQ_BLOCK * unroll)), block(AGOQ_DQ_BLOCK);
+    const bool small = fits_rounds(n_vec, kDqBlock, 4, 3, 2);   // as for 4-bit integer codes
+    const dim3 grid(blocks_for(n_vec, kDqBlock * (small ? 4 : 2))), block(kDqBlock);
     hipStream_t st = (hipStream_t)stream;
     u32x4* y = (u32x4*)y_bf16;
     if (group == 128) {
-        if (unroll == 4)
-            act_dequant_kernel<4, 128, 4, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
-        else
-            act_dequant_kernel<4, 128, 2, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
-    } else {
-        if (unroll == 4)
-            act_dequant_kernel<4, 64, 4, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
-        else
-            act_dequant_kernel<4, 64, 2, true><<<grid, block, kCapLds, st>>>(codes, scales, n_vec, y);
+        if (small) return launch(act_dequant_kernel<4, 128, 4, true>, grid, block, 0, st, codes, scales, n_vec, y);
+        return launch(act_dequant_kernel<4, 128, 2, true>, grid, block, 0, st, codes, scales, n_vec, y);
     }
-    return launch_status();
+    if (small) return launch(act_dequant_kernel<4, 64, 4, true>, grid, block, 0, st, codes, scales, n_vec, y);
+    return launch(act_dequant_kernel<4, 64, 2, true>, grid, block, 0, st, codes, scales, n_vec, y);
 }
 
 int agoq_act_quant_layer(const agoq_act_slot* slots, int count, int group, void* stream)
@@ -386,11 +330,8 @@ int agoq_act_quant_layer(const agoq_act_slot* slots, int count, int group, void*
     unsigned blocks = 0;
     if (int rc = layer_args(slots, count, group, true, a, blocks)) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (group == 128)
-        act_quant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLq, st>>>(a);
-    else
-        act_quant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_AQ_BLOCK), kCapLq, st>>>(a);
-    return launch_status();
+    if (group == 128) return launch(act_quant_layer_kernel<128>, dim3(blocks), dim3(kAqBlock), 0, st, a);
+    return launch(act_quant_layer_kernel<64>, dim3(blocks), dim3(kAqBlock), 0, st, a);
 }
 
 int agoq_act_dequant_layer(const agoq_act_slot* slots, int count, int group, void* stream)
@@ -399,11 +340,8 @@ int agoq_act_dequant_layer(const agoq_act_slot* slots, int count, int group, voi
     unsigned blocks = 0;
     if (int rc = layer_args(slots, count, group, false, a, blocks)) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (group == 128)
-        act_dequant_layer_kernel<128><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), kCapLdq, st>>>(a);
-    else
-        act_dequant_layer_kernel<64><<<dim3(blocks), dim3(AGOQ_DQ_BLOCK), kCapLdq, st>>>(a);
-    return launch_status();
+    if (group == 128) return launch(act_dequant_layer_kernel<128>, dim3(blocks), dim3(kDqBlock), kCapLdq, st, a);
+    return launch(act_dequant_layer_kernel<64>, dim3(blocks), dim3(kDqBlock), kCapLdq, st, a);
 }
 
 }  // extern "C"

@@ -25,6 +25,8 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <tuple>
+#include <type_traits>
 
 #include "agoq.h"
 namespace {
@@ -34,121 +36,24 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// ---- launch shapes and cache hints, per kernel (measured on MI355X) ------------------
-// Each macro can be overridden on the compiler command line for tuning sweeps.
-#ifndef AGOQ_AQ_BLOCK          // activation quantize
-#define AGOQ_AQ_BLOCK 128
-#endif
-#ifndef AGOQ_AQ_UNROLL         // 16-byte vectors per lane: 1, 2 or 4
-#define AGOQ_AQ_UNROLL 2
-#endif
-#ifndef AGOQ_AQ_NTL
-#define AGOQ_AQ_NTL 1
-#endif
-#ifndef AGOQ_AQ_NTS
-#define AGOQ_AQ_NTS 1
-#endif
-#ifndef AGOQ_DQ_BLOCK          // activation dequantize
-#define AGOQ_DQ_BLOCK 512
-#endif
-#ifndef AGOQ_DQ_FORCE_UNROLL   // 0 = chosen per launch; else 1, 2 or 4
-#define AGOQ_DQ_FORCE_UNROLL 0
-#endif
-#ifndef AGOQ_DQ_NTC            // code loads
-#define AGOQ_DQ_NTC 1
-#endif
-#ifndef AGOQ_DQ_NTSC           // scale loads
-#define AGOQ_DQ_NTSC 0
-#endif
-#ifndef AGOQ_DQ_NTS
-#define AGOQ_DQ_NTS 1
-#endif
-#ifndef AGOQ_GQ_BLOCK          // gradient quantize
-#define AGOQ_GQ_BLOCK 256
-#endif
-#ifndef AGOQ_GQ_UNROLL
-#define AGOQ_GQ_UNROLL 1
-#endif
-#ifndef AGOQ_GQ_NTL
-#define AGOQ_GQ_NTL 1
-#endif
-#ifndef AGOQ_GQ_NTS
-#define AGOQ_GQ_NTS 1
-#endif
-#ifndef AGOQ_RD_BLOCK          // reduce + requantize
-#define AGOQ_RD_BLOCK 512
-#endif
-#ifndef AGOQ_RD_NTC
-#define AGOQ_RD_NTC 1
-#endif
-#ifndef AGOQ_RD_NTSC
-#define AGOQ_RD_NTSC 1
-#endif
-#ifndef AGOQ_RD_NTS
-#define AGOQ_RD_NTS 1
-#endif
-
-#ifndef AGOQ_SCALE_NT          // scale stores (a few bytes per wavefront) streaming too, or cached
-#define AGOQ_SCALE_NT 1
-#endif
-#ifndef AGOQ_SI_BLOCK          // SiLU & Multiply recompute
-#define AGOQ_SI_BLOCK 256
-#endif
-#ifndef AGOQ_SI_UNROLL
-#define AGOQ_SI_UNROLL 2
-#endif
-#ifndef AGOQ_GB_BLOCK          // accumulate, bf16 addend
-#define AGOQ_GB_BLOCK 128
-#endif
-#ifndef AGOQ_GB_UNROLL
-#define AGOQ_GB_UNROLL 2
-#endif
-// Occupancy caps: dynamic LDS (KB per workgroup, never touched by the kernel) that limits
-// how many workgroups share a compute unit's 160 KB.  Measured per kernel: kernels that
-// read or write several streams at once run faster with fewer wavefronts in flight than
-// the registers allow.  0 = no cap.
-#ifndef AGOQ_GA_CAP_KB         // accumulate, fp32 addend: 6 workgroups of 256
-#define AGOQ_GA_CAP_KB 26
-#endif
-#ifndef AGOQ_SF_CAP_KB         // SiLU & Multiply forward + quantize: 8 workgroups of 128
-#define AGOQ_SF_CAP_KB 20
-#endif
-#ifndef AGOQ_GD_CAP_KB         // gradient dequantize
-#define AGOQ_GD_CAP_KB 0
-#endif
-#ifndef AGOQ_SI_CAP_KB         // SiLU & Multiply recompute
-#define AGOQ_SI_CAP_KB 0
-#endif
-#ifndef AGOQ_LQ_CAP_KB         // layer quantize
-#define AGOQ_LQ_CAP_KB 0
-#endif
-#ifndef AGOQ_LDQ_CAP_KB        // layer dequantize: 3 workgroups of 512
-#define AGOQ_LDQ_CAP_KB 48
-#endif
-#ifndef AGOQ_DQ8_CAP_KB        // dequantize of 8-bit codes, tensors beyond one round: 3 of 512
-#define AGOQ_DQ8_CAP_KB 48
-#endif
-#ifndef AGOQ_CAP_KB            // tuning: dynamic LDS (KB, never touched) per workgroup of the
-#define AGOQ_CAP_KB 0          // kernels that have no cap of their own; 0 = no cap
-#endif
-#ifndef AGOQ_GD_BLOCK          // gradient dequantize
-#define AGOQ_GD_BLOCK 512
-#endif
-#ifndef AGOQ_GD_UNROLL
-#define AGOQ_GD_UNROLL 2
-#endif
-#ifndef AGOQ_GD_NTS
-#define AGOQ_GD_NTS 1
-#endif
-
-constexpr size_t kCapLds = (size_t)AGOQ_CAP_KB * 1024;
-constexpr size_t kCapGa = (size_t)AGOQ_GA_CAP_KB * 1024;
-constexpr size_t kCapSf = (size_t)AGOQ_SF_CAP_KB * 1024;
-constexpr size_t kCapGd = (size_t)AGOQ_GD_CAP_KB * 1024;
-constexpr size_t kCapSi = (size_t)AGOQ_SI_CAP_KB * 1024;
-constexpr size_t kCapLq = (size_t)AGOQ_LQ_CAP_KB * 1024;
-constexpr size_t kCapLdq = (size_t)AGOQ_LDQ_CAP_KB * 1024;
-constexpr size_t kCapDq8 = (size_t)AGOQ_DQ8_CAP_KB * 1024;
+// ---- launch shapes, per kernel (measured on MI355X) ------------------------------------
+// Block = lanes per workgroup, Unroll = 16-byte vectors (or dwords of codes) per lane.
+// Every streaming load and store carries the non-temporal hint except the loads of scales in
+// the dequantize kernels (a scale is read by up to 16 lanes).
+constexpr int kAqBlock = 128, kAqUnroll = 2;     // activation quantize
+constexpr int kDqBlock = 512;                    // activation dequantize (unroll chosen per launch)
+constexpr int kGqBlock = 256, kGqUnroll = 1;     // gradient quantize and fp32-addend accumulate
+constexpr int kGbBlock = 128, kGbUnroll = 2;     // accumulate, bf16 addend
+constexpr int kGdBlock = 512, kGdUnroll = 2;     // gradient dequantize
+constexpr int kSiBlock = 256, kSiUnroll = 2;     // SiLU & Multiply recompute
+// Occupancy caps: dynamic LDS (bytes per workgroup, never touched by the kernel) that limits
+// how many workgroups share a compute unit's 160 KB.  Measured per kernel: kernels that read
+// or write several streams at once run faster with fewer wavefronts in flight than the
+// registers allow; single-stream kernels have no cap.
+constexpr size_t kCapGa = 26 * 1024;    // accumulate, fp32 addend: 6 workgroups of 256
+constexpr size_t kCapSf = 20 * 1024;    // SiLU & Multiply forward + quantize: 8 workgroups of 128
+constexpr size_t kCapLdq = 48 * 1024;   // layer dequantize: 3 workgroups of 512
+constexpr size_t kCapDq8 = 48 * 1024;   // dequantize of 8-bit codes, tensors beyond one round: 3 of 512
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
 constexpr u32 kAmaxMinBits = 0x0D800000u;   // 2^-100: groups below it are stored as zeros
 constexpr u32 kInfBits = 0x7F800000u;       // magnitudes from here up are Inf or NaN
@@ -377,7 +282,7 @@ __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bi
         for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
         st<NTS>((u32x2*)codes + vi, u32x2{keep ? p0 : 0u, keep ? p1 : 0u});
     }
-    if ((vi & (LANES - 1)) == 0) st<NTS && AGOQ_SCALE_NT>(scales + vi / LANES, scale);
+    if ((vi & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
 }
 
 // The stored codes of the 8 elements a lane owns, as loaded.  4/5/6-bit: lo = the nibble
@@ -508,9 +413,40 @@ inline int check_common(int64_t numel, int group)
     return AGOQ_OK;
 }
 
-inline int launch_status()
+// Enqueue one kernel and report THIS launch's status: the return value of the launch call
+// itself.  An error that an earlier, unrelated HIP call of the caller left behind in the
+// runtime's per-thread state is neither reported as this call's nor cleared.
+template <typename... Params, typename... Args>
+inline int launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                  Args... args)
 {
-    return hipGetLastError() == hipSuccess ? AGOQ_OK : AGOQ_ERR_HIP;
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<std::remove_cv_t<Params>...> held(static_cast<std::remove_cv_t<Params>>(args)...);
+    return std::apply(
+        [&](auto&... value) {
+            void* slots[] = {static_cast<void*>(&value)...};
+            return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, slots, lds_bytes,
+                                   stream) == hipSuccess
+                       ? AGOQ_OK
+                       : AGOQ_ERR_HIP;
+        },
+        held);
+}
+
+// Calls f(std::integral_constant<int, BITS>, std::integral_constant<int, GROUP>) for the
+// run-time pair (bits in {4, 5, 6, 8} and group in {64, 128}, already validated).
+template <typename F>
+inline int dispatch_bits_group(int bits, int group, F&& f)
+{
+    auto with_group = [&](auto b) {
+        return group == 128 ? f(b, std::integral_constant<int, 128>{}) : f(b, std::integral_constant<int, 64>{});
+    };
+    switch (bits) {
+    case 4: return with_group(std::integral_constant<int, 4>{});
+    case 5: return with_group(std::integral_constant<int, 5>{});
+    case 6: return with_group(std::integral_constant<int, 6>{});
+    default: return with_group(std::integral_constant<int, 8>{});
+    }
 }
 
 inline unsigned blocks_for(int64_t items, int per_block)

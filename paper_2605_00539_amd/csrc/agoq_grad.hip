@@ -12,15 +12,15 @@ namespace {
 // each load instruction reads whole 256-byte runs.
 // ---------------------------------------------------------------------------
 template <int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* __restrict__ g,
+__global__ __launch_bounds__(kGqBlock) void grad_quant_kernel(const f32x4* __restrict__ g,
                                                             int64_t n_groups,
                                                             u32* __restrict__ codes,
                                                             float* __restrict__ scales)
 {
     constexpr int VPL = GROUP / 64;   // vectors per lane: 1 (group 64) or 2 (group 128)
     constexpr int VPG = GROUP / 4;    // vectors per group
-    constexpr int kBlock = AGOQ_GQ_BLOCK;
-    constexpr bool NTL = AGOQ_GQ_NTL, NTS = AGOQ_GQ_NTS;
+    constexpr int kBlock = kGqBlock;
+    constexpr bool NTL = true, NTS = true;
     const int lane16 = threadIdx.x & 15;
     const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_quant_kernel(const f32x4* 
                 if (!keep) w = 0;   // dead group: no signed zeros; non-finite group: no codes
                 st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
             }
-            if (lane16 == 0) st<NTS && AGOQ_SCALE_NT>(scales + grp, scale);
+            if (lane16 == 0) st<NTS>(scales + grp, scale);
         }
     }
 }
@@ -81,8 +81,8 @@ __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi
         for (int d = 0; d < 4; ++d)
             w[d] = encode4_bytes<FP>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv);
         if (!keep) w = u32x4{0, 0, 0, 0};   // dead group: no signed zeros; non-finite: no codes
-        st<AGOQ_RD_NTS>(out_codes + vi, w);
-        if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_RD_NTS && AGOQ_SCALE_NT>(out_scales + vi / LANES, scale);
+        st<true>(out_codes + vi, w);
+        if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
     }
 }
 
@@ -98,12 +98,10 @@ __device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, fl
     }
 }
 
-// K known at compile time (4, 8, 16): RU 16-byte vectors per lane, all RU*K code loads and
-// scale loads of the lane issued before the first is needed, then one vector after the
-// other is summed, requantized and stored.
-#ifndef AGOQ_RD_PRIO_FROM_K     // chunk count from which the loads are issued at raised priority; 0 = never
-#define AGOQ_RD_PRIO_FROM_K 16
-#endif
+// K known at compile time: RU 16-byte vectors per lane, all RU*K code loads and scale loads
+// of the lane issued before the first is needed, then one vector after the other is summed,
+// requantized and stored.
+constexpr int kReducePrioFromK = 16;   // chunk count from which the loads are issued at raised priority
 template <int GROUP, int KT, bool FP, int BLOCK, int RU>
 __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
                                                      int64_t stride_codes,
@@ -113,14 +111,13 @@ __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __rest
                                                      float* __restrict__ out_scales)
 {
     constexpr int LANES = GROUP / 16;
-    constexpr bool NTC = AGOQ_RD_NTC, NTSC = AGOQ_RD_NTSC;
     const int64_t base = (int64_t)blockIdx.x * (BLOCK * RU) + threadIdx.x;
     u32x4 c[RU][KT];
     float s[RU][KT];
     // With 16 chunks and two vectors per lane a wavefront issues 64 loads; at raised priority
     // it issues them in one go instead of taking turns with the wavefront that is summing
     // (measured: +4 % at K = 16, nothing at K = 8, -1 % on the one-vector shape).
-    constexpr bool kLoadsFirst = AGOQ_RD_PRIO_FROM_K > 0 && RU > 1 && KT >= AGOQ_RD_PRIO_FROM_K;
+    constexpr bool kLoadsFirst = RU > 1 && KT >= kReducePrioFromK;
     if (kLoadsFirst) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
@@ -128,8 +125,8 @@ __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __rest
         const int64_t vc = vi < n_vec ? vi : 0;   // out-of-range lanes read vector 0, store nothing
 #pragma unroll
         for (int k = 0; k < KT; ++k) {
-            c[u][k] = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
-            s[u][k] = ld<NTSC>(in_scales + (int64_t)k * stride_scales + vc / LANES);
+            c[u][k] = ld<true>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
+            s[u][k] = ld<true>(in_scales + (int64_t)k * stride_scales + vc / LANES);
         }
     }
     if (kLoadsFirst) {
@@ -159,120 +156,132 @@ __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __rest
     }
 }
 
-// Any other K (1..64): chunks four at a time, then the rest.
+// Any K (1..64) at run time: chunks k .. k+N-1 of the lane's vector, loads first, then the
+// N terms in chunk order.
+template <int N, bool FP, int LANES>
+__device__ __forceinline__ void reduce_batch(float (&acc)[16], const int8_t* __restrict__ in_codes,
+                                             int64_t stride_codes, const float* __restrict__ in_scales,
+                                             int64_t stride_scales, int k, int64_t vc)
+{
+    u32x4 c[N];
+    float s[N];
+#pragma unroll
+    for (int t = 0; t < N; ++t) {
+        c[t] = ld<true>((const u32x4*)(in_codes + (int64_t)(k + t) * stride_codes) + vc);
+        s[t] = ld<true>(in_scales + (int64_t)(k + t) * stride_scales + vc / LANES);
+    }
+#pragma unroll
+    for (int t = 0; t < N; ++t) reduce_term<FP>(acc, c[t], s[t]);
+}
+
+// Four chunks at a time, then the remaining one to three together (one at a time they would
+// each wait a full memory latency).
+constexpr int kAnyKBlock = 512;
 template <int GROUP, bool FP>
-__global__ __launch_bounds__(AGOQ_RD_BLOCK) void grad_reduce_anyk_kernel(
+__global__ __launch_bounds__(kAnyKBlock) void grad_reduce_anyk_kernel(
     const int8_t* __restrict__ in_codes, int64_t stride_codes, const float* __restrict__ in_scales,
     int64_t stride_scales, int K, int64_t n_vec, u32x4* __restrict__ out_codes,
     float* __restrict__ out_scales)
 {
     constexpr int LANES = GROUP / 16;
-    constexpr bool NTC = AGOQ_RD_NTC, NTSC = AGOQ_RD_NTSC;
-    const int64_t vi = (int64_t)blockIdx.x * AGOQ_RD_BLOCK + threadIdx.x;
+    const int64_t vi = (int64_t)blockIdx.x * kAnyKBlock + threadIdx.x;
     const bool valid = vi < n_vec;
     const int64_t vc = valid ? vi : 0;      // out-of-range lanes read vector 0, store nothing
-    const int64_t grp = vc / LANES;
     float acc[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
     int k = 0;
-    for (; k + 4 <= K; k += 4) {
-        u32x4 c[4];
-        float s[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            c[t] = ld<NTC>((const u32x4*)(in_codes + (int64_t)(k + t) * stride_codes) + vc);
-            s[t] = ld<NTSC>(in_scales + (int64_t)(k + t) * stride_scales + grp);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) reduce_term<FP>(acc, c[t], s[t]);
-    }
-    for (; k < K; ++k) {
-        const u32x4 c = ld<NTC>((const u32x4*)(in_codes + (int64_t)k * stride_codes) + vc);
-        const float s = ld<NTSC>(in_scales + (int64_t)k * stride_scales + grp);
-        reduce_term<FP>(acc, c, s);
+    for (; k + 4 <= K; k += 4)
+        reduce_batch<4, FP, LANES>(acc, in_codes, stride_codes, in_scales, stride_scales, k, vc);
+    switch (K - k) {
+    case 3: reduce_batch<3, FP, LANES>(acc, in_codes, stride_codes, in_scales, stride_scales, k, vc); break;
+    case 2: reduce_batch<2, FP, LANES>(acc, in_codes, stride_codes, in_scales, stride_scales, k, vc); break;
+    case 1: reduce_batch<1, FP, LANES>(acc, in_codes, stride_codes, in_scales, stride_scales, k, vc); break;
+    default: break;
     }
     reduce_finish<GROUP, FP>(acc, vi, valid, out_codes, out_scales);
 }
 
-// Launch of the reduce for either code book (arguments already checked).
-// Measured on K = 8 and 16 streams of 7M to 218M elements: the kernel is fastest with
-// FEWER wavefronts in flight than the registers allow -- two workgroups per compute unit
-// (K = 8 on 218M elements: 6.5 TB/s against 5.8 at full occupancy) -- presumably because
-// every resident wavefront keeps K DRAM pages open.  The cap is a dynamic LDS allocation
-// that no kernel touches: 64 KB per workgroup lets two share a compute unit's 160 KB.
-// From 40M elements on the two workgroups are of 256 lanes with two vectors per lane, below
-// that of 512 lanes with one (+2 % at 27M elements, +10 % at 7M, -6 % at 218M).
+// Launch of the reduce for either code book (arguments already checked).  Measured on
+// 13M to 218M elements per chunk, K = 1..64:
+//   * Large tensors (from 40M elements) with a chunk count that has a compile-time kernel
+//     (5, 6, 7, 8, 12, 16) are fastest with FEWER wavefronts in flight than the registers
+//     allow -- two workgroups of 256 lanes per compute unit, two vectors per lane (K = 8 on
+//     218M elements: 6.5 TB/s against 5.8 at full occupancy) -- presumably because every
+//     resident wavefront keeps K DRAM pages open.  The cap is a dynamic LDS allocation that no
+//     kernel touches: 64 KB per workgroup lets two share a compute unit's 160 KB.
+//   * K = 8 below that size: the same cap, workgroups of 512 lanes with one vector each.
+//   * K = 1, 2: too few loads per vector to fill the memory pipes under a cap; two vectors
+//     per lane at full occupancy.
+//   * K = 3, 4, 5 below that size: compile-time kernels at full occupancy, one vector per
+//     lane (1-3 % ahead of the run-time-K kernel on 13M and 27M elements).
+//   * Everything else runs the run-time-K kernel at full occupancy: 73-77 % of peak for
+//     K = 6..64 on a 27M-element shard, 76-81 % for K = 3, 4 on 218M elements (where the
+//     capped compile-time kernels for K = 4 measured 76 %).
 constexpr size_t kTwoPerCuLds = 64 * 1024;
 constexpr int64_t kReduceTwoVectorsFrom = 2500000;    // 16-element vectors
-template <bool FP>
-int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_scales,
-                  int64_t stride_scales, int K, int64_t n_vec, int group, u32x4* oc,
-                  float* out_scales, hipStream_t st)
+struct ReduceArgs {
+    const int8_t* in_codes;
+    int64_t stride_codes;
+    const float* in_scales;
+    int64_t stride_scales;
+    int K;
+    int64_t n_vec;
+    u32x4* out_codes;
+    float* out_scales;
+    hipStream_t st;
+};
+
+template <int GROUP, int KT, bool FP, int BLOCK, int RU>
+int launch_reduce_kt(const ReduceArgs& a, size_t lds)
 {
-    const bool two = n_vec >= kReduceTwoVectorsFrom;
-#ifndef AGOQ_RD1_BLOCK         // the small-tensor shape of the compile-time-K reduce
-#define AGOQ_RD1_BLOCK 512
-#endif
-#ifndef AGOQ_RD1_RU
-#define AGOQ_RD1_RU 1
-#endif
-#ifndef AGOQ_RD1_CAP_KB
-#define AGOQ_RD1_CAP_KB 64
-#endif
-#ifndef AGOQ_RD2_BLOCK         // the large-tensor shape of the compile-time-K reduce
-#define AGOQ_RD2_BLOCK 256
-#endif
-#ifndef AGOQ_RD2_RU
-#define AGOQ_RD2_RU 2
-#endif
-#ifndef AGOQ_RD2_CAP_KB
-#define AGOQ_RD2_CAP_KB 64
-#endif
-#define AGOQ_LAUNCH_REDUCE(G, KT)                                                               \
-    if (two)                                                                                    \
-        grad_reduce_kernel<G, KT, FP, AGOQ_RD2_BLOCK, AGOQ_RD2_RU><<<dim3(blocks_for(n_vec, AGOQ_RD2_BLOCK * AGOQ_RD2_RU)), dim3(AGOQ_RD2_BLOCK), (size_t)AGOQ_RD2_CAP_KB * 1024, st>>>( \
-            in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales);           \
-    else                                                                                        \
-        grad_reduce_kernel<G, KT, FP, AGOQ_RD1_BLOCK, AGOQ_RD1_RU><<<dim3(blocks_for(n_vec, AGOQ_RD1_BLOCK * AGOQ_RD1_RU)), dim3(AGOQ_RD1_BLOCK), (size_t)AGOQ_RD1_CAP_KB * 1024, st>>>( \
-            in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales)
-#ifndef AGOQ_RD_SMALLK_BLOCK
-#define AGOQ_RD_SMALLK_BLOCK 256
-#endif
-#ifndef AGOQ_RD_SMALLK_RU
-#define AGOQ_RD_SMALLK_RU 2
-#endif
-#ifndef AGOQ_RD_SMALLK_CAP_KB
-#define AGOQ_RD_SMALLK_CAP_KB 0
-#endif
-    // K = 1, 2 (and 3 in the run-time-K kernel): too few loads per vector to fill the memory
-    // pipes under a cap; two vectors per lane and full occupancy instead (K = 1: 5.5 TB/s
-    // against 3.9 capped, K = 2: 5.8 against 4.5, K = 3: 6.1 against 4.8)
-#define AGOQ_LAUNCH_REDUCE_SMALLK(G, KT)                                                        \
-    grad_reduce_kernel<G, KT, FP, AGOQ_RD_SMALLK_BLOCK, AGOQ_RD_SMALLK_RU>                      \
-        <<<dim3(blocks_for(n_vec, AGOQ_RD_SMALLK_BLOCK * AGOQ_RD_SMALLK_RU)), dim3(AGOQ_RD_SMALLK_BLOCK), (size_t)AGOQ_RD_SMALLK_CAP_KB * 1024, st>>>( \
-            in_codes, stride_codes, in_scales, stride_scales, n_vec, oc, out_scales)
-#define AGOQ_LAUNCH_REDUCE_G(G)                                                                 \
-    switch (K) {                                                                                \
-    case 1: AGOQ_LAUNCH_REDUCE_SMALLK(G, 1); break;                                             \
-    case 2: AGOQ_LAUNCH_REDUCE_SMALLK(G, 2); break;                                             \
-    case 4: AGOQ_LAUNCH_REDUCE(G, 4); break;                                                    \
-    case 8: AGOQ_LAUNCH_REDUCE(G, 8); break;                                                    \
-    case 16: AGOQ_LAUNCH_REDUCE(G, 16); break;                                                  \
-    default:                                                                                    \
-        grad_reduce_anyk_kernel<G, FP><<<dim3(blocks_for(n_vec, AGOQ_RD_BLOCK)), dim3(AGOQ_RD_BLOCK), K < 4 ? 0 : kTwoPerCuLds, st>>>( \
-            in_codes, stride_codes, in_scales, stride_scales, K, n_vec, oc, out_scales);        \
-        break;                                                                                  \
+    return launch(grad_reduce_kernel<GROUP, KT, FP, BLOCK, RU>, dim3(blocks_for(a.n_vec, BLOCK * RU)),
+                  dim3(BLOCK), lds, a.st, a.in_codes, a.stride_codes, a.in_scales, a.stride_scales,
+                  a.n_vec, a.out_codes, a.out_scales);
+}
+
+template <int GROUP, bool FP>
+int launch_reduce_group(const ReduceArgs& a)
+{
+    const bool large = a.n_vec >= kReduceTwoVectorsFrom;
+    switch (a.K) {
+    case 1: return launch_reduce_kt<GROUP, 1, FP, 256, 2>(a, 0);
+    case 2: return launch_reduce_kt<GROUP, 2, FP, 256, 2>(a, 0);
+    case 8:
+        return large ? launch_reduce_kt<GROUP, 8, FP, 256, 2>(a, kTwoPerCuLds)
+                     : launch_reduce_kt<GROUP, 8, FP, 512, 1>(a, kTwoPerCuLds);
+    case 3: if (!large) return launch_reduce_kt<GROUP, 3, FP, 512, 1>(a, 0); break;
+    case 4: if (!large) return launch_reduce_kt<GROUP, 4, FP, 512, 1>(a, 0); break;
+    case 5:
+        return large ? launch_reduce_kt<GROUP, 5, FP, 256, 2>(a, kTwoPerCuLds)
+                     : launch_reduce_kt<GROUP, 5, FP, 512, 1>(a, 0);
+    case 6: if (large) return launch_reduce_kt<GROUP, 6, FP, 256, 2>(a, kTwoPerCuLds); break;
+    case 7: if (large) return launch_reduce_kt<GROUP, 7, FP, 256, 2>(a, kTwoPerCuLds); break;
+    case 12: if (large) return launch_reduce_kt<GROUP, 12, FP, 256, 2>(a, kTwoPerCuLds); break;
+    case 16: if (large) return launch_reduce_kt<GROUP, 16, FP, 256, 2>(a, kTwoPerCuLds); break;
+    default: break;
     }
-    if (group == 128) {
-        AGOQ_LAUNCH_REDUCE_G(128)
-    } else {
-        AGOQ_LAUNCH_REDUCE_G(64)
-    }
-#undef AGOQ_LAUNCH_REDUCE_G
-#undef AGOQ_LAUNCH_REDUCE_SMALLK
-#undef AGOQ_LAUNCH_REDUCE
-    return launch_status();
+    return launch(grad_reduce_anyk_kernel<GROUP, FP>, dim3(blocks_for(a.n_vec, kAnyKBlock)), dim3(kAnyKBlock),
+                  0, a.st, a.in_codes, a.stride_codes, a.in_scales, a.stride_scales, a.K, a.n_vec,
+                  a.out_codes, a.out_scales);
+}
+
+// Validation and launch shared by the int8 and E4M3 forms of the reduce.
+template <bool FP>
+int launch_reduce(const void* in_codes, int64_t chunk_stride_codes, const float* in_scales,
+                  int64_t chunk_stride_scales, int K, int64_t numel, int group, void* out_codes,
+                  float* out_scales, void* stream)
+{
+    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (K < 1 || K > 64) return AGOQ_ERR_K;
+    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
+    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
+        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
+        return AGOQ_ERR_ALIGN;
+    const ReduceArgs a{(const int8_t*)in_codes, chunk_stride_codes, in_scales, chunk_stride_scales, K,
+                       numel / 16, (u32x4*)out_codes, out_scales, (hipStream_t)stream};
+    return group == 128 ? launch_reduce_group<128, FP>(a) : launch_reduce_group<64, FP>(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -285,13 +294,13 @@ int launch_reduce(const int8_t* in_codes, int64_t stride_codes, const float* in_
 //   bf16 addend: lane layout of act_quant_kernel (8 elements per lane).
 // ---------------------------------------------------------------------------
 template <int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
+__global__ __launch_bounds__(kGqBlock) void grad_accumulate_f32_kernel(
     const u32* main_codes, const float* main_scales, const f32x4* __restrict__ g_new,
     int64_t n_groups, u32* out_codes, float* out_scales)
 {
     constexpr int VPL = GROUP / 64;
     constexpr int VPG = GROUP / 4;
-    constexpr int kBlock = AGOQ_GQ_BLOCK;
+    constexpr int kBlock = kGqBlock;
     const int lane16 = threadIdx.x & 15;
     const int64_t slot = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
@@ -337,18 +346,18 @@ __global__ __launch_bounds__(AGOQ_GQ_BLOCK) void grad_accumulate_f32_kernel(
                 if (!keep) w = 0;   // dead group: no signed zeros; non-finite group: no codes
                 st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
             }
-            if (lane16 == 0) st<AGOQ_SCALE_NT>(out_scales + grp, scale);
+            if (lane16 == 0) st<true>(out_scales + grp, scale);
         }
     }
 }
 
 template <int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_GB_BLOCK) void grad_accumulate_bf16_kernel(
+__global__ __launch_bounds__(kGbBlock) void grad_accumulate_bf16_kernel(
     const u32x2* main_codes, const float* main_scales, const u32x4* __restrict__ g_new,
     int64_t n_vec, u32x2* out_codes, float* out_scales)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = AGOQ_GB_BLOCK;
+    constexpr int kBlock = kGbBlock;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
 
     // (Measured: this kernel is fastest as first written, each vector's three loads under
@@ -391,7 +400,7 @@ __global__ __launch_bounds__(AGOQ_GB_BLOCK) void grad_accumulate_bf16_kernel(
             u32 p1 = encode4_bytes<FP>(acc[4], acc[5], acc[6], acc[7], inv);
             if (!keep) p0 = p1 = 0;   // dead group: no signed zeros; non-finite group: no codes
             st<true>(out_codes + vi, u32x2{p0, p1});
-            if ((threadIdx.x & (LANES - 1)) == 0) st<AGOQ_SCALE_NT>(out_scales + vi / LANES, scale);
+            if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
         }
     }
 }
@@ -401,13 +410,13 @@ __global__ __launch_bounds__(AGOQ_GB_BLOCK) void grad_accumulate_bf16_kernel(
 // One lane: 4 codes (one dword) -> one 16-byte store.
 // ---------------------------------------------------------------------------
 template <int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* __restrict__ codes,
+__global__ __launch_bounds__(kGdBlock) void grad_dequant_kernel(const u32* __restrict__ codes,
                                                                      const float* __restrict__ scales,
                                                                      int64_t n_vec,
                                                                      f32x4* __restrict__ out)
 {
     constexpr int LANES = GROUP / 4;      // lanes per group
-    constexpr int kBlock = AGOQ_GD_BLOCK;
+    constexpr int kBlock = kGdBlock;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
     // loads (unconditional: a lane past the end re-reads the last vector and stores nothing),
     // one point where all of them are waited for, then arithmetic and stores vector by vector
@@ -436,12 +445,47 @@ __global__ __launch_bounds__(AGOQ_GD_BLOCK) void grad_dequant_kernel(const u32* 
         decode4_bytes<FP>(c[u], q);
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[j] = __fmul_rn(q[j], s[u]);
-        if (vi < n_vec) st<AGOQ_GD_NTS>(out + vi, o);
+        if (vi < n_vec) st<true>(out + vi, o);
         if (UNROLL > 1) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// Validation and launch shared by the int8 and E4M3 forms of the local accumulation.
+// Validation and launch shared by the int8 and E4M3 forms of the gradient store.
+template <bool FP>
+int launch_grad_quant(const float* grad, int64_t numel, int group, void* codes, float* scales, void* stream)
+{
+    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
+    const int64_t n_groups = numel / group;
+    const dim3 grid(blocks_for(n_groups * 16, kGqBlock * kGqUnroll)), block(kGqBlock);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        return launch(grad_quant_kernel<128, kGqUnroll, FP>, grid, block, 0, st, (const f32x4*)grad, n_groups,
+                      (u32*)codes, scales);
+    return launch(grad_quant_kernel<64, kGqUnroll, FP>, grid, block, 0, st, (const f32x4*)grad, n_groups,
+                  (u32*)codes, scales);
+}
+
+// ... of the gradient dequantize.
+template <bool FP>
+int launch_grad_dequant(const void* codes, const float* scales, int64_t numel, int group, float* out,
+                        void* stream)
+{
+    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
+    if (int rc = check_common(numel, group)) return rc;
+    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
+    const int64_t n_vec = numel / 4;
+    const dim3 grid(blocks_for(n_vec, kGdBlock * kGdUnroll)), block(kGdBlock);
+    hipStream_t st = (hipStream_t)stream;
+    if (group == 128)
+        return launch(grad_dequant_kernel<128, kGdUnroll, FP>, grid, block, 0, st, (const u32*)codes, scales,
+                      n_vec, (f32x4*)out);
+    return launch(grad_dequant_kernel<64, kGdUnroll, FP>, grid, block, 0, st, (const u32*)codes, scales, n_vec,
+                  (f32x4*)out);
+}
+
+// ... of the local accumulation.
 template <bool FP>
 int launch_accumulate(const void* main_codes, const float* main_scales, const void* g_new,
                       int g_new_is_bf16, int64_t numel, int group, void* out_codes,
@@ -455,30 +499,24 @@ int launch_accumulate(const void* main_codes, const float* main_scales, const vo
     hipStream_t st = (hipStream_t)stream;
     if (g_new_is_bf16) {
         const int64_t n_vec = numel / 8;
-        constexpr int U = AGOQ_GB_UNROLL;
-        const dim3 grid(blocks_for(n_vec, AGOQ_GB_BLOCK * U)), block(AGOQ_GB_BLOCK);
+        const dim3 grid(blocks_for(n_vec, kGbBlock * kGbUnroll)), block(kGbBlock);
         if (group == 128)
-            grad_accumulate_bf16_kernel<128, U, FP><<<grid, block, kCapLds, st>>>(
-                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
-                (u32x2*)out_codes, out_scales);
-        else
-            grad_accumulate_bf16_kernel<64, U, FP><<<grid, block, kCapLds, st>>>(
-                (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
-                (u32x2*)out_codes, out_scales);
-    } else {
-        const int64_t n_groups = numel / group;
-        constexpr int U = AGOQ_GQ_UNROLL;
-        const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
-        if (group == 128)
-            grad_accumulate_f32_kernel<128, U, FP><<<grid, block, kCapGa, st>>>(
-                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
-                (u32*)out_codes, out_scales);
-        else
-            grad_accumulate_f32_kernel<64, U, FP><<<grid, block, kCapGa, st>>>(
-                (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups,
-                (u32*)out_codes, out_scales);
+            return launch(grad_accumulate_bf16_kernel<128, kGbUnroll, FP>, grid, block, 0, st,
+                          (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
+                          (u32x2*)out_codes, out_scales);
+        return launch(grad_accumulate_bf16_kernel<64, kGbUnroll, FP>, grid, block, 0, st,
+                      (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec, (u32x2*)out_codes,
+                      out_scales);
     }
-    return launch_status();
+    const int64_t n_groups = numel / group;
+    const dim3 grid(blocks_for(n_groups * 16, kGqBlock * kGqUnroll)), block(kGqBlock);
+    if (group == 128)
+        return launch(grad_accumulate_f32_kernel<128, kGqUnroll, FP>, grid, block, kCapGa, st,
+                      (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups, (u32*)out_codes,
+                      out_scales);
+    return launch(grad_accumulate_f32_kernel<64, kGqUnroll, FP>, grid, block, kCapGa, st,
+                  (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups, (u32*)out_codes,
+                  out_scales);
 }
 
 }  // namespace
@@ -488,20 +526,7 @@ extern "C" {
 int agoq_grad_quant(const float* grad, int64_t numel, int group, int8_t* codes, float* scales,
                     void* stream)
 {
-    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
-    const int64_t n_groups = numel / group;
-    constexpr int U = AGOQ_GQ_UNROLL;
-    const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
-    hipStream_t st = (hipStream_t)stream;
-    if (group == 128)
-        grad_quant_kernel<128, U><<<grid, block, kCapLds, st>>>((const f32x4*)grad, n_groups, (u32*)codes,
-                                                          scales);
-    else
-        grad_quant_kernel<64, U><<<grid, block, kCapLds, st>>>((const f32x4*)grad, n_groups, (u32*)codes,
-                                                         scales);
-    return launch_status();
+    return launch_grad_quant<false>(grad, numel, group, codes, scales, stream);
 }
 
 int agoq_grad_reduce_requant(const int8_t* in_codes, int64_t chunk_stride_codes,
@@ -509,16 +534,8 @@ int agoq_grad_reduce_requant(const int8_t* in_codes, int64_t chunk_stride_codes,
                              int64_t numel, int group, int8_t* out_codes, float* out_scales,
                              void* stream)
 {
-    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (K < 1 || K > 64) return AGOQ_ERR_K;
-    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
-    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
-        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
-        return AGOQ_ERR_ALIGN;
-    return launch_reduce<false>(in_codes, chunk_stride_codes, in_scales, chunk_stride_scales, K,
-                                numel / 16, group, (u32x4*)out_codes, out_scales,
-                                (hipStream_t)stream);
+    return launch_reduce<false>(in_codes, chunk_stride_codes, in_scales, chunk_stride_scales, K, numel,
+                                group, out_codes, out_scales, stream);
 }
 
 int agoq_grad_accumulate(const int8_t* main_codes, const float* main_scales, const void* g_new,
@@ -529,6 +546,27 @@ int agoq_grad_accumulate(const int8_t* main_codes, const float* main_scales, con
                                     out_codes, out_scales, stream);
 }
 
+int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, int group,
+                      float* out, void* stream)
+{
+    return launch_grad_dequant<false>(codes, scales, numel, group, out, stream);
+}
+
+int agoq_fp8_grad_quant(const float* grad, int64_t numel, int group, uint8_t* codes, float* scales,
+                        void* stream)
+{
+    return launch_grad_quant<true>(grad, numel, group, codes, scales, stream);
+}
+
+int agoq_fp8_grad_reduce_requant(const uint8_t* in_codes, int64_t chunk_stride_codes,
+                                 const float* in_scales, int64_t chunk_stride_scales, int K,
+                                 int64_t numel, int group, uint8_t* out_codes, float* out_scales,
+                                 void* stream)
+{
+    return launch_reduce<true>(in_codes, chunk_stride_codes, in_scales, chunk_stride_scales, K, numel,
+                               group, out_codes, out_scales, stream);
+}
+
 int agoq_fp8_grad_accumulate(const uint8_t* main_codes, const float* main_scales, const void* g_new,
                              int g_new_is_bf16, int64_t numel, int group, uint8_t* out_codes,
                              float* out_scales, void* stream)
@@ -537,78 +575,10 @@ int agoq_fp8_grad_accumulate(const uint8_t* main_codes, const float* main_scales
                                    out_codes, out_scales, stream);
 }
 
-int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, int group,
-                      float* out, void* stream)
-{
-    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
-    const int64_t n_vec = numel / 4;
-    constexpr int U = AGOQ_GD_UNROLL;
-    const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
-    hipStream_t st = (hipStream_t)stream;
-    if (group == 128)
-        grad_dequant_kernel<128, U><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
-                                                            (f32x4*)out);
-    else
-        grad_dequant_kernel<64, U><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
-                                                           (f32x4*)out);
-    return launch_status();
-}
-
-int agoq_fp8_grad_quant(const float* grad, int64_t numel, int group, uint8_t* codes, float* scales,
-                        void* stream)
-{
-    if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (misaligned(grad) || misaligned(codes) || misaligned(scales)) return AGOQ_ERR_ALIGN;
-    const int64_t n_groups = numel / group;
-    constexpr int U = AGOQ_GQ_UNROLL;
-    const dim3 grid(blocks_for(n_groups * 16, AGOQ_GQ_BLOCK * U)), block(AGOQ_GQ_BLOCK);
-    hipStream_t st = (hipStream_t)stream;
-    if (group == 128)
-        grad_quant_kernel<128, U, true><<<grid, block, kCapLds, st>>>((const f32x4*)grad, n_groups,
-                                                                (u32*)codes, scales);
-    else
-        grad_quant_kernel<64, U, true><<<grid, block, kCapLds, st>>>((const f32x4*)grad, n_groups,
-                                                               (u32*)codes, scales);
-    return launch_status();
-}
-
 int agoq_fp8_grad_dequant(const uint8_t* codes, const float* scales, int64_t numel, int group,
                           float* out, void* stream)
 {
-    if (!codes || !scales || !out) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (misaligned(codes) || misaligned(scales) || misaligned(out)) return AGOQ_ERR_ALIGN;
-    const int64_t n_vec = numel / 4;
-    constexpr int U = AGOQ_GD_UNROLL;
-    const dim3 grid(blocks_for(n_vec, AGOQ_GD_BLOCK * U)), block(AGOQ_GD_BLOCK);
-    hipStream_t st = (hipStream_t)stream;
-    if (group == 128)
-        grad_dequant_kernel<128, U, true><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
-                                                                  (f32x4*)out);
-    else
-        grad_dequant_kernel<64, U, true><<<grid, block, kCapGd, st>>>((const u32*)codes, scales, n_vec,
-                                                                 (f32x4*)out);
-    return launch_status();
-}
-
-int agoq_fp8_grad_reduce_requant(const uint8_t* in_codes, int64_t chunk_stride_codes,
-                                 const float* in_scales, int64_t chunk_stride_scales, int K,
-                                 int64_t numel, int group, uint8_t* out_codes, float* out_scales,
-                                 void* stream)
-{
-    if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
-    if (int rc = check_common(numel, group)) return rc;
-    if (K < 1 || K > 64) return AGOQ_ERR_K;
-    if (chunk_stride_codes < numel || chunk_stride_scales < numel / group) return AGOQ_ERR_SHAPE;
-    if (misaligned(in_codes) || misaligned(in_scales) || misaligned(out_codes) ||
-        misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
-        return AGOQ_ERR_ALIGN;
-    return launch_reduce<true>((const int8_t*)in_codes, chunk_stride_codes, in_scales,
-                               chunk_stride_scales, K, numel / 16, group, (u32x4*)out_codes,
-                               out_scales, (hipStream_t)stream);
+    return launch_grad_dequant<true>(codes, scales, numel, group, out, stream);
 }
 
 }  // extern "C"

@@ -98,6 +98,6 @@ const char* agoq_strerror(int status)
     }
 }
 
-int agoq_version(void) { return 102; }
+int agoq_version(void) { return 200; }
 
 }  // extern "C"

@@ -24,30 +24,15 @@ constexpr int norm_max_block(int vpt)
 {
     return (int)(kNormMaxCols / 8 / vpt) < kNormMaxBlock ? (int)(kNormMaxCols / 8 / vpt) : kNormMaxBlock;
 }
-#ifndef AGOQ_NORM_VPT          // column vectors per lane (doubled while a row needs > 1024 lanes)
-#define AGOQ_NORM_VPT 4
-#endif
-#ifndef AGOQ_NORM_DEPTH        // rows in flight beyond the one being reduced: 1 or 2
-#define AGOQ_NORM_DEPTH 2
-#endif
-#ifndef AGOQ_NORM_DEPTH56      // ... with 5- and 6-bit codes (three loads per vector)
-#define AGOQ_NORM_DEPTH56 1
-#endif
-#ifndef AGOQ_NORM_VPT8         // the same two for 8-bit codes, whose buffers are twice the size
-#define AGOQ_NORM_VPT8 2
-#endif
-#ifndef AGOQ_NORM_DEPTH8
-#define AGOQ_NORM_DEPTH8 2
-#endif
-#ifndef AGOQ_NORM_FWD_VPT      // the same two for the forward kernel
-#define AGOQ_NORM_FWD_VPT 2
-#endif
-#ifndef AGOQ_NORM_FWD_DEPTH
-#define AGOQ_NORM_FWD_DEPTH 2
-#endif
-#ifndef AGOQ_NORM_RESIDENT     // lanes per compute unit the grid is sized for
-#define AGOQ_NORM_RESIDENT 1024
-#endif
+// Launch shape of the row kernels (measured on [8192,4096] and [8192,14336] tensors).
+constexpr int kNormVpt = 4;         // column vectors per lane (doubled while a row needs > 1024 lanes)
+constexpr int kNormDepth = 2;       // rows in flight beyond the one being reduced: 1 or 2
+constexpr int kNormDepth56 = 1;     // ... with 5- and 6-bit codes (three loads per vector)
+constexpr int kNormVpt8 = 2;        // the same two for 8-bit codes, whose buffers are twice the size
+constexpr int kNormDepth8 = 2;
+constexpr int kNormFwdVpt = 2;      // the same two for the forward kernel
+constexpr int kNormFwdDepth = 2;
+constexpr int kNormResident = 1024; // lanes per compute unit the grid is sized for
 
 // Sum of the per-wavefront partial sums of a workgroup, in wavefront order.
 __device__ __forceinline__ float block_sum(float wave_total, float* wave_part)
@@ -115,7 +100,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     // Loads take no lane test (a lane past the end of the row re-reads the row's last vector
     // and uses scale 0, so it adds nothing to the row sum): a load under a branch would have
     // to be merged with the register's old value, which again waits for the data.
-    constexpr int kDepth = BITS == 8 ? AGOQ_NORM_DEPTH8 : BITS == 4 ? AGOQ_NORM_DEPTH : AGOQ_NORM_DEPTH56;
+    constexpr int kDepth = BITS == 8 ? kNormDepth8 : BITS == 4 ? kNormDepth : kNormDepth56;
     struct RowBuf {
         Codes8<BITS> c[VPT];
         float sc[VPT];
@@ -227,13 +212,13 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
 // SiLU & Multiply recompute: z = bf16(u' * g' * sigmoid(g')), elementwise over the two
 // stored tensors (which may have different code widths).
 template <int BITS_G, int BITS_U, int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_SI_BLOCK) void act_dequant_silu_mul_kernel(
+__global__ __launch_bounds__(kSiBlock) void act_dequant_silu_mul_kernel(
     const void* __restrict__ gate_codes, const float* __restrict__ gate_scales,
     const void* __restrict__ up_codes, const float* __restrict__ up_scales, int64_t n_vec,
     u32x4* __restrict__ z)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = AGOQ_SI_BLOCK;
+    constexpr int kBlock = kSiBlock;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
     // loads (unconditional: a lane past the end re-reads the last vector and stores nothing),
     // one point where all of them are waited for, then arithmetic and stores vector by vector
@@ -289,7 +274,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     float* __restrict__ r_out, void* __restrict__ codes, float* __restrict__ scales)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kDepth = AGOQ_NORM_FWD_DEPTH;
+    constexpr int kDepth = kNormFwdDepth;
     __shared__ float wave_part[2][kNormMaxBlock / 64];
     f32x4 g0[VPT], g1[VPT];
 #pragma unroll
@@ -406,13 +391,13 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
 // SiLU & Multiply forward + quantize(gate), quantize(up), elementwise.
 //   z = bf16(up * gate * sigmoid(gate))
 template <int BITS_G, int BITS_U, int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(AGOQ_AQ_BLOCK) void silu_mul_fwd_quant_kernel(
+__global__ __launch_bounds__(kAqBlock) void silu_mul_fwd_quant_kernel(
     const u32x4* __restrict__ gate, const u32x4* __restrict__ up, int64_t n_vec,
     u32x4* __restrict__ z, void* __restrict__ gate_codes, float* __restrict__ gate_scales,
     void* __restrict__ up_codes, float* __restrict__ up_scales)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = AGOQ_AQ_BLOCK;
+    constexpr int kBlock = kAqBlock;
     const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
     u32x4 gv[UNROLL], uv[UNROLL];
 #pragma unroll
@@ -460,17 +445,28 @@ inline void norm_launch_shape(int vecs_per_row, int preferred_vpt, int& vpt, int
 }
 
 // Workgroups of a row kernel that walks its rows: as many as are resident at once when
-// every compute unit holds AGOQ_NORM_RESIDENT lanes -- one workgroup per unit for wide
+// every compute unit holds kNormResident lanes -- one workgroup per unit for wide
 // rows (workgroups of six wavefronts or more) when two further rows are in flight
 // (measured +2-4 % on 14336-wide rows; with one row in flight it costs 9 %).
 inline unsigned norm_grid(int64_t rows, int threads, int depth)
 {
-    const int per_cu = (threads >= 384 && depth >= 2) ? 1 : AGOQ_NORM_RESIDENT / threads;
+    const int per_cu = (threads >= 384 && depth >= 2) ? 1 : kNormResident / threads;
     const int64_t resident = (int64_t)compute_units() * (per_cu > 0 ? per_cu : 1);
     return (unsigned)(rows < resident ? rows : resident);
 }
 
 
+
+// Calls f(std::integral_constant<int, VPT>) for vpt in {1, 2, 4}.
+template <typename F>
+int dispatch_vpt(int vpt, F&& f)
+{
+    switch (vpt) {
+    case 1: return f(std::integral_constant<int, 1>{});
+    case 2: return f(std::integral_constant<int, 2>{});
+    default: return f(std::integral_constant<int, 4>{});
+    }
+}
 
 int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, int64_t cols, int group,
                          int bits, bool fp, const float* gamma, float eps, void* y_bf16, float* r_out,
@@ -491,47 +487,29 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
     int vpt, threads;
-    norm_launch_shape(vecs_per_row, bits == 8 ? AGOQ_NORM_VPT8 : AGOQ_NORM_VPT, vpt, threads);
-    const int depth = bits == 8 ? AGOQ_NORM_DEPTH8 : bits == 4 ? AGOQ_NORM_DEPTH : AGOQ_NORM_DEPTH56;
+    norm_launch_shape(vecs_per_row, bits == 8 ? kNormVpt8 : kNormVpt, vpt, threads);
+    const int depth = bits == 8 ? kNormDepth8 : bits == 4 ? kNormDepth : kNormDepth56;
     const dim3 grid(norm_grid(rows, threads, depth)), block(threads);
     const bool pipe = vecs_per_row == vpt * threads && rows >= (int64_t)grid.x * kNormPipeRows;
-#define AGOQ_NORM_ARGS codes, scales, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out
-#define AGOQ_LAUNCH_NORM_V(B, G, V, F)                                                             \
-    if (pipe)                                                                                     \
-        act_dequant_rmsnorm_kernel<B, G, V, F, true><<<grid, block, kCapLds, st>>>(AGOQ_NORM_ARGS); \
-    else                                                                                          \
-        act_dequant_rmsnorm_kernel<B, G, V, F, false><<<grid, block, kCapLds, st>>>(AGOQ_NORM_ARGS);
-#define AGOQ_LAUNCH_NORM_F(B, G, F)                                                                \
-    switch (vpt) {                                                                                \
-    case 1: AGOQ_LAUNCH_NORM_V(B, G, 1, F) break;                                                 \
-    case 2: AGOQ_LAUNCH_NORM_V(B, G, 2, F) break;                                                 \
-    default: AGOQ_LAUNCH_NORM_V(B, G, 4, F) break;                                                \
-    }
-#define AGOQ_LAUNCH_NORM(B, G) AGOQ_LAUNCH_NORM_F(B, G, false)
-#define AGOQ_LAUNCH_NORM_FP(G) AGOQ_LAUNCH_NORM_F(4, G, true)
-    if (fp) {
-        if (group == 128) { AGOQ_LAUNCH_NORM_FP(128) } else { AGOQ_LAUNCH_NORM_FP(64) }
-    } else if (group == 128) {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_NORM(4, 128) break;
-        case 5: AGOQ_LAUNCH_NORM(5, 128) break;
-        case 6: AGOQ_LAUNCH_NORM(6, 128) break;
-        default: AGOQ_LAUNCH_NORM(8, 128) break;
+    auto go = [&](auto kernel) {
+        return launch(kernel, grid, block, 0, st, codes, scales, n_vec_total, rows, vecs_per_row, gm, eps,
+                      inv_cols, y, r_out);
+    };
+    return dispatch_vpt(vpt, [&](auto v) {
+        constexpr int V = decltype(v)::value;
+        if (fp) {
+            if (group == 128)
+                return pipe ? go(act_dequant_rmsnorm_kernel<4, 128, V, true, true>)
+                            : go(act_dequant_rmsnorm_kernel<4, 128, V, true, false>);
+            return pipe ? go(act_dequant_rmsnorm_kernel<4, 64, V, true, true>)
+                        : go(act_dequant_rmsnorm_kernel<4, 64, V, true, false>);
         }
-    } else {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_NORM(4, 64) break;
-        case 5: AGOQ_LAUNCH_NORM(5, 64) break;
-        case 6: AGOQ_LAUNCH_NORM(6, 64) break;
-        default: AGOQ_LAUNCH_NORM(8, 64) break;
-        }
-    }
-#undef AGOQ_LAUNCH_NORM_FP
-#undef AGOQ_LAUNCH_NORM
-#undef AGOQ_LAUNCH_NORM_F
-#undef AGOQ_LAUNCH_NORM_V
-#undef AGOQ_NORM_ARGS
-    return launch_status();
+        return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+            constexpr int B = decltype(b)::value, G = decltype(g)::value;
+            return pipe ? go(act_dequant_rmsnorm_kernel<B, G, V, false, true>)
+                        : go(act_dequant_rmsnorm_kernel<B, G, V, false, false>);
+        });
+    });
 }
 
 int dequant_silu_mul_impl(const void* gate_codes, const float* gate_scales, int gate_bits,
@@ -547,38 +525,22 @@ int dequant_silu_mul_impl(const void* gate_codes, const float* gate_scales, int 
         misaligned(up_scales) || misaligned(z_bf16))
         return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
-    constexpr int U = AGOQ_SI_UNROLL;
-    const dim3 grid(blocks_for(n_vec, AGOQ_SI_BLOCK * U)), block(AGOQ_SI_BLOCK);
+    constexpr int U = kSiUnroll;
+    const dim3 grid(blocks_for(n_vec, kSiBlock * U)), block(kSiBlock);
     hipStream_t st = (hipStream_t)stream;
     u32x4* z = (u32x4*)z_bf16;
-#define AGOQ_LAUNCH_SILU(BG, BU)                                                                  \
-    if (group == 128)                                                                             \
-        act_dequant_silu_mul_kernel<BG, BU, 128, U><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z); \
-    else                                                                                          \
-        act_dequant_silu_mul_kernel<BG, BU, 64, U><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
-#define AGOQ_SILU_UP(BG)                                                                          \
-    switch (up_bits) {                                                                            \
-    case 4: AGOQ_LAUNCH_SILU(BG, 4) break;                                                        \
-    case 5: AGOQ_LAUNCH_SILU(BG, 5) break;                                                        \
-    case 6: AGOQ_LAUNCH_SILU(BG, 6) break;                                                        \
-    default: AGOQ_LAUNCH_SILU(BG, 8) break;                                                       \
-    }
-    if (fp) {
-        if (group == 128)
-            act_dequant_silu_mul_kernel<4, 4, 128, U, true><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
-        else
-            act_dequant_silu_mul_kernel<4, 4, 64, U, true><<<grid, block, kCapSi, st>>>(gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
-    } else {
-        switch (gate_bits) {
-        case 4: AGOQ_SILU_UP(4) break;
-        case 5: AGOQ_SILU_UP(5) break;
-        case 6: AGOQ_SILU_UP(6) break;
-        default: AGOQ_SILU_UP(8) break;
-        }
-    }
-#undef AGOQ_SILU_UP
-#undef AGOQ_LAUNCH_SILU
-    return launch_status();
+    auto go = [&](auto kernel) {
+        return launch(kernel, grid, block, 0, st, gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
+    };
+    if (fp)
+        return group == 128 ? go(act_dequant_silu_mul_kernel<4, 4, 128, U, true>)
+                            : go(act_dequant_silu_mul_kernel<4, 4, 64, U, true>);
+    return dispatch_bits_group(gate_bits, group, [&](auto bg, auto g) {
+        // the group is the same for both tensors: the inner dispatch only resolves the up width
+        return dispatch_bits_group(up_bits, group, [&](auto bu, auto) {
+            return go(act_dequant_silu_mul_kernel<decltype(bg)::value, decltype(bu)::value, decltype(g)::value, U>);
+        });
+    });
 }
 
 int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const float* gamma, float eps,
@@ -598,50 +560,32 @@ int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const
     const int64_t n_vec_total = rows * vecs_per_row;
     const float inv_cols = 1.0f / (float)cols;
     int vpt, threads;
-    norm_launch_shape(vecs_per_row, AGOQ_NORM_FWD_VPT, vpt, threads);
-    const dim3 grid(norm_grid(rows, threads, AGOQ_NORM_FWD_DEPTH)), block(threads);
+    norm_launch_shape(vecs_per_row, kNormFwdVpt, vpt, threads);
+    const dim3 grid(norm_grid(rows, threads, kNormFwdDepth)), block(threads);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
     const bool pipe = vecs_per_row == vpt * threads && rows >= (int64_t)grid.x * kNormPipeRows;
-#define AGOQ_NORM_FWD_ARGS x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y, r_out, codes, scales
-#define AGOQ_LAUNCH_NORM_FWD_V(B, G, V, F)                                                         \
-    if (pipe)                                                                                     \
-        rmsnorm_fwd_quant_kernel<B, G, V, F, true><<<grid, block, kCapLds, st>>>(AGOQ_NORM_FWD_ARGS); \
-    else                                                                                          \
-        rmsnorm_fwd_quant_kernel<B, G, V, F, false><<<grid, block, kCapLds, st>>>(AGOQ_NORM_FWD_ARGS);
-#define AGOQ_LAUNCH_NORM_FWD_F(B, G, F)                                                            \
-    switch (vpt) {                                                                                \
-    case 1: AGOQ_LAUNCH_NORM_FWD_V(B, G, 1, F) break;                                             \
-    case 2: AGOQ_LAUNCH_NORM_FWD_V(B, G, 2, F) break;                                             \
-    default: AGOQ_LAUNCH_NORM_FWD_V(B, G, 4, F) break;                                            \
-    }
-#define AGOQ_LAUNCH_NORM_FWD(B, G) AGOQ_LAUNCH_NORM_FWD_F(B, G, false)
-#define AGOQ_LAUNCH_NORM_FWD_FP(G) AGOQ_LAUNCH_NORM_FWD_F(4, G, true)
-    if (fp) {
-        if (group == 128) { AGOQ_LAUNCH_NORM_FWD_FP(128) } else { AGOQ_LAUNCH_NORM_FWD_FP(64) }
-    } else if (group == 128) {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_NORM_FWD(4, 128) break;
-        case 5: AGOQ_LAUNCH_NORM_FWD(5, 128) break;
-        case 6: AGOQ_LAUNCH_NORM_FWD(6, 128) break;
-        default: AGOQ_LAUNCH_NORM_FWD(8, 128) break;
+    auto go = [&](auto kernel) {
+        return launch(kernel, grid, block, 0, st, x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y,
+                      r_out, codes, scales);
+    };
+    return dispatch_vpt(vpt, [&](auto v) {
+        constexpr int V = decltype(v)::value;
+        if (fp) {
+            if (group == 128)
+                return pipe ? go(rmsnorm_fwd_quant_kernel<4, 128, V, true, true>)
+                            : go(rmsnorm_fwd_quant_kernel<4, 128, V, true, false>);
+            return pipe ? go(rmsnorm_fwd_quant_kernel<4, 64, V, true, true>)
+                        : go(rmsnorm_fwd_quant_kernel<4, 64, V, true, false>);
         }
-    } else {
-        switch (bits) {
-        case 4: AGOQ_LAUNCH_NORM_FWD(4, 64) break;
-        case 5: AGOQ_LAUNCH_NORM_FWD(5, 64) break;
-        case 6: AGOQ_LAUNCH_NORM_FWD(6, 64) break;
-        default: AGOQ_LAUNCH_NORM_FWD(8, 64) break;
-        }
-    }
-#undef AGOQ_LAUNCH_NORM_FWD_FP
-#undef AGOQ_LAUNCH_NORM_FWD
-#undef AGOQ_LAUNCH_NORM_FWD_F
-#undef AGOQ_LAUNCH_NORM_FWD_V
-#undef AGOQ_NORM_FWD_ARGS
-    return launch_status();
+        return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+            constexpr int B = decltype(b)::value, G = decltype(g)::value;
+            return pipe ? go(rmsnorm_fwd_quant_kernel<B, G, V, false, true>)
+                        : go(rmsnorm_fwd_quant_kernel<B, G, V, false, false>);
+        });
+    });
 }
 
 int silu_mul_fwd_quant_impl(const void* gate_bf16, const void* up_bf16, int64_t numel, int group,
@@ -660,39 +604,23 @@ int silu_mul_fwd_quant_impl(const void* gate_bf16, const void* up_bf16, int64_t 
         return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
     constexpr int U = 2;
-    const dim3 grid(blocks_for(n_vec, AGOQ_AQ_BLOCK * U)), block(AGOQ_AQ_BLOCK);
+    const dim3 grid(blocks_for(n_vec, kAqBlock * U)), block(kAqBlock);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* g = (const u32x4*)gate_bf16;
     const u32x4* up = (const u32x4*)up_bf16;
     u32x4* z = (u32x4*)z_bf16;
-#define AGOQ_LAUNCH_SILU_FWD(BG, BU)                                                              \
-    if (group == 128)                                                                             \
-        silu_mul_fwd_quant_kernel<BG, BU, 128, U><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales); \
-    else                                                                                          \
-        silu_mul_fwd_quant_kernel<BG, BU, 64, U><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
-#define AGOQ_SILU_FWD_UP(BG)                                                                      \
-    switch (up_bits) {                                                                            \
-    case 4: AGOQ_LAUNCH_SILU_FWD(BG, 4) break;                                                    \
-    case 5: AGOQ_LAUNCH_SILU_FWD(BG, 5) break;                                                    \
-    case 6: AGOQ_LAUNCH_SILU_FWD(BG, 6) break;                                                    \
-    default: AGOQ_LAUNCH_SILU_FWD(BG, 8) break;                                                   \
-    }
-    if (fp) {
-        if (group == 128)
-            silu_mul_fwd_quant_kernel<4, 4, 128, U, true><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
-        else
-            silu_mul_fwd_quant_kernel<4, 4, 64, U, true><<<grid, block, kCapSf, st>>>(g, up, n_vec, z, gate_codes, gate_scales, up_codes, up_scales);
-    } else {
-        switch (gate_bits) {
-        case 4: AGOQ_SILU_FWD_UP(4) break;
-        case 5: AGOQ_SILU_FWD_UP(5) break;
-        case 6: AGOQ_SILU_FWD_UP(6) break;
-        default: AGOQ_SILU_FWD_UP(8) break;
-        }
-    }
-#undef AGOQ_SILU_FWD_UP
-#undef AGOQ_LAUNCH_SILU_FWD
-    return launch_status();
+    auto go = [&](auto kernel) {
+        return launch(kernel, grid, block, kCapSf, st, g, up, n_vec, z, gate_codes, gate_scales, up_codes,
+                      up_scales);
+    };
+    if (fp)
+        return group == 128 ? go(silu_mul_fwd_quant_kernel<4, 4, 128, U, true>)
+                            : go(silu_mul_fwd_quant_kernel<4, 4, 64, U, true>);
+    return dispatch_bits_group(gate_bits, group, [&](auto bg, auto gr) {
+        return dispatch_bits_group(up_bits, group, [&](auto bu, auto) {
+            return go(silu_mul_fwd_quant_kernel<decltype(bg)::value, decltype(bu)::value, decltype(gr)::value, U>);
+        });
+    });
 }
 
 }  // namespace

@@ -173,6 +173,36 @@ int main() {
     }
     // error paths: nothing launched
     if (agoq_act_quant(nullptr, 128, 128, 4, nullptr, nullptr, nullptr) != AGOQ_ERR_NULL) ++failures;
+    // An error that an earlier, unrelated HIP call of the caller left behind is neither reported
+    // as a library call's status nor cleared by it.  (An invalid device ordinal is refused on
+    // the host; nothing reaches the GPU.)
+    {
+        const int group = 128;
+        const int64_t n = (int64_t)group * 64;
+        std::vector<uint16_t> x(n);
+        for (auto& v : x) v = to_bf16_trunc(bell());
+        uint16_t* dx = dev_copy(x);
+        uint8_t* dc = nullptr;
+        float* ds = nullptr;
+        HIP_OK(hipMalloc(&dc, n / 2));
+        HIP_OK(hipMalloc(&ds, n / group * 4));
+        const bool refused = hipSetDevice(12345) != hipSuccess;     // leaves the error behind
+        const int rc = agoq_act_quant(dx, n, group, 4, dc, ds, stream);
+        const bool still_there = hipPeekAtLastError() != hipSuccess;
+        (void)hipGetLastError();                                     // the caller clears its own error
+        HIP_OK(hipStreamSynchronize(stream));
+        std::vector<uint8_t> c(n / 2), c_ref(n / 2);
+        std::vector<float> sc(n / group), sc_ref(n / group);
+        HIP_OK(hipMemcpy(c.data(), dc, c.size(), hipMemcpyDeviceToHost));
+        agoq_ref_act_quant(x.data(), n, group, 4, c_ref.data(), sc_ref.data());
+        // (whether the runtime itself keeps an error across later successful calls is its
+        // business: reported, not required)
+        const bool ok = refused && rc == AGOQ_OK && c == c_ref;
+        printf("a caller's earlier HIP error is not this call's (%s afterwards): %s\n",
+               still_there ? "still pending" : "gone", ok ? "match" : "MISMATCH");
+        failures += !ok;
+        HIP_OK(hipFree(dx)); HIP_OK(hipFree(dc)); HIP_OK(hipFree(ds));
+    }
     HIP_OK(hipStreamDestroy(stream));
     printf("%s\n", failures ? "FAILED" : "all C-ABI checks passed");
     return failures ? 1 : 0;

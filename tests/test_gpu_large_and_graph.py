@@ -176,4 +176,4 @@ def test_c_abi_from_a_torch_free_client():
     proc = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
     assert proc.returncode == 0, proc.stdout
     assert "all C-ABI checks passed" in proc.stdout
-    assert proc.stdout.count("match") == 11 and "MISMATCH" not in proc.stdout
+    assert proc.stdout.count("match") == 12 and "MISMATCH" not in proc.stdout

@@ -127,7 +127,7 @@ def test_descriptor_array_can_be_reused_and_freed(agoq, ref):
     bitmap = [4, 8]
     codes = [torch.zeros(x.numel() * b // 8, dtype=torch.uint8, device="cuda") for x, b in zip(xs, bitmap)]
     scales = [torch.zeros(x.numel() // 128, dtype=torch.float32, device="cuda") for x in xs]
-    slots = agoq.layer_slots(xs, bitmap, codes, scales)
+    slots = agoq.layer_slots(xs, bitmap, codes, scales, 128)
     for _ in range(3):
         agoq.act_quant_layer(xs, 128, bitmap, slots=slots)
     torch.cuda.synchronize()

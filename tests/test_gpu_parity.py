@@ -168,7 +168,7 @@ def test_gradient_quant_sizes(agoq, ref, group, n_groups):
 
 
 @pytest.mark.parametrize("group", [64, 128])
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 9, 16, 17, 64])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 16, 17, 63, 64])
 def test_reduce_requant_chunk_counts(agoq, ref, group, K):
     rng = np.random.default_rng(3000 + K)
     n_groups = 2 * 256 * 16 // group + 3          # two blocks and a ragged tail

@@ -50,13 +50,14 @@ def test_dequant_around_the_resident_grid_thresholds(agoq, ref, bits):
         del x, codes, scales, y
 
 
-@pytest.mark.parametrize("K", [4, 8, 16])
+@pytest.mark.parametrize("K", [4, 5, 6, 7, 8, 12, 16])
 @pytest.mark.parametrize("group", [64, 128])
 def test_reduce_around_the_two_vector_threshold(agoq, ref, K, group):
-    # the reduce takes two vectors per lane from 2,500,000 vectors of 16 elements on
+    # from 2,500,000 vectors of 16 elements on, the reduce takes two vectors per lane in a kernel
+    # compiled for the chunk count (K = 5, 6, 7, 8, 12, 16; K = 4 stays on the run-time-K kernel)
     edge = 2500000 * 16 // 2048 * 2048           # elements, rounded to whole groups
     rng = np.random.default_rng(1000 + K)
-    sizes = (edge - group, edge + 37 * group) if K == 16 else (edge - group, edge, edge + group, edge + 37 * group)
+    sizes = (edge - group, edge + 37 * group) if K >= 12 else (edge - group, edge, edge + group, edge + 37 * group)
     for numel in sizes:
         stride_c = numel + 16 * int(rng.integers(0, 5))
         stride_s = numel // group + int(rng.integers(0, 7))
