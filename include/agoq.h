@@ -322,6 +322,34 @@ int64_t agoq_layer_stored_bytes(int64_t tokens, int64_t hidden, int64_t ffn, int
 const char *agoq_strerror(int status);
 
 /*
+ * Stochastic rounding -- an optional variant of the four integer-grid quantizers above.
+ * The paper itself never uses it (its quantizers round to nearest); the variant exists for
+ * callers that want the stored value to be unbiased, e.g. when a gradient is re-quantized at
+ * every accumulation step.  Same arguments and layouts as the calls without the suffix, plus
+ * `seed`; scales are identical to theirs, only the codes differ:
+ *     code = max(floor(x * inv + u), -qmax),       u = B / 256
+ * where x * inv is the rounded binary32 product, the sum is one binary32 addition, and B is
+ * one byte of a 32-bit hash word shared by the four consecutive elements 4b .. 4b+3 of the
+ * tensor being written (byte 0, the least significant, belongs to element 4b):
+ *     key  = mix(seed ^ (high 32 bits of b) * 0x9E3779B9),   word = mix((low 32 bits of b) ^ key)
+ * with mix() the 32-bit finalizer of MurmurHash3 (h ^= h >> 16; h *= 0x85EBCA6B;
+ * h ^= h >> 13; h *= 0xC2B2AE35; h ^= h >> 16).  For the reduce and the accumulation the
+ * element index is that of the OUTPUT element.  A call is a pure function of its inputs and
+ * the seed: the same seed gives the same codes on every run and launch shape.  Dead and
+ * non-finite groups follow the rule of the nearest-rounding calls.  Integer grids only.
+ */
+int agoq_act_quant_sr(const void *x_bf16, int64_t numel, int group, int bits, uint32_t seed, void *codes,
+                      float *scales, void *stream);
+int agoq_grad_quant_sr(const float *grad, int64_t numel, int group, uint32_t seed, int8_t *codes,
+                       float *scales, void *stream);
+int agoq_grad_reduce_requant_sr(const int8_t *in_codes, int64_t chunk_stride_codes, const float *in_scales,
+                                int64_t chunk_stride_scales, int K, int64_t numel, int group,
+                                uint32_t seed, int8_t *out_codes, float *out_scales, void *stream);
+int agoq_grad_accumulate_sr(const int8_t *main_codes, const float *main_scales, const void *g_new,
+                            int g_new_is_bf16, int64_t numel, int group, uint32_t seed,
+                            int8_t *out_codes, float *out_scales, void *stream);
+
+/*
  * Measurement aid (no passage of the paper: this is not part of the method).  A streaming
  * kernel with the memory traffic of an encode or decode kernel and none of its arithmetic:
  * lane item i loads load_bytes bytes from src + i*load_bytes and stores store_bytes bytes to

@@ -54,6 +54,15 @@
  *   then dequantizes to a NaN (0 * NaN).  A NaN converts to bf16 as a NaN whose
  *   payload is not specified.  Pinned by tests/test_oracle_nonfinite_pins.py.
  *
+ *   Stochastic rounding (the *_sr functions): the paper never uses it; it is
+ *   the optional variant the task statement allows ("driven by a counter-based
+ *   hash").  Reading: code = clamp(floor(x*inv + u)), u = B/256 with B one byte
+ *   of a 32-bit hash of (seed, element index / 4); the hash is the 32-bit
+ *   finalizer of MurmurHash3 (A. Appleby, public domain) applied to the counter
+ *   xor a per-seed key.  Pinned by tests/test_oracle_sr_pins.py (published
+ *   hash vectors, u = 0 gives floor, grid values unchanged, |code - t| < 1,
+ *   the mean over many seeds, exact rational re-evaluation, byte statistics).
+ *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  * Parallelism is over groups only; a group is always handled by one thread
  * from start to end, so results do not depend on the thread count.
@@ -129,8 +138,56 @@ static int group_is_finite(const float *x, int G)
     return 1;
 }
 
-/* Quantize G fp32 values to integer codes in [-qmax, qmax]; returns scale. */
-static float quantize_group(const float *x, int G, int qmax, int *q)
+/*
+ * Stochastic rounding.  The random variate of element i under `seed` is one
+ * byte of a 32-bit word that four consecutive elements share:
+ *     block = i / 4                                   (64-bit)
+ *     key   = mix(seed ^ (high 32 bits of block) * 0x9E3779B9)
+ *     word  = mix((low 32 bits of block) ^ key)
+ *     B     = byte (i mod 4) of word, byte 0 the least significant
+ *     u     = B / 256                                 (exact in binary32)
+ * mix() is the 32-bit finalizer of MurmurHash3 (xor-shift 16, multiply by
+ * 0x85EBCA6B, xor-shift 13, multiply by 0xC2B2AE35, xor-shift 16).
+ */
+static uint32_t sr_mix(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+static uint32_t sr_word(uint32_t seed, uint64_t block)
+{
+    const uint32_t lo = (uint32_t)block;
+    const uint32_t hi = (uint32_t)(block >> 32);
+    const uint32_t key = sr_mix(seed ^ (hi * 0x9E3779B9u));
+    return sr_mix(lo ^ key);
+}
+
+static float sr_u(uint32_t seed, int64_t i)
+{
+    const uint32_t word = sr_word(seed, (uint64_t)i >> 2);
+    const uint32_t byte = (word >> (8 * (int)(i & 3))) & 0xFFu;
+    return (float)byte / 256.0f;
+}
+
+uint32_t agoq_ref_sr_word(uint32_t seed, uint64_t block) { return sr_word(seed, block); }
+float agoq_ref_sr_u(uint32_t seed, int64_t i) { return sr_u(seed, i); }
+
+/* How t = x * inv becomes an integer: to nearest (ties to even), or stochastically. */
+struct rounding {
+    int stochastic;
+    uint32_t seed;
+};
+static const struct rounding ROUND_NEAREST = {0, 0};
+
+/* Quantize G fp32 values to integer codes in [-qmax, qmax]; returns scale.
+   first_index is the tensor index of x[0] (the stochastic variate depends on it). */
+static float quantize_group(const float *x, int G, int qmax, int *q, struct rounding mode,
+                            int64_t first_index)
 {
     if (!group_is_finite(x, G)) { /* Inf or NaN anywhere: the whole group reads back as NaN */
         for (int j = 0; j < G; ++j)
@@ -153,7 +210,13 @@ static float quantize_group(const float *x, int G, int qmax, int *q)
     const float inv = fq / amax;
     for (int j = 0; j < G; ++j) {
         float t = x[j] * inv;
-        float r = rintf(t); /* default rounding mode: ties to even */
+        float r;
+        if (mode.stochastic) {
+            float shifted = t + sr_u(mode.seed, first_index + j); /* one binary32 addition */
+            r = floorf(shifted);
+        } else {
+            r = rintf(t); /* default rounding mode: ties to even */
+        }
         if (r > fq)
             r = fq;
         if (r < -fq)
@@ -234,9 +297,8 @@ static int check_shape(int64_t numel, int group, int bits)
 
 /* ---- activations -------------------------------------------------------- */
 
-/* x: numel bf16 bit patterns.  codes: numel*bits/8 bytes.  scales: numel/group. */
-int agoq_ref_act_quant(const uint16_t *x, int64_t numel, int group, int bits,
-                       uint8_t *codes, float *scales)
+static int act_quant_any(const uint16_t *x, int64_t numel, int group, int bits, struct rounding mode,
+                         uint8_t *codes, float *scales)
 {
     if (!x || !codes || !scales)
         return REF_ERR_NULL;
@@ -252,12 +314,27 @@ int agoq_ref_act_quant(const uint16_t *x, int64_t numel, int group, int bits,
         const uint16_t *xg = x + g * group;
         for (int j = 0; j < group; ++j)
             xf[j] = bf16_bits_to_f32(xg[j]);
-        scales[g] = quantize_group(xf, group, qmax, q);
+        scales[g] = quantize_group(xf, group, qmax, q, mode, g * group);
         /* a group's bytes in every plane belong to that group alone */
         for (int j = 0; j < group; ++j)
             put_code(codes, numel, g * group + j, bits, q[j]);
     }
     return REF_OK;
+}
+
+/* x: numel bf16 bit patterns.  codes: numel*bits/8 bytes.  scales: numel/group. */
+int agoq_ref_act_quant(const uint16_t *x, int64_t numel, int group, int bits,
+                       uint8_t *codes, float *scales)
+{
+    return act_quant_any(x, numel, group, bits, ROUND_NEAREST, codes, scales);
+}
+
+/* The same with stochastic rounding of the codes (scales are unchanged by the mode). */
+int agoq_ref_act_quant_sr(const uint16_t *x, int64_t numel, int group, int bits, uint32_t seed,
+                          uint8_t *codes, float *scales)
+{
+    const struct rounding mode = {1, seed};
+    return act_quant_any(x, numel, group, bits, mode, codes, scales);
 }
 
 int agoq_ref_act_dequant(const uint8_t *codes, const float *scales, int64_t numel,
@@ -405,8 +482,8 @@ int agoq_ref_silu_mul_fwd(const uint16_t *gate, const uint16_t *up, int64_t nume
 
 /* ---- gradients ---------------------------------------------------------- */
 
-int agoq_ref_grad_quant(const float *grad, int64_t numel, int group, int8_t *codes,
-                        float *scales)
+static int grad_quant_any(const float *grad, int64_t numel, int group, struct rounding mode,
+                          int8_t *codes, float *scales)
 {
     if (!grad || !codes || !scales)
         return REF_ERR_NULL;
@@ -417,11 +494,24 @@ int agoq_ref_grad_quant(const float *grad, int64_t numel, int group, int8_t *cod
 #pragma omp parallel for schedule(static)
     for (int64_t g = 0; g < n_groups; ++g) {
         int q[4096];
-        scales[g] = quantize_group(grad + g * group, group, 127, q);
+        scales[g] = quantize_group(grad + g * group, group, 127, q, mode, g * group);
         for (int j = 0; j < group; ++j)
             codes[g * group + j] = (int8_t)q[j];
     }
     return REF_OK;
+}
+
+int agoq_ref_grad_quant(const float *grad, int64_t numel, int group, int8_t *codes,
+                        float *scales)
+{
+    return grad_quant_any(grad, numel, group, ROUND_NEAREST, codes, scales);
+}
+
+int agoq_ref_grad_quant_sr(const float *grad, int64_t numel, int group, uint32_t seed,
+                           int8_t *codes, float *scales)
+{
+    const struct rounding mode = {1, seed};
+    return grad_quant_any(grad, numel, group, mode, codes, scales);
 }
 
 /* int8 codes + scales -> fp32 values (what an optimizer would read). */
@@ -446,10 +536,9 @@ int agoq_ref_grad_dequant(const int8_t *codes, const float *scales, int64_t nume
  * k*stride_codes (numel int8) and in_scales + k*stride_scales (numel/group
  * fp32).  Summation order is the chunk index, one fmaf per term.
  */
-int agoq_ref_grad_reduce_requant(const int8_t *in_codes, int64_t stride_codes,
-                                 const float *in_scales, int64_t stride_scales, int K,
-                                 int64_t numel, int group, int8_t *out_codes,
-                                 float *out_scales)
+static int grad_reduce_any(const int8_t *in_codes, int64_t stride_codes, const float *in_scales,
+                           int64_t stride_scales, int K, int64_t numel, int group,
+                           struct rounding mode, int8_t *out_codes, float *out_scales)
 {
     if (!in_codes || !in_scales || !out_codes || !out_scales)
         return REF_ERR_NULL;
@@ -474,11 +563,31 @@ int agoq_ref_grad_reduce_requant(const int8_t *in_codes, int64_t stride_codes,
             }
             acc[j] = a;
         }
-        out_scales[g] = quantize_group(acc, group, 127, q);
+        out_scales[g] = quantize_group(acc, group, 127, q, mode, g * group);
         for (int j = 0; j < group; ++j)
             out_codes[g * group + j] = (int8_t)q[j];
     }
     return REF_OK;
+}
+
+int agoq_ref_grad_reduce_requant(const int8_t *in_codes, int64_t stride_codes,
+                                 const float *in_scales, int64_t stride_scales, int K,
+                                 int64_t numel, int group, int8_t *out_codes,
+                                 float *out_scales)
+{
+    return grad_reduce_any(in_codes, stride_codes, in_scales, stride_scales, K, numel, group,
+                           ROUND_NEAREST, out_codes, out_scales);
+}
+
+/* The sums as above; the requantization rounds stochastically (variate of OUTPUT element i). */
+int agoq_ref_grad_reduce_requant_sr(const int8_t *in_codes, int64_t stride_codes,
+                                    const float *in_scales, int64_t stride_scales, int K,
+                                    int64_t numel, int group, uint32_t seed, int8_t *out_codes,
+                                    float *out_scales)
+{
+    const struct rounding mode = {1, seed};
+    return grad_reduce_any(in_codes, stride_codes, in_scales, stride_scales, K, numel, group, mode,
+                           out_codes, out_scales);
 }
 
 /*
@@ -518,9 +627,9 @@ int agoq_ref_grad_reduce_f64(const int8_t *in_codes, int64_t stride_codes,
  * acc = fmaf(code, scale, g_new)), and the sum is quantized back to 8 bits.
  * g_new is fp32 (new_is_bf16 = 0) or bf16 bit patterns (new_is_bf16 = 1).
  */
-int agoq_ref_grad_accumulate(const int8_t *main_codes, const float *main_scales,
-                             const void *g_new, int new_is_bf16, int64_t numel, int group,
-                             int8_t *out_codes, float *out_scales)
+static int grad_accumulate_any(const int8_t *main_codes, const float *main_scales, const void *g_new,
+                               int new_is_bf16, int64_t numel, int group, struct rounding mode,
+                               int8_t *out_codes, float *out_scales)
 {
     if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales)
         return REF_ERR_NULL;
@@ -539,11 +648,29 @@ int agoq_ref_grad_accumulate(const int8_t *main_codes, const float *main_scales,
                                     : ((const float *)g_new)[i];
             acc[j] = fmaf((float)main_codes[i], s, add);
         }
-        out_scales[g] = quantize_group(acc, group, 127, q);
+        out_scales[g] = quantize_group(acc, group, 127, q, mode, g * group);
         for (int j = 0; j < group; ++j)
             out_codes[g * group + j] = (int8_t)q[j];
     }
     return REF_OK;
+}
+
+int agoq_ref_grad_accumulate(const int8_t *main_codes, const float *main_scales,
+                             const void *g_new, int new_is_bf16, int64_t numel, int group,
+                             int8_t *out_codes, float *out_scales)
+{
+    return grad_accumulate_any(main_codes, main_scales, g_new, new_is_bf16, numel, group,
+                               ROUND_NEAREST, out_codes, out_scales);
+}
+
+/* The same with stochastic rounding of the stored sum (variate of element i). */
+int agoq_ref_grad_accumulate_sr(const int8_t *main_codes, const float *main_scales,
+                                const void *g_new, int new_is_bf16, int64_t numel, int group,
+                                uint32_t seed, int8_t *out_codes, float *out_scales)
+{
+    const struct rounding mode = {1, seed};
+    return grad_accumulate_any(main_codes, main_scales, g_new, new_is_bf16, numel, group, mode,
+                               out_codes, out_scales);
 }
 
 /* ======================================================================= */

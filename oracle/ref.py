@@ -15,6 +15,7 @@ __all__ = [
     "lib", "rmsnorm_fwd", "silu_mul_fwd", "fp4_act_quant", "fp4_act_dequant", "fp8_grad_quant", "fp8_grad_dequant",
     "fp8_grad_reduce_requant", "fp8_grad_accumulate", "e2m1_encode", "e2m1_decode", "e4m3_encode", "e4m3_decode", "act_quant", "act_dequant", "act_dequant_rmsnorm", "act_dequant_silu_mul", "grad_quant", "grad_dequant",
     "grad_reduce_requant", "grad_reduce_f64", "grad_accumulate", "dbca_bits",
+    "act_quant_sr", "grad_quant_sr", "grad_reduce_requant_sr", "grad_accumulate_sr", "sr_word", "sr_u",
     "dbca_stored_microbatches", "bf16_to_f32", "f32_to_bf16", "max_threads",
     "set_threads", "OracleError", "Oracle",
 ]
@@ -49,6 +50,15 @@ def _bind(path):
     L.agoq_ref_fp8_grad_dequant.argtypes = [_P, _P, _I64, _INT, _P]
     L.agoq_ref_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P]
     L.agoq_ref_fp8_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P]
+    _U32 = ctypes.c_uint32
+    L.agoq_ref_act_quant_sr.argtypes = [_P, _I64, _INT, _INT, _U32, _P, _P]
+    L.agoq_ref_grad_quant_sr.argtypes = [_P, _I64, _INT, _U32, _P, _P]
+    L.agoq_ref_grad_reduce_requant_sr.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _U32, _P, _P]
+    L.agoq_ref_grad_accumulate_sr.argtypes = [_P, _P, _P, _INT, _I64, _INT, _U32, _P, _P]
+    L.agoq_ref_sr_word.argtypes = [_U32, ctypes.c_uint64]
+    L.agoq_ref_sr_word.restype = _U32
+    L.agoq_ref_sr_u.argtypes = [_U32, _I64]
+    L.agoq_ref_sr_u.restype = ctypes.c_float
     for name in ("e2m1", "e4m3"):
         enc = getattr(L, "agoq_ref_%s_encode" % name)
         enc.argtypes = [ctypes.c_float]
@@ -113,6 +123,55 @@ class Oracle:
         scales = np.zeros(max(n // max(group, 1), 0), np.float32)
         _check(self.lib.agoq_ref_act_quant(_ptr(x), n, group, bits, _ptr(codes), _ptr(scales)))
         return codes, scales
+
+    # ---- stochastic rounding (optional variant; the paper never uses it) ----
+
+    def sr_word(self, seed, block):
+        return self.lib.agoq_ref_sr_word(int(seed) & 0xFFFFFFFF, int(block))
+
+    def sr_u(self, seed, index):
+        return self.lib.agoq_ref_sr_u(int(seed) & 0xFFFFFFFF, int(index))
+
+    def act_quant_sr(self, x_bf16_bits, group, bits, seed):
+        x = _c(x_bf16_bits, np.uint16).reshape(-1)
+        n = x.size
+        codes = np.zeros(max(n * bits // 8, 0), np.uint8)
+        scales = np.zeros(max(n // max(group, 1), 0), np.float32)
+        _check(self.lib.agoq_ref_act_quant_sr(_ptr(x), n, group, bits, int(seed) & 0xFFFFFFFF, _ptr(codes),
+                                              _ptr(scales)))
+        return codes, scales
+
+    def grad_quant_sr(self, g, group, seed):
+        g = _c(g, np.float32).reshape(-1)
+        codes = np.zeros(g.size, np.int8)
+        scales = np.zeros(g.size // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_grad_quant_sr(_ptr(g), g.size, group, int(seed) & 0xFFFFFFFF, _ptr(codes),
+                                               _ptr(scales)))
+        return codes, scales
+
+    def grad_reduce_requant_sr(self, in_codes, in_scales, numel, group, seed):
+        in_codes, in_scales = _chunks(in_codes, in_scales)
+        K = in_codes.shape[0]
+        out_codes = np.zeros(numel, np.int8)
+        out_scales = np.zeros(numel // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_grad_reduce_requant_sr(
+            _ptr(in_codes), in_codes.shape[1], _ptr(in_scales), in_scales.shape[1], K, numel, group,
+            int(seed) & 0xFFFFFFFF, _ptr(out_codes), _ptr(out_scales)))
+        return out_codes, out_scales
+
+    def grad_accumulate_sr(self, main_codes, main_scales, g_new, group, seed):
+        main_codes = _c(main_codes, np.int8).reshape(-1)
+        main_scales = _c(main_scales, np.float32).reshape(-1)
+        g_new = np.ascontiguousarray(g_new).reshape(-1)
+        if g_new.dtype not in (np.dtype(np.float32), np.dtype(np.uint16)):
+            raise TypeError("g_new must be float32 or uint16 (bf16 bits)")
+        n = main_codes.size
+        out_codes = np.zeros(n, np.int8)
+        out_scales = np.zeros(n // max(group, 1), np.float32)
+        _check(self.lib.agoq_ref_grad_accumulate_sr(
+            _ptr(main_codes), _ptr(main_scales), _ptr(g_new), 1 if g_new.dtype == np.uint16 else 0, n, group,
+            int(seed) & 0xFFFFFFFF, _ptr(out_codes), _ptr(out_scales)))
+        return out_codes, out_scales
 
     def act_dequant(self, codes, scales, numel, group, bits):
         codes = _c(codes, np.uint8).reshape(-1)
@@ -328,6 +387,12 @@ grad_dequant = _default.grad_dequant
 grad_reduce_requant = _default.grad_reduce_requant
 grad_reduce_f64 = _default.grad_reduce_f64
 grad_accumulate = _default.grad_accumulate
+act_quant_sr = _default.act_quant_sr
+grad_quant_sr = _default.grad_quant_sr
+grad_reduce_requant_sr = _default.grad_reduce_requant_sr
+grad_accumulate_sr = _default.grad_accumulate_sr
+sr_word = _default.sr_word
+sr_u = _default.sr_u
 dbca_bits = _default.dbca_bits
 dbca_stored_microbatches = _default.dbca_stored_microbatches
 bf16_to_f32 = _default.bf16_to_f32

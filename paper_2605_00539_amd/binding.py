@@ -64,6 +64,11 @@ def load_library():
     L.agoq_fp8_grad_reduce_requant.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_fp8_grad_accumulate.argtypes = [_P, _P, _P, _INT, _I64, _INT, _P, _P, _P]
     L.agoq_probe_stream.argtypes = [_P, _INT, _P, _INT, _I64, _P]
+    _U32 = ctypes.c_uint32
+    L.agoq_act_quant_sr.argtypes = [_P, _I64, _INT, _INT, _U32, _P, _P, _P]
+    L.agoq_grad_quant_sr.argtypes = [_P, _I64, _INT, _U32, _P, _P, _P]
+    L.agoq_grad_reduce_requant_sr.argtypes = [_P, _I64, _P, _I64, _INT, _I64, _INT, _U32, _P, _P, _P]
+    L.agoq_grad_accumulate_sr.argtypes = [_P, _P, _P, _INT, _I64, _INT, _U32, _P, _P, _P]
     L.agoq_codes_bytes.argtypes = [_I64, _INT]
     L.agoq_codes_bytes.restype = _I64
     L.agoq_num_groups.argtypes = [_I64, _INT]
@@ -149,8 +154,9 @@ def _raw(ptr):
 
 # ---- device entry points ------------------------------------------------------
 
-def act_quant(x, group, bits, codes=None, scales=None, stream=None):
-    """x: bf16 tensor on the GPU.  Returns (codes uint8 [numel*bits/8], scales float32 [numel/group])."""
+def act_quant(x, group, bits, codes=None, scales=None, stream=None, sr_seed=None):
+    """x: bf16 tensor on the GPU.  Returns (codes uint8 [numel*bits/8], scales float32 [numel/group]).
+    sr_seed: an integer selects the stochastic-rounding variant (agoq_act_quant_sr) under that seed."""
     import torch
     L = load_library()
     x = _dev(x, torch.bfloat16, "x")
@@ -164,8 +170,12 @@ def act_quant(x, group, bits, codes=None, scales=None, stream=None):
     _holds(codes, _code_bytes(n, bits), "codes")
     _holds(scales, _groups(n, group), "scales")
     with _on_device(x.device):
-        _check(L.agoq_act_quant(_raw(x.data_ptr()), n, group, bits, _raw(codes.data_ptr()),
-                                _raw(scales.data_ptr()), _stream(stream)))
+        if sr_seed is None:
+            _check(L.agoq_act_quant(_raw(x.data_ptr()), n, group, bits, _raw(codes.data_ptr()),
+                                    _raw(scales.data_ptr()), _stream(stream)))
+        else:
+            _check(L.agoq_act_quant_sr(_raw(x.data_ptr()), n, group, bits, int(sr_seed) & 0xFFFFFFFF,
+                                       _raw(codes.data_ptr()), _raw(scales.data_ptr()), _stream(stream)))
     return codes, scales
 
 
@@ -401,8 +411,9 @@ def silu_mul_fwd_quant(gate, up, group, gate_bits, up_bits, stream=None, fp4=Fal
     return z, gc, gs, uc, us
 
 
-def grad_quant(grad, group, codes=None, scales=None, stream=None):
-    """grad: fp32 tensor on the GPU.  Returns (codes int8 [numel], scales float32 [numel/group])."""
+def grad_quant(grad, group, codes=None, scales=None, stream=None, sr_seed=None):
+    """grad: fp32 tensor on the GPU.  Returns (codes int8 [numel], scales float32 [numel/group]).
+    sr_seed: an integer selects the stochastic-rounding variant under that seed."""
     import torch
     L = load_library()
     grad = _dev(grad, torch.float32, "grad")
@@ -416,13 +427,17 @@ def grad_quant(grad, group, codes=None, scales=None, stream=None):
     _holds(codes, n, "codes")
     _holds(scales, _groups(n, group), "scales")
     with _on_device(grad.device):
-        _check(L.agoq_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
-                                 _raw(scales.data_ptr()), _stream(stream)))
+        if sr_seed is None:
+            _check(L.agoq_grad_quant(_raw(grad.data_ptr()), n, group, _raw(codes.data_ptr()),
+                                     _raw(scales.data_ptr()), _stream(stream)))
+        else:
+            _check(L.agoq_grad_quant_sr(_raw(grad.data_ptr()), n, group, int(sr_seed) & 0xFFFFFFFF,
+                                        _raw(codes.data_ptr()), _raw(scales.data_ptr()), _stream(stream)))
     return codes, scales
 
 
 def grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_scales=None,
-                        stream=None):
+                        stream=None, sr_seed=None):
     """in_codes: int8 [K, stride_c]; in_scales: float32 [K, stride_s] (the receive buffer of the
     All-to-All, chunk k in row k).  Returns (codes int8 [numel], scales float32 [numel/group])."""
     import torch
@@ -442,15 +457,21 @@ def grad_reduce_requant(in_codes, in_scales, numel, group, out_codes=None, out_s
     _holds(out_codes, numel, "out_codes")
     _holds(out_scales, _groups(numel, group), "out_scales")
     with _on_device(in_codes.device):
-        _check(L.agoq_grad_reduce_requant(
-            _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
-            in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),
-            _raw(out_scales.data_ptr()), _stream(stream)))
+        if sr_seed is None:
+            _check(L.agoq_grad_reduce_requant(
+                _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
+                in_scales.shape[1], K, numel, group, _raw(out_codes.data_ptr()),
+                _raw(out_scales.data_ptr()), _stream(stream)))
+        else:
+            _check(L.agoq_grad_reduce_requant_sr(
+                _raw(in_codes.data_ptr()), in_codes.shape[1], _raw(in_scales.data_ptr()),
+                in_scales.shape[1], K, numel, group, int(sr_seed) & 0xFFFFFFFF,
+                _raw(out_codes.data_ptr()), _raw(out_scales.data_ptr()), _stream(stream)))
     return out_codes, out_scales
 
 
 def grad_accumulate(main_codes, main_scales, g_new, group, out_codes=None, out_scales=None,
-                    stream=None):
+                    stream=None, sr_seed=None):
     """main_codes int8 [numel], main_scales float32 [numel/group], g_new float32 or bfloat16
     [numel].  With out_codes/out_scales left None the stored gradient is updated in place."""
     import torch
@@ -473,10 +494,16 @@ def grad_accumulate(main_codes, main_scales, g_new, group, out_codes=None, out_s
     _holds(out_codes, n, "out_codes")
     _holds(out_scales, _groups(n, group), "out_scales")
     with _on_device(main_codes.device):
-        _check(L.agoq_grad_accumulate(
-            _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
-            1 if g_new.dtype == torch.bfloat16 else 0, n, group, _raw(out_codes.data_ptr()),
-            _raw(out_scales.data_ptr()), _stream(stream)))
+        if sr_seed is None:
+            _check(L.agoq_grad_accumulate(
+                _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
+                1 if g_new.dtype == torch.bfloat16 else 0, n, group, _raw(out_codes.data_ptr()),
+                _raw(out_scales.data_ptr()), _stream(stream)))
+        else:
+            _check(L.agoq_grad_accumulate_sr(
+                _raw(main_codes.data_ptr()), _raw(main_scales.data_ptr()), _raw(g_new.data_ptr()),
+                1 if g_new.dtype == torch.bfloat16 else 0, n, group, int(sr_seed) & 0xFFFFFFFF,
+                _raw(out_codes.data_ptr()), _raw(out_scales.data_ptr()), _stream(stream)))
     return out_codes, out_scales
 
 

@@ -20,10 +20,10 @@ namespace {
 // phases are gone).  Otherwise -- the one workgroup that straddles the end -- a lane past
 // the end re-reads the last vector, which is always in bounds, and its stores are masked;
 // lanes of one group are all inside or all outside.
-template <int BITS, int GROUP, int UNROLL, bool FP, bool FULL>
+template <int BITS, int GROUP, int UNROLL, bool FP, bool FULL, bool SR>
 __device__ __forceinline__ void act_quant_body(const u32x4* __restrict__ x, int64_t n_vec,
                                                void* __restrict__ codes, float* __restrict__ scales,
-                                               unsigned block)
+                                               unsigned block, u32 seed)
 {
     constexpr int LANES = GROUP / 8;
     constexpr int kBlock = kAqBlock;
@@ -44,27 +44,28 @@ __device__ __forceinline__ void act_quant_body(const u32x4* __restrict__ x, int6
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
         const int64_t vi = base + (int64_t)u * kBlock;
-        quantize_store8<BITS, GROUP, FP, NTS>(f[u], m[u], vi, n_vec, FULL || vi < n_vec, codes, scales);
+        quantize_store8<BITS, GROUP, FP, NTS, SR>(f[u], m[u], vi, n_vec, FULL || vi < n_vec, codes, scales, seed);
     }
 }
 
-template <int BITS, int GROUP, int UNROLL, bool FP>
+template <int BITS, int GROUP, int UNROLL, bool FP, bool SR = false>
 __device__ __forceinline__ void act_quant_tile(const u32x4* __restrict__ x, int64_t n_vec,
                                                void* __restrict__ codes, float* __restrict__ scales,
-                                               unsigned block)
+                                               unsigned block, u32 seed = 0)
 {
     if (((int64_t)block + 1) * (kAqBlock * UNROLL) <= n_vec)
-        act_quant_body<BITS, GROUP, UNROLL, FP, true>(x, n_vec, codes, scales, block);
+        act_quant_body<BITS, GROUP, UNROLL, FP, true, SR>(x, n_vec, codes, scales, block, seed);
     else
-        act_quant_body<BITS, GROUP, UNROLL, FP, false>(x, n_vec, codes, scales, block);
+        act_quant_body<BITS, GROUP, UNROLL, FP, false, SR>(x, n_vec, codes, scales, block, seed);
 }
 
-template <int BITS, int GROUP, int UNROLL, bool FP = false>
+// SR: the codes are rounded stochastically under `seed` (optional variant; else seed is unused).
+template <int BITS, int GROUP, int UNROLL, bool FP = false, bool SR = false>
 __global__ __launch_bounds__(kAqBlock) void act_quant_kernel(const u32x4* __restrict__ x,
                                                            int64_t n_vec, void* __restrict__ codes,
-                                                           float* __restrict__ scales)
+                                                           float* __restrict__ scales, u32 seed)
 {
-    act_quant_tile<BITS, GROUP, UNROLL, FP>(x, n_vec, codes, scales, blockIdx.x);
+    act_quant_tile<BITS, GROUP, UNROLL, FP, SR>(x, n_vec, codes, scales, blockIdx.x, seed);
 }
 
 // ---------------------------------------------------------------------------
@@ -247,8 +248,13 @@ int layer_args(const agoq_act_slot* slots, int count, int group, bool quantize, 
 
 extern "C" {
 
-int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void* codes,
-                   float* scales, void* stream)
+}  // extern "C"
+
+namespace {
+
+template <bool SR>
+int launch_act_quant(const void* x_bf16, int64_t numel, int group, int bits, u32 seed, void* codes,
+                     float* scales, void* stream)
 {
     if (!x_bf16 || !codes || !scales) return AGOQ_ERR_NULL;
     if (bits != 4 && bits != 5 && bits != 6 && bits != 8) return AGOQ_ERR_BITS;
@@ -257,9 +263,25 @@ int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void*
     const int64_t n_vec = numel / 8;
     const dim3 grid(blocks_for(n_vec, kAqBlock * kAqUnroll)), block(kAqBlock);
     return dispatch_bits_group(bits, group, [&](auto b, auto g) {
-        return launch(act_quant_kernel<decltype(b)::value, decltype(g)::value, kAqUnroll>, grid, block, 0,
-                      (hipStream_t)stream, (const u32x4*)x_bf16, n_vec, codes, scales);
+        return launch(act_quant_kernel<decltype(b)::value, decltype(g)::value, kAqUnroll, false, SR>, grid,
+                      block, 0, (hipStream_t)stream, (const u32x4*)x_bf16, n_vec, codes, scales, seed);
     });
+}
+
+}  // namespace
+
+extern "C" {
+
+int agoq_act_quant(const void* x_bf16, int64_t numel, int group, int bits, void* codes,
+                   float* scales, void* stream)
+{
+    return launch_act_quant<false>(x_bf16, numel, group, bits, 0, codes, scales, stream);
+}
+
+int agoq_act_quant_sr(const void* x_bf16, int64_t numel, int group, int bits, uint32_t seed, void* codes,
+                      float* scales, void* stream)
+{
+    return launch_act_quant<true>(x_bf16, numel, group, bits, seed, codes, scales, stream);
 }
 
 int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int group, int bits,
@@ -301,8 +323,8 @@ int agoq_fp4_act_quant(const void* x_bf16, int64_t numel, int group, void* codes
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     if (group == 128)
-        return launch(act_quant_kernel<4, 128, kAqUnroll, true>, grid, block, 0, st, x, n_vec, codes, scales);
-    return launch(act_quant_kernel<4, 64, kAqUnroll, true>, grid, block, 0, st, x, n_vec, codes, scales);
+        return launch(act_quant_kernel<4, 128, kAqUnroll, true>, grid, block, 0, st, x, n_vec, codes, scales, 0u);
+    return launch(act_quant_kernel<4, 64, kAqUnroll, true>, grid, block, 0, st, x, n_vec, codes, scales, 0u);
 }
 
 int agoq_fp4_act_dequant(const void* codes, const float* scales, int64_t numel, int group,

@@ -45,7 +45,7 @@ constexpr int kDqBlock = 512;                    // activation dequantize (unrol
 constexpr int kGqBlock = 256, kGqUnroll = 1;     // gradient quantize and fp32-addend accumulate
 constexpr int kGbBlock = 128, kGbUnroll = 2;     // accumulate, bf16 addend
 constexpr int kGdBlock = 512, kGdUnroll = 2;     // gradient dequantize
-constexpr int kSiBlock = 256, kSiUnroll = 2;     // SiLU & Multiply recompute
+constexpr int kSiBlock = 256, kSiBlockNarrow = 128, kSiUnroll = 2;   // SiLU & Multiply recompute (8-bit; below)
 // Occupancy caps: dynamic LDS (bytes per workgroup, never touched by the kernel) that limits
 // how many workgroups share a compute unit's 160 KB.  Measured per kernel: kernels that read
 // or write several streams at once run faster with fewer wavefronts in flight than the
@@ -131,6 +131,65 @@ __device__ __forceinline__ u32 code_bits(float x, float inv)
     return as_u32(__fadd_rn(__fmul_rn(x, inv), kRoundMagic));
 }
 
+// ---- stochastic rounding (optional variant; the paper itself rounds to nearest) ---------
+// code = max(floor(x * inv + u), -qmax) with u = B / 256, B one byte of a 32-bit hash word
+// that the four consecutive elements 4b .. 4b+3 share (byte 0, the least significant, is
+// element 4b's):
+//     key  = mix(seed ^ (high 32 bits of b) * 0x9E3779B9)
+//     word = mix((low 32 bits of b) ^ key)
+// mix() is the 32-bit finalizer of MurmurHash3.  x * inv + u is ONE binary32 addition of the
+// rounded product and u (here an fma with the exact factor 2^-8, which rounds the same
+// sum).  The sum stays below qmax + 1, so only the lower clamp can ever act (x = -amax can
+// come out a hair below -qmax).
+__device__ __forceinline__ u32 sr_mix(u32 h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+__device__ __forceinline__ u32 sr_word(u32 seed, int64_t block)
+{
+    const u32 lo = (u32)block, hi = (u32)((uint64_t)block >> 32);
+    u32 key = sr_mix(seed);                      // the same for every lane: scalar work
+    if (hi != 0) key = sr_mix(seed ^ (hi * 0x9E3779B9u));   // tensors beyond 2^34 elements
+    return sr_mix(lo ^ key);
+}
+
+template <int K>
+__device__ __forceinline__ float ubyte_to_f32(u32 w);     // (defined with the decoders below)
+
+// The stochastic code of x under byte K of `word`, as the low bits of the returned word.
+template <int K, int QMAX>
+__device__ __forceinline__ u32 sr_code_bits(float x, float inv, u32 word)
+{
+    const float shifted = __fmaf_rn(ubyte_to_f32<K>(word), 0.00390625f, __fmul_rn(x, inv));
+    const float r = fmaxf(__builtin_floorf(shifted), -(float)QMAX);
+    return (u32)(int)r;
+}
+
+// The codes of the four elements 4*block .. 4*block+3 (low bits of c[0..3], two's complement).
+template <bool SR, int QMAX>
+__device__ __forceinline__ void codes4(float x0, float x1, float x2, float x3, float inv, u32 seed,
+                                       int64_t block, u32 (&c)[4])
+{
+    if constexpr (SR) {
+        const u32 word = sr_word(seed, block);
+        c[0] = sr_code_bits<0, QMAX>(x0, inv, word);
+        c[1] = sr_code_bits<1, QMAX>(x1, inv, word);
+        c[2] = sr_code_bits<2, QMAX>(x2, inv, word);
+        c[3] = sr_code_bits<3, QMAX>(x3, inv, word);
+    } else {
+        c[0] = code_bits(x0, inv);
+        c[1] = code_bits(x1, inv);
+        c[2] = code_bits(x2, inv);
+        c[3] = code_bits(x3, inv);
+    }
+}
+
 __device__ __forceinline__ u32 push_nibble(u32 packed, u32 code)
 {
     // shifts the pair {code, packed} right by 4: the new nibble enters at the top, so
@@ -154,22 +213,28 @@ __device__ __forceinline__ float byte_to_f32(u32 w, int j)
 // at the largest magnitude and keep the sign of a zero -- the semantics of the code books
 // here.  fp4 conversions take a power-of-two scale operand; it is always 1.
 
-// Four fp32 values times inv -> one word of 8-bit codes, element 0 in the low byte.
-template <bool FP>
-__device__ __forceinline__ u32 encode4_bytes(float x0, float x1, float x2, float x3, float inv)
+// Four fp32 values times inv -> one word of 8-bit codes, element 0 in the low byte.  The
+// four are the tensor elements 4*block .. 4*block+3 (which matters to stochastic rounding only).
+template <bool FP, bool SR = false>
+__device__ __forceinline__ u32 encode4_bytes(float x0, float x1, float x2, float x3, float inv,
+                                             u32 seed = 0, int64_t block = 0)
 {
-    if (FP) {
+    static_assert(!(FP && SR), "stochastic rounding is defined for the integer grids");
+    if constexpr (FP) {
         int w = 0;
         w = __builtin_amdgcn_cvt_pk_fp8_f32(__fmul_rn(x0, inv), __fmul_rn(x1, inv), w, false);
         w = __builtin_amdgcn_cvt_pk_fp8_f32(__fmul_rn(x2, inv), __fmul_rn(x3, inv), w, true);
         return (u32)w;
+    } else {
+        u32 c[4];
+        codes4<SR, 127>(x0, x1, x2, x3, inv, seed, block, c);
+        u32 w = 0;
+        w = push_byte(w, c[0]);
+        w = push_byte(w, c[1]);
+        w = push_byte(w, c[2]);
+        w = push_byte(w, c[3]);
+        return w;
     }
-    u32 w = 0;
-    w = push_byte(w, code_bits(x0, inv));
-    w = push_byte(w, code_bits(x1, inv));
-    w = push_byte(w, code_bits(x2, inv));
-    w = push_byte(w, code_bits(x3, inv));
-    return w;
 }
 
 // The four 8-bit codes of a word as fp32 values.
@@ -240,47 +305,61 @@ __device__ __forceinline__ u32 unpack8_bf16(const u32x4& v, float (&f)[8])
 // lane's whole group (already reduced across its GROUP/8 lanes); vi is the lane's vector
 // index in the tensor of n_vec vectors.  Every lane must call this (the caller reduces
 // across lanes first); `valid` gates the stores.
-template <int BITS, int GROUP, bool FP, bool NTS>
+template <int BITS, int GROUP, bool FP, bool NTS, bool SR = false>
 __device__ __forceinline__ void quantize_store8(const float (&f)[8], u32 amax_bits, int64_t vi,
                                                 int64_t n_vec, bool valid, void* codes,
-                                                float* scales)
+                                                float* scales, u32 seed = 0)
 {
     static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
+    static_assert(!(FP && SR), "stochastic rounding is defined for the integer grids");
     constexpr int LANES = GROUP / 8;
     constexpr int QMAX = FP ? 6 : (1 << (BITS - 1)) - 1;   // largest code magnitude
     float scale, inv;
     const bool keep = scale_and_inv<QMAX>(amax_bits, scale, inv);
     if (!valid) return;
-    if (FP) {
+    if constexpr (FP) {
         const u32 p = encode8_e2m1(f, inv);
         st<NTS>((u32*)codes + vi, keep ? p : 0u);   // no signed zeros left in a zeroed group
-    } else if (BITS == 4) {
-        u32 p = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) p = push_nibble(p, code_bits(f[j], inv));
-        st<NTS>((u32*)codes + vi, keep ? p : 0u);
-    } else if (BITS == 5 || BITS == 6) {
-        u32 p = 0, h = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const u32 c = code_bits(f[j], inv);
-            p = push_nibble(p, c);
-            h = __builtin_amdgcn_alignbit(c >> 4, h, BITS - 4);  // bits 4.. of the code
-        }
-        h = keep ? h : 0u;
-        st<NTS>((u32*)codes + vi, keep ? p : 0u);
-        uint8_t* high = (uint8_t*)codes + n_vec * 4;
-        if (BITS == 5)
-            st<NTS>(high + vi, (uint8_t)(h >> 24));
-        else
-            st<NTS>((uint16_t*)high + vi, (uint16_t)(h >> 16));
     } else {
-        u32 p0 = 0, p1 = 0;
+        // the lane's elements are 8*vi .. 8*vi+7: two blocks of four
+        u32 c[8];
+        {
+            u32 lo[4], hi[4];
+            codes4<SR, QMAX>(f[0], f[1], f[2], f[3], inv, seed, 2 * vi, lo);
+            codes4<SR, QMAX>(f[4], f[5], f[6], f[7], inv, seed, 2 * vi + 1, hi);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) p0 = push_byte(p0, code_bits(f[j], inv));
+            for (int j = 0; j < 4; ++j) {
+                c[j] = lo[j];
+                c[4 + j] = hi[j];
+            }
+        }
+        if constexpr (BITS == 4) {
+            u32 p = 0;
 #pragma unroll
-        for (int j = 4; j < 8; ++j) p1 = push_byte(p1, code_bits(f[j], inv));
-        st<NTS>((u32x2*)codes + vi, u32x2{keep ? p0 : 0u, keep ? p1 : 0u});
+            for (int j = 0; j < 8; ++j) p = push_nibble(p, c[j]);
+            st<NTS>((u32*)codes + vi, keep ? p : 0u);
+        } else if constexpr (BITS == 5 || BITS == 6) {
+            u32 p = 0, h = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                p = push_nibble(p, c[j]);
+                h = __builtin_amdgcn_alignbit(c[j] >> 4, h, BITS - 4);  // bits 4.. of the code
+            }
+            h = keep ? h : 0u;
+            st<NTS>((u32*)codes + vi, keep ? p : 0u);
+            uint8_t* high = (uint8_t*)codes + n_vec * 4;
+            if constexpr (BITS == 5)
+                st<NTS>(high + vi, (uint8_t)(h >> 24));
+            else
+                st<NTS>((uint16_t*)high + vi, (uint16_t)(h >> 16));
+        } else {
+            u32 p0 = 0, p1 = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) p0 = push_byte(p0, c[j]);
+#pragma unroll
+            for (int j = 4; j < 8; ++j) p1 = push_byte(p1, c[j]);
+            st<NTS>((u32x2*)codes + vi, u32x2{keep ? p0 : 0u, keep ? p1 : 0u});
+        }
     }
     if ((vi & (LANES - 1)) == 0) st<NTS>(scales + vi / LANES, scale);
 }
@@ -357,22 +436,88 @@ __device__ __forceinline__ float decode8(const Codes8<BITS>& c, int j)
     }
 }
 
+// The lane's eight 4-, 5- or 6-bit codes as unsigned bytes code + 2^(BITS-1), the even
+// elements in the four bytes of `even`, the odd ones in `odd`: a handful of word-wide
+// operations instead of two to four per element, after which v_cvt_f32_ubyte<k> turns a byte
+// into a float in one operation.
+//   4 bits: flipping the top bit of every nibble adds 8 to the two's-complement code.
+//   5 bits: the high-bit byte is flipped the same way, then its even (odd) bits are spread to
+//           bit 4 of the four bytes by one 24-bit multiply: bit 2k times
+//           2^4 + 2^10 + 2^16 + 2^22 puts a copy at 8k + 4; the other copies and the carries of
+//           colliding copies land on bits the mask removes.
+//   6 bits: the two high bits per element are spread by two shift-or-mask steps
+//           (4-bit spacing -> 8-bit spacing), then shifted above the nibble.
+template <int BITS>
+__device__ __forceinline__ void biased_code_bytes(const Codes8<BITS>& c, u32& even, u32& odd)
+{
+    static_assert(BITS == 4 || BITS == 5 || BITS == 6, "8-bit codes are bytes already");
+    if constexpr (BITS == 4) {
+        const u32 w = c.lo ^ 0x88888888u;
+        even = w & 0x0F0F0F0Fu;
+        odd = (w >> 4) & 0x0F0F0F0Fu;
+    } else if constexpr (BITS == 5) {
+        const u32 h = (u32)c.hi ^ 0xFFu;
+        const u32 he = __umul24(h & 0x55u, 0x410410u);   // bits 0,2,4,6 -> 4,12,20,28
+        const u32 ho = __umul24(h & 0xAAu, 0x208208u);   // bits 1,3,5,7 -> 4,12,20,28
+        even = (he & 0x10101010u) | (c.lo & 0x0F0F0F0Fu);
+        odd = (ho & 0x10101010u) | ((c.lo >> 4) & 0x0F0F0F0Fu);
+    } else {
+        const u32 h = (u32)c.hi ^ 0xAAAAu;
+        u32 he = h & 0x3333u, ho = (h >> 2) & 0x3333u;                   // fields 4 bits apart
+        he = (he | (he << 8)) & 0x00FF00FFu;
+        ho = (ho | (ho << 8)) & 0x00FF00FFu;
+        he = (he | (he << 4)) & 0x03030303u;                             // fields 8 bits apart
+        ho = (ho | (ho << 4)) & 0x03030303u;
+        even = (he << 4) | (c.lo & 0x0F0F0F0Fu);
+        odd = (ho << 4) | ((c.lo >> 4) & 0x0F0F0F0Fu);
+    }
+}
+
+// Unsigned byte K of a word as a float (the compiler selects v_cvt_f32_ubyte<K>).
+template <int K>
+__device__ __forceinline__ float ubyte_to_f32(u32 w)
+{
+    return (float)((w >> (8 * K)) & 0xFFu);
+}
+
 // x' = bf16(code * scale) for the lane's 8 elements, as four words of two bf16 each
 // (element 2k in the low half of word k).  FP: the codes are E2M1 nibbles.
+// 5- and 6-bit codes go through their biased bytes u = code + 2^(BITS-1):
+// fma(u, scale, -2^(BITS-1) * scale) rounds the exact value code * scale once, like the
+// product itself (the subtrahend is exact, a power of two times the scale), so x' is the
+// bit pattern agoq_act_dequant produces -- except that a zero scale yields +0 where the
+// product of a negative code would be -0, which no consumer of these helpers can tell apart
+// (sums of squares, and layer outputs compared by magnitude).
 template <int BITS, bool FP = false>
 __device__ __forceinline__ void dequant8_packed(const Codes8<BITS>& c, float scale, u32 (&w)[4])
 {
     static_assert(!FP || BITS == 4, "the floating-point activation code book is E2M1");
-    float q[8];
+    float x[8];
     if constexpr (FP) {
+        float q[8];
         decode8_e2m1(c.lo, q);
-    } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) q[j] = decode8<BITS>(c, j);
+        for (int j = 0; j < 8; ++j) x[j] = __fmul_rn(q[j], scale);
+    } else if constexpr (BITS == 8 || BITS == 4) {
+        // one or two operations per element already (sign-extending byte select; bit-field
+        // extract + convert): the byte route measured no shorter for 4-bit codes
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = __fmul_rn(decode8<BITS>(c, j), scale);
+    } else {
+        u32 even, odd;
+        biased_code_bytes<BITS>(c, even, odd);
+        const float off = __fmul_rn(-(float)(1 << (BITS - 1)), scale);
+        x[0] = __fmaf_rn(ubyte_to_f32<0>(even), scale, off);
+        x[1] = __fmaf_rn(ubyte_to_f32<0>(odd), scale, off);
+        x[2] = __fmaf_rn(ubyte_to_f32<1>(even), scale, off);
+        x[3] = __fmaf_rn(ubyte_to_f32<1>(odd), scale, off);
+        x[4] = __fmaf_rn(ubyte_to_f32<2>(even), scale, off);
+        x[5] = __fmaf_rn(ubyte_to_f32<2>(odd), scale, off);
+        x[6] = __fmaf_rn(ubyte_to_f32<3>(even), scale, off);
+        x[7] = __fmaf_rn(ubyte_to_f32<3>(odd), scale, off);
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-        w[k] = pack_bf16x2(__fmul_rn(q[2 * k], scale), __fmul_rn(q[2 * k + 1], scale));
+    for (int k = 0; k < 4; ++k) w[k] = pack_bf16x2(x[2 * k], x[2 * k + 1]);
 }
 
 // The same as fp32 values.

@@ -11,11 +11,11 @@ namespace {
 // vector p of lane l being elements [p*64 + 4l, p*64 + 4l + 4) of the group, so
 // each load instruction reads whole 256-byte runs.
 // ---------------------------------------------------------------------------
-template <int GROUP, int UNROLL, bool FP = false>
+template <int GROUP, int UNROLL, bool FP = false, bool SR = false>
 __global__ __launch_bounds__(kGqBlock) void grad_quant_kernel(const f32x4* __restrict__ g,
                                                             int64_t n_groups,
                                                             u32* __restrict__ codes,
-                                                            float* __restrict__ scales)
+                                                            float* __restrict__ scales, u32 seed)
 {
     constexpr int VPL = GROUP / 64;   // vectors per lane: 1 (group 64) or 2 (group 128)
     constexpr int VPG = GROUP / 4;    // vectors per group
@@ -48,9 +48,11 @@ __global__ __launch_bounds__(kGqBlock) void grad_quant_kernel(const f32x4* __res
         if (grp < n_groups) {
 #pragma unroll
             for (int p = 0; p < VPL; ++p) {
-                u32 w = encode4_bytes<FP>(v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3], inv);
+                // the vector's four elements are 4 * (its index) ..: its index is their block
+                const int64_t vec = grp * VPG + p * 16 + lane16;
+                u32 w = encode4_bytes<FP, SR>(v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3], inv, seed, vec);
                 if (!keep) w = 0;   // dead group: no signed zeros; non-finite group: no codes
-                st<NTS>(codes + grp * VPG + p * 16 + lane16, w);
+                st<NTS>(codes + vec, w);
             }
             if (lane16 == 0) st<NTS>(scales + grp, scale);
         }
@@ -63,10 +65,10 @@ __global__ __launch_bounds__(kGqBlock) void grad_quant_kernel(const f32x4* __res
 // a group.  acc = fma(code_k, scale_k, acc) for k = 0..K-1 in that order.
 // KT > 0: K known at compile time (all loads hoisted); KT == 0: run-time K.
 // ---------------------------------------------------------------------------
-template <int GROUP, bool FP = false>
+template <int GROUP, bool FP = false, bool SR = false>
 __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi,
                                               bool valid, u32x4* __restrict__ out_codes,
-                                              float* __restrict__ out_scales)
+                                              float* __restrict__ out_scales, u32 seed = 0)
 {
     constexpr int LANES = GROUP / 16;
     u32 m = 0;
@@ -79,7 +81,8 @@ __device__ __forceinline__ void reduce_finish(const float (&acc)[16], int64_t vi
         u32x4 w = {0, 0, 0, 0};
 #pragma unroll
         for (int d = 0; d < 4; ++d)
-            w[d] = encode4_bytes<FP>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv);
+            w[d] = encode4_bytes<FP, SR>(acc[4 * d], acc[4 * d + 1], acc[4 * d + 2], acc[4 * d + 3], inv, seed,
+                                         4 * vi + d);   // the lane's elements are 16 * vi ..: four blocks
         if (!keep) w = u32x4{0, 0, 0, 0};   // dead group: no signed zeros; non-finite: no codes
         st<true>(out_codes + vi, w);
         if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
@@ -177,11 +180,11 @@ __device__ __forceinline__ void reduce_batch(float (&acc)[16], const int8_t* __r
 // Four chunks at a time, then the remaining one to three together (one at a time they would
 // each wait a full memory latency).
 constexpr int kAnyKBlock = 512;
-template <int GROUP, bool FP>
+template <int GROUP, bool FP, bool SR = false>
 __global__ __launch_bounds__(kAnyKBlock) void grad_reduce_anyk_kernel(
     const int8_t* __restrict__ in_codes, int64_t stride_codes, const float* __restrict__ in_scales,
     int64_t stride_scales, int K, int64_t n_vec, u32x4* __restrict__ out_codes,
-    float* __restrict__ out_scales)
+    float* __restrict__ out_scales, u32 seed)
 {
     constexpr int LANES = GROUP / 16;
     const int64_t vi = (int64_t)blockIdx.x * kAnyKBlock + threadIdx.x;
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(kAnyKBlock) void grad_reduce_anyk_kernel(
     case 1: reduce_batch<1, FP, LANES>(acc, in_codes, stride_codes, in_scales, stride_scales, k, vc); break;
     default: break;
     }
-    reduce_finish<GROUP, FP>(acc, vi, valid, out_codes, out_scales);
+    reduce_finish<GROUP, FP, SR>(acc, vi, valid, out_codes, out_scales, seed);
 }
 
 // Launch of the reduce for either code book (arguments already checked).  Measured on
@@ -230,6 +233,7 @@ struct ReduceArgs {
     u32x4* out_codes;
     float* out_scales;
     hipStream_t st;
+    u32 seed;            // stochastic rounding only
 };
 
 template <int GROUP, int KT, bool FP, int BLOCK, int RU>
@@ -240,9 +244,14 @@ int launch_reduce_kt(const ReduceArgs& a, size_t lds)
                   a.n_vec, a.out_codes, a.out_scales);
 }
 
-template <int GROUP, bool FP>
+template <int GROUP, bool FP, bool SR>
 int launch_reduce_group(const ReduceArgs& a)
 {
+    // the stochastic variant runs the run-time-K kernel for every chunk count
+    if constexpr (SR)
+        return launch(grad_reduce_anyk_kernel<GROUP, FP, true>, dim3(blocks_for(a.n_vec, kAnyKBlock)),
+                      dim3(kAnyKBlock), 0, a.st, a.in_codes, a.stride_codes, a.in_scales, a.stride_scales, a.K,
+                      a.n_vec, a.out_codes, a.out_scales, a.seed);
     const bool large = a.n_vec >= kReduceTwoVectorsFrom;
     switch (a.K) {
     case 1: return launch_reduce_kt<GROUP, 1, FP, 256, 2>(a, 0);
@@ -263,14 +272,14 @@ int launch_reduce_group(const ReduceArgs& a)
     }
     return launch(grad_reduce_anyk_kernel<GROUP, FP>, dim3(blocks_for(a.n_vec, kAnyKBlock)), dim3(kAnyKBlock),
                   0, a.st, a.in_codes, a.stride_codes, a.in_scales, a.stride_scales, a.K, a.n_vec,
-                  a.out_codes, a.out_scales);
+                  a.out_codes, a.out_scales, 0u);
 }
 
 // Validation and launch shared by the int8 and E4M3 forms of the reduce.
-template <bool FP>
+template <bool FP, bool SR = false>
 int launch_reduce(const void* in_codes, int64_t chunk_stride_codes, const float* in_scales,
                   int64_t chunk_stride_scales, int K, int64_t numel, int group, void* out_codes,
-                  float* out_scales, void* stream)
+                  float* out_scales, void* stream, u32 seed = 0)
 {
     if (!in_codes || !in_scales || !out_codes || !out_scales) return AGOQ_ERR_NULL;
     if (int rc = check_common(numel, group)) return rc;
@@ -280,8 +289,8 @@ int launch_reduce(const void* in_codes, int64_t chunk_stride_codes, const float*
         misaligned(out_scales) || (chunk_stride_codes & 15) != 0)
         return AGOQ_ERR_ALIGN;
     const ReduceArgs a{(const int8_t*)in_codes, chunk_stride_codes, in_scales, chunk_stride_scales, K,
-                       numel / 16, (u32x4*)out_codes, out_scales, (hipStream_t)stream};
-    return group == 128 ? launch_reduce_group<128, FP>(a) : launch_reduce_group<64, FP>(a);
+                       numel / 16, (u32x4*)out_codes, out_scales, (hipStream_t)stream, seed};
+    return group == 128 ? launch_reduce_group<128, FP, SR>(a) : launch_reduce_group<64, FP, SR>(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -293,10 +302,10 @@ int launch_reduce(const void* in_codes, int64_t chunk_stride_codes, const float*
 //   fp32 addend: lane layout of grad_quant_kernel (one DPP row per group).
 //   bf16 addend: lane layout of act_quant_kernel (8 elements per lane).
 // ---------------------------------------------------------------------------
-template <int GROUP, int UNROLL, bool FP = false>
+template <int GROUP, int UNROLL, bool FP = false, bool SR = false>
 __global__ __launch_bounds__(kGqBlock) void grad_accumulate_f32_kernel(
     const u32* main_codes, const float* main_scales, const f32x4* __restrict__ g_new,
-    int64_t n_groups, u32* out_codes, float* out_scales)
+    int64_t n_groups, u32* out_codes, float* out_scales, u32 seed)
 {
     constexpr int VPL = GROUP / 64;
     constexpr int VPG = GROUP / 4;
@@ -342,19 +351,20 @@ __global__ __launch_bounds__(kGqBlock) void grad_accumulate_f32_kernel(
         if (grp < n_groups) {
 #pragma unroll
             for (int p = 0; p < VPL; ++p) {
-                u32 w = encode4_bytes<FP>(acc[p][0], acc[p][1], acc[p][2], acc[p][3], inv);
+                const int64_t vec = grp * VPG + p * 16 + lane16;      // = the block of its four elements
+                u32 w = encode4_bytes<FP, SR>(acc[p][0], acc[p][1], acc[p][2], acc[p][3], inv, seed, vec);
                 if (!keep) w = 0;   // dead group: no signed zeros; non-finite group: no codes
-                st<true>(out_codes + grp * VPG + p * 16 + lane16, w);
+                st<true>(out_codes + vec, w);
             }
             if (lane16 == 0) st<true>(out_scales + grp, scale);
         }
     }
 }
 
-template <int GROUP, int UNROLL, bool FP = false>
+template <int GROUP, int UNROLL, bool FP = false, bool SR = false>
 __global__ __launch_bounds__(kGbBlock) void grad_accumulate_bf16_kernel(
     const u32x2* main_codes, const float* main_scales, const u32x4* __restrict__ g_new,
-    int64_t n_vec, u32x2* out_codes, float* out_scales)
+    int64_t n_vec, u32x2* out_codes, float* out_scales, u32 seed)
 {
     constexpr int LANES = GROUP / 8;
     constexpr int kBlock = kGbBlock;
@@ -396,8 +406,8 @@ __global__ __launch_bounds__(kGbBlock) void grad_accumulate_bf16_kernel(
         float scale, inv;
         const bool keep = scale_and_inv<FP ? 448 : 127>(m, scale, inv);
         if (vi < n_vec) {
-            u32 p0 = encode4_bytes<FP>(acc[0], acc[1], acc[2], acc[3], inv);
-            u32 p1 = encode4_bytes<FP>(acc[4], acc[5], acc[6], acc[7], inv);
+            u32 p0 = encode4_bytes<FP, SR>(acc[0], acc[1], acc[2], acc[3], inv, seed, 2 * vi);
+            u32 p1 = encode4_bytes<FP, SR>(acc[4], acc[5], acc[6], acc[7], inv, seed, 2 * vi + 1);
             if (!keep) p0 = p1 = 0;   // dead group: no signed zeros; non-finite group: no codes
             st<true>(out_codes + vi, u32x2{p0, p1});
             if ((threadIdx.x & (LANES - 1)) == 0) st<true>(out_scales + vi / LANES, scale);
@@ -451,8 +461,9 @@ __global__ __launch_bounds__(kGdBlock) void grad_dequant_kernel(const u32* __res
 }
 
 // Validation and launch shared by the int8 and E4M3 forms of the gradient store.
-template <bool FP>
-int launch_grad_quant(const float* grad, int64_t numel, int group, void* codes, float* scales, void* stream)
+template <bool FP, bool SR = false>
+int launch_grad_quant(const float* grad, int64_t numel, int group, void* codes, float* scales, void* stream,
+                      u32 seed = 0)
 {
     if (!grad || !codes || !scales) return AGOQ_ERR_NULL;
     if (int rc = check_common(numel, group)) return rc;
@@ -461,10 +472,10 @@ int launch_grad_quant(const float* grad, int64_t numel, int group, void* codes, 
     const dim3 grid(blocks_for(n_groups * 16, kGqBlock * kGqUnroll)), block(kGqBlock);
     hipStream_t st = (hipStream_t)stream;
     if (group == 128)
-        return launch(grad_quant_kernel<128, kGqUnroll, FP>, grid, block, 0, st, (const f32x4*)grad, n_groups,
-                      (u32*)codes, scales);
-    return launch(grad_quant_kernel<64, kGqUnroll, FP>, grid, block, 0, st, (const f32x4*)grad, n_groups,
-                  (u32*)codes, scales);
+        return launch(grad_quant_kernel<128, kGqUnroll, FP, SR>, grid, block, 0, st, (const f32x4*)grad, n_groups,
+                      (u32*)codes, scales, seed);
+    return launch(grad_quant_kernel<64, kGqUnroll, FP, SR>, grid, block, 0, st, (const f32x4*)grad, n_groups,
+                  (u32*)codes, scales, seed);
 }
 
 // ... of the gradient dequantize.
@@ -486,10 +497,10 @@ int launch_grad_dequant(const void* codes, const float* scales, int64_t numel, i
 }
 
 // ... of the local accumulation.
-template <bool FP>
+template <bool FP, bool SR = false>
 int launch_accumulate(const void* main_codes, const float* main_scales, const void* g_new,
                       int g_new_is_bf16, int64_t numel, int group, void* out_codes,
-                      float* out_scales, void* stream)
+                      float* out_scales, void* stream, u32 seed = 0)
 {
     if (!main_codes || !main_scales || !g_new || !out_codes || !out_scales) return AGOQ_ERR_NULL;
     if (int rc = check_common(numel, group)) return rc;
@@ -501,22 +512,22 @@ int launch_accumulate(const void* main_codes, const float* main_scales, const vo
         const int64_t n_vec = numel / 8;
         const dim3 grid(blocks_for(n_vec, kGbBlock * kGbUnroll)), block(kGbBlock);
         if (group == 128)
-            return launch(grad_accumulate_bf16_kernel<128, kGbUnroll, FP>, grid, block, 0, st,
+            return launch(grad_accumulate_bf16_kernel<128, kGbUnroll, FP, SR>, grid, block, 0, st,
                           (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec,
-                          (u32x2*)out_codes, out_scales);
-        return launch(grad_accumulate_bf16_kernel<64, kGbUnroll, FP>, grid, block, 0, st,
+                          (u32x2*)out_codes, out_scales, seed);
+        return launch(grad_accumulate_bf16_kernel<64, kGbUnroll, FP, SR>, grid, block, 0, st,
                       (const u32x2*)main_codes, main_scales, (const u32x4*)g_new, n_vec, (u32x2*)out_codes,
-                      out_scales);
+                      out_scales, seed);
     }
     const int64_t n_groups = numel / group;
     const dim3 grid(blocks_for(n_groups * 16, kGqBlock * kGqUnroll)), block(kGqBlock);
     if (group == 128)
-        return launch(grad_accumulate_f32_kernel<128, kGqUnroll, FP>, grid, block, kCapGa, st,
+        return launch(grad_accumulate_f32_kernel<128, kGqUnroll, FP, SR>, grid, block, kCapGa, st,
                       (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups, (u32*)out_codes,
-                      out_scales);
-    return launch(grad_accumulate_f32_kernel<64, kGqUnroll, FP>, grid, block, kCapGa, st,
+                      out_scales, seed);
+    return launch(grad_accumulate_f32_kernel<64, kGqUnroll, FP, SR>, grid, block, kCapGa, st,
                   (const u32*)main_codes, main_scales, (const f32x4*)g_new, n_groups, (u32*)out_codes,
-                  out_scales);
+                  out_scales, seed);
 }
 
 }  // namespace
@@ -550,6 +561,28 @@ int agoq_grad_dequant(const int8_t* codes, const float* scales, int64_t numel, i
                       float* out, void* stream)
 {
     return launch_grad_dequant<false>(codes, scales, numel, group, out, stream);
+}
+
+int agoq_grad_quant_sr(const float* grad, int64_t numel, int group, uint32_t seed, int8_t* codes,
+                       float* scales, void* stream)
+{
+    return launch_grad_quant<false, true>(grad, numel, group, codes, scales, stream, seed);
+}
+
+int agoq_grad_reduce_requant_sr(const int8_t* in_codes, int64_t chunk_stride_codes, const float* in_scales,
+                                int64_t chunk_stride_scales, int K, int64_t numel, int group,
+                                uint32_t seed, int8_t* out_codes, float* out_scales, void* stream)
+{
+    return launch_reduce<false, true>(in_codes, chunk_stride_codes, in_scales, chunk_stride_scales, K, numel,
+                                      group, out_codes, out_scales, stream, seed);
+}
+
+int agoq_grad_accumulate_sr(const int8_t* main_codes, const float* main_scales, const void* g_new,
+                            int g_new_is_bf16, int64_t numel, int group, uint32_t seed,
+                            int8_t* out_codes, float* out_scales, void* stream)
+{
+    return launch_accumulate<false, true>(main_codes, main_scales, g_new, g_new_is_bf16, numel, group,
+                                          out_codes, out_scales, stream, seed);
 }
 
 int agoq_fp8_grad_quant(const float* grad, int64_t numel, int group, uint8_t* codes, float* scales,

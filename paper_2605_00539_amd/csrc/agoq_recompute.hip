@@ -25,13 +25,12 @@ constexpr int norm_max_block(int vpt)
     return (int)(kNormMaxCols / 8 / vpt) < kNormMaxBlock ? (int)(kNormMaxCols / 8 / vpt) : kNormMaxBlock;
 }
 // Launch shape of the row kernels (measured on [8192,4096] and [8192,14336] tensors).
-constexpr int kNormVpt = 4;         // column vectors per lane (doubled while a row needs > 1024 lanes)
-constexpr int kNormDepth = 2;       // rows in flight beyond the one being reduced: 1 or 2
-constexpr int kNormDepth56 = 1;     // ... with 5- and 6-bit codes (three loads per vector)
-constexpr int kNormVpt8 = 2;        // the same two for 8-bit codes, whose buffers are twice the size
-constexpr int kNormDepth8 = 2;
-constexpr int kNormFwdVpt = 2;      // the same two for the forward kernel
-constexpr int kNormFwdDepth = 2;
+constexpr int kNormDepth = 2;       // rows of a workgroup in flight beyond the one being reduced
+constexpr int kNormVpt = 4;         // column vectors per lane, 4-bit codes (doubled while a row needs > 1024 lanes)
+constexpr int kNormVpt8 = 2;        // ... 8-bit codes, whose buffers are twice the size
+constexpr int kNormFwdVpt = 2;      // ... the forward kernel
+// 5- and 6-bit codes (three loads per vector): two per lane on rows of up to 1024 vectors, else four
+constexpr int norm_vpt56(int vecs_per_row) { return vecs_per_row <= 1024 ? 2 : 4; }
 constexpr int kNormResident = 1024; // lanes per compute unit the grid is sized for
 
 // Sum of the per-wavefront partial sums of a workgroup, in wavefront order.
@@ -73,6 +72,37 @@ __device__ __forceinline__ float sumsq8(const u32 (&xp)[4], float ss)
     return ss;
 }
 
+// Addressing of the row kernels: a row's base pointers are uniform over the workgroup (scalar
+// registers, scalar arithmetic) and a lane's byte offsets within a row never change, so the
+// row loop spends one vector instruction per access on its address instead of the three or
+// four that 64-bit index arithmetic per lane took (a seventh of the loop's instructions).
+template <typename T>
+__device__ __forceinline__ const T* at_bytes(const T* base, unsigned byte_offset)
+{
+    return (const T*)((const char*)base + byte_offset);
+}
+template <typename T>
+__device__ __forceinline__ T* at_bytes(T* base, unsigned byte_offset)
+{
+    return (T*)((char*)base + byte_offset);
+}
+
+// The stored codes of vector v (index within the row) of a row whose nibble plane starts at
+// row_lo and whose high-bit plane starts at row_hi.
+template <int BITS>
+__device__ __forceinline__ Codes8<BITS> load_row_codes8(const void* row_lo, const void* row_hi, unsigned v)
+{
+    Codes8<BITS> c;
+    if constexpr (BITS == 8) {
+        c.w = ld<true>(at_bytes((const uint64_t*)row_lo, v * 8u));
+    } else {
+        c.lo = ld<true>(at_bytes((const u32*)row_lo, v * 4u));
+        if constexpr (BITS == 5) c.hi = ld<true>(at_bytes((const uint8_t*)row_hi, v));
+        if constexpr (BITS == 6) c.hi = ld<true>(at_bytes((const uint16_t*)row_hi, v * 2u));
+    }
+    return c;
+}
+
 // PIPE: chosen by the host when every workgroup has many rows and the row has exactly
 // VPT * blockDim.x vectors.  No lane is then ever past the end of a row, nothing in the row
 // loop sits under a lane test, and the walk has a steady part (below).
@@ -100,19 +130,30 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     // Loads take no lane test (a lane past the end of the row re-reads the row's last vector
     // and uses scale 0, so it adds nothing to the row sum): a load under a branch would have
     // to be merged with the register's old value, which again waits for the data.
-    constexpr int kDepth = BITS == 8 ? kNormDepth8 : BITS == 4 ? kNormDepth : kNormDepth56;
+    constexpr int kDepth = kNormDepth;
     struct RowBuf {
         Codes8<BITS> c[VPT];
         float sc[VPT];
     };
     const int64_t step = gridDim.x;
+    // the lane's vectors within a row (a lane past the end of the row: the row's last vector)
+    unsigned vc[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int v = threadIdx.x + u * blockDim.x;
+        vc[u] = (unsigned)(PIPE || v < vecs_per_row ? v : vecs_per_row - 1);
+    }
+    constexpr int kHighBytes = BITS == 6 ? 2 : 1;     // bytes per vector in the high-bit plane
+    const uint8_t* const high = (const uint8_t*)codes + n_vec_total * 4;
     auto fetch = [&](RowBuf& b, int64_t row) {
+        const int64_t first = row * vecs_per_row;                   // uniform over the workgroup
+        const void* row_lo = (const uint8_t*)codes + first * (BITS == 8 ? 8 : 4);
+        const void* row_hi = high + first * kHighBytes;
+        const float* row_sc = scales + first / LANES;               // rows are whole groups
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
-            const int v = threadIdx.x + u * blockDim.x;
-            const int64_t vi = row * vecs_per_row + (PIPE || v < vecs_per_row ? v : vecs_per_row - 1);
-            b.c[u] = load_codes8<BITS, true>(codes, n_vec_total, vi);
-            b.sc[u] = ld<false>(scales + vi / LANES);
+            b.c[u] = load_row_codes8<BITS>(row_lo, row_hi, vc[u]);
+            b.sc[u] = ld<false>(at_bytes(row_sc, vc[u] / LANES * 4u));
         }
     };
     // One row from its buffer to memory; `refill` (the same buffer, free once the row has
@@ -133,11 +174,12 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
         const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
         const float rinv = __fdiv_rn(1.0f, r);
         if (threadIdx.x == 0) r_out[row] = r;
+        u32x4* const y_row = y + row * vecs_per_row;                // uniform over the workgroup
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const int v = threadIdx.x + u * blockDim.x;
             if (PIPE || v < vecs_per_row)
-                st<true>(y + row * vecs_per_row + v, norm_out8(xp[u], rinv, g0[u], g1[u]));
+                st<true>(at_bytes(y_row, vc[u] * 16u), norm_out8(xp[u], rinv, g0[u], g1[u]));
         }
     };
     constexpr std::true_type kSure{};
@@ -154,72 +196,65 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     // longer code costs more than the waits) the tail loop is the whole walk.
     int64_t row = blockIdx.x;                       // the grid never exceeds the row count
     int phase = 0;
-    if constexpr (kDepth == 2) {
-        RowBuf b0, b1, b2;
-        if (PIPE && row + 5 * step < rows) {
-            fetch(b0, row);
-            fetch(b1, row + step);
-            fetch(b2, row + 2 * step);
-            do {
-                finish(kSure, b0, row, b0, phase);
-                finish(kSure, b1, row + step, b1, phase ^ 1);
-                finish(kSure, b2, row + 2 * step, b2, phase);
-                row += 3 * step;
-                phase ^= 1;
-            } while (row + 5 * step < rows);
-        } else {
-            fetch(b0, row);
-            if (row + step < rows) fetch(b1, row + step);
-            if (row + 2 * step < rows) fetch(b2, row + 2 * step);
-        }
-        while (true) {
-            finish(kTested, b0, row, b0, phase);
-            if ((row += step) >= rows) break;
-            finish(kTested, b1, row, b1, phase ^ 1);
-            if ((row += step) >= rows) break;
-            finish(kTested, b2, row, b2, phase);
-            if ((row += step) >= rows) break;
-            finish(kTested, b0, row, b0, phase ^ 1);
-            if ((row += step) >= rows) break;
-            finish(kTested, b1, row, b1, phase);
-            if ((row += step) >= rows) break;
-            finish(kTested, b2, row, b2, phase ^ 1);
-            if ((row += step) >= rows) break;
-        }
+    static_assert(kDepth == 2, "the walk below rotates three row buffers");
+    RowBuf b0, b1, b2;
+    if (PIPE && row + 5 * step < rows) {
+        fetch(b0, row);
+        fetch(b1, row + step);
+        fetch(b2, row + 2 * step);
+        do {
+            finish(kSure, b0, row, b0, phase);
+            finish(kSure, b1, row + step, b1, phase ^ 1);
+            finish(kSure, b2, row + 2 * step, b2, phase);
+            row += 3 * step;
+            phase ^= 1;
+        } while (row + 5 * step < rows);
     } else {
-        RowBuf b0, b1;
-        if (PIPE && row + 3 * step < rows) {
-            fetch(b0, row);
-            fetch(b1, row + step);
-            do {
-                finish(kSure, b0, row, b0, 0);
-                finish(kSure, b1, row + step, b1, 1);
-                row += 2 * step;
-            } while (row + 3 * step < rows);
-        } else {
-            fetch(b0, row);
-            if (row + step < rows) fetch(b1, row + step);
-        }
-        while (true) {
-            finish(kTested, b0, row, b0, 0);
-            if ((row += step) >= rows) break;
-            finish(kTested, b1, row, b1, 1);
-            if ((row += step) >= rows) break;
-        }
+        fetch(b0, row);
+        if (row + step < rows) fetch(b1, row + step);
+        if (row + 2 * step < rows) fetch(b2, row + 2 * step);
+    }
+    while (true) {
+        finish(kTested, b0, row, b0, phase);
+        if ((row += step) >= rows) break;
+        finish(kTested, b1, row, b1, phase ^ 1);
+        if ((row += step) >= rows) break;
+        finish(kTested, b2, row, b2, phase);
+        if ((row += step) >= rows) break;
+        finish(kTested, b0, row, b0, phase ^ 1);
+        if ((row += step) >= rows) break;
+        finish(kTested, b1, row, b1, phase);
+        if ((row += step) >= rows) break;
+        finish(kTested, b2, row, b2, phase ^ 1);
+        if ((row += step) >= rows) break;
     }
 }
 
 // SiLU & Multiply recompute: z = bf16(u' * g' * sigmoid(g')), elementwise over the two
-// stored tensors (which may have different code widths).
-template <int BITS_G, int BITS_U, int GROUP, int UNROLL, bool FP = false>
-__global__ __launch_bounds__(kSiBlock) void act_dequant_silu_mul_kernel(
-    const void* __restrict__ gate_codes, const float* __restrict__ gate_scales,
-    const void* __restrict__ up_codes, const float* __restrict__ up_scales, int64_t n_vec,
-    u32x4* __restrict__ z)
+// stored tensors (which may have different code widths).  The kernel is bound by vector
+// instructions as much as by memory (two decodes, exp and rcp at a quarter of the rate), so a
+// tile's base pointers are scalar, lane offsets are 32 bits wide, and only the one workgroup
+// that straddles the end of the tensor clamps its loads (FULL = false).
+template <int BITS_G, int BITS_U, int GROUP, int BLOCK, int UNROLL, bool FP, bool FULL>
+__device__ __forceinline__ void dequant_silu_mul_tile(const void* __restrict__ gate_codes,
+                                                      const float* __restrict__ gate_scales,
+                                                      const void* __restrict__ up_codes,
+                                                      const float* __restrict__ up_scales, int64_t n_vec,
+                                                      u32x4* __restrict__ z)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kBlock = kSiBlock;
-    const int64_t base = (int64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
+    constexpr int kTile = BLOCK * UNROLL;
+    const int64_t first = (int64_t)blockIdx.x * kTile;                  // uniform over the workgroup
+    const unsigned left = FULL ? (unsigned)kTile : (unsigned)(n_vec - first);   // vectors from `first` on
+    const uint8_t* const gate_bytes = (const uint8_t*)gate_codes;
+    const uint8_t* const up_bytes = (const uint8_t*)up_codes;
+    const void* g_lo = gate_bytes + first * (BITS_G == 8 ? 8 : 4);
+    const void* g_hi = gate_bytes + n_vec * 4 + first * (BITS_G == 6 ? 2 : 1);
+    const void* u_lo = up_bytes + first * (BITS_U == 8 ? 8 : 4);
+    const void* u_hi = up_bytes + n_vec * 4 + first * (BITS_U == 6 ? 2 : 1);
+    const float* g_sc = gate_scales + first / LANES;                    // a tile is whole groups
+    const float* u_sc = up_scales + first / LANES;
+    u32x4* const z_tile = z + first;
     // loads (unconditional: a lane past the end re-reads the last vector and stores nothing),
     // one point where all of them are waited for, then arithmetic and stores vector by vector
     Codes8<BITS_G> gc[UNROLL];
@@ -227,12 +262,12 @@ __global__ __launch_bounds__(kSiBlock) void act_dequant_silu_mul_kernel(
     float gs[UNROLL], us[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        const int64_t vi = base + (int64_t)u * kBlock;
-        const int64_t vc = vi < n_vec ? vi : n_vec - 1;
-        gc[u] = load_codes8<BITS_G, true>(gate_codes, n_vec, vc);
-        uc[u] = load_codes8<BITS_U, true>(up_codes, n_vec, vc);
-        gs[u] = ld<false>(gate_scales + vc / LANES);
-        us[u] = ld<false>(up_scales + vc / LANES);
+        const unsigned lane = threadIdx.x + u * BLOCK;
+        const unsigned vc = FULL || lane < left ? lane : left - 1;
+        gc[u] = load_row_codes8<BITS_G>(g_lo, g_hi, vc);
+        uc[u] = load_row_codes8<BITS_U>(u_lo, u_hi, vc);
+        gs[u] = ld<false>(at_bytes(g_sc, vc / LANES * 4u));
+        us[u] = ld<false>(at_bytes(u_sc, vc / LANES * 4u));
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -244,7 +279,7 @@ __global__ __launch_bounds__(kSiBlock) void act_dequant_silu_mul_kernel(
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        const int64_t vi = base + (int64_t)u * kBlock;
+        const unsigned lane = threadIdx.x + u * BLOCK;
         float g[8], up[8], o[8];
         dequant8_bf16<BITS_G, FP>(gc[u], gs[u], g);
         dequant8_bf16<BITS_U, FP>(uc[u], us[u], up);
@@ -254,10 +289,25 @@ __global__ __launch_bounds__(kSiBlock) void act_dequant_silu_mul_kernel(
             const float sig = __builtin_amdgcn_rcpf(1.0f + e);
             o[j] = __fmul_rn(__fmul_rn(up[j], g[j]), sig);
         }
-        if (vi < n_vec)
-            st<true>(z + vi, u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]),
-                                   pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])});
+        if (FULL || lane < left)
+            st<true>(at_bytes(z_tile, lane * 16u),
+                     u32x4{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                           pack_bf16x2(o[6], o[7])});
     }
+}
+
+template <int BITS_G, int BITS_U, int GROUP, int BLOCK, int UNROLL, bool FP = false>
+__global__ __launch_bounds__(BLOCK) void act_dequant_silu_mul_kernel(
+    const void* __restrict__ gate_codes, const float* __restrict__ gate_scales,
+    const void* __restrict__ up_codes, const float* __restrict__ up_scales, int64_t n_vec,
+    u32x4* __restrict__ z)
+{
+    if (((int64_t)blockIdx.x + 1) * (BLOCK * UNROLL) <= n_vec)
+        dequant_silu_mul_tile<BITS_G, BITS_U, GROUP, BLOCK, UNROLL, FP, true>(gate_codes, gate_scales, up_codes,
+                                                                       up_scales, n_vec, z);
+    else
+        dequant_silu_mul_tile<BITS_G, BITS_U, GROUP, BLOCK, UNROLL, FP, false>(gate_codes, gate_scales, up_codes,
+                                                                        up_scales, n_vec, z);
 }
 
 // ---------------------------------------------------------------------------
@@ -274,7 +324,7 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     float* __restrict__ r_out, void* __restrict__ codes, float* __restrict__ scales)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int kDepth = kNormFwdDepth;
+    constexpr int kDepth = kNormDepth;
     __shared__ float wave_part[2][kNormMaxBlock / 64];
     f32x4 g0[VPT], g1[VPT];
 #pragma unroll
@@ -292,12 +342,17 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
         u32x4 v[VPT];
     };
     const int64_t step = gridDim.x;
-    auto fetch = [&](RowBuf& b, int64_t row) {
+    // the lane's vectors within a row (a lane past the end of the row: the row's last vector)
+    unsigned vc[VPT];
 #pragma unroll
-        for (int u = 0; u < VPT; ++u) {
-            const int c = threadIdx.x + u * blockDim.x;
-            b.v[u] = ld<true>(x + row * vecs_per_row + (PIPE || c < vecs_per_row ? c : vecs_per_row - 1));
-        }
+    for (int u = 0; u < VPT; ++u) {
+        const int c = threadIdx.x + u * blockDim.x;
+        vc[u] = (unsigned)(PIPE || c < vecs_per_row ? c : vecs_per_row - 1);
+    }
+    auto fetch = [&](RowBuf& b, int64_t row) {
+        const u32x4* const x_row = x + row * vecs_per_row;          // uniform over the workgroup
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) b.v[u] = ld<true>(at_bytes(x_row, vc[u] * 16u));
     };
     auto finish = [&](auto sure, const RowBuf& b, int64_t row, RowBuf& refill, int phase) {
         u32x4 v[VPT];
@@ -320,12 +375,13 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
         const float r = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
         const float rinv = __fdiv_rn(1.0f, r);
         if (threadIdx.x == 0 && r_out) r_out[row] = r;
+        u32x4* const y_row = y + row * vecs_per_row;                // uniform over the workgroup
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             const int c = threadIdx.x + u * blockDim.x;
             const u32 xp[4] = {v[u][0], v[u][1], v[u][2], v[u][3]};
             if (PIPE || c < vecs_per_row)
-                st<true>(y + row * vecs_per_row + c, norm_out8(xp, rinv, g0[u], g1[u]));
+                st<true>(at_bytes(y_row, vc[u] * 16u), norm_out8(xp, rinv, g0[u], g1[u]));
         }
     };
     constexpr std::true_type kSure{};
@@ -333,58 +389,37 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     // steady part with untested refills, then the tail: see the recompute kernel
     int64_t row = blockIdx.x;                       // the grid never exceeds the row count
     int phase = 0;
-    if constexpr (kDepth == 2) {
-        RowBuf b0, b1, b2;
-        if (PIPE && row + 5 * step < rows) {
-            fetch(b0, row);
-            fetch(b1, row + step);
-            fetch(b2, row + 2 * step);
-            do {
-                finish(kSure, b0, row, b0, phase);
-                finish(kSure, b1, row + step, b1, phase ^ 1);
-                finish(kSure, b2, row + 2 * step, b2, phase);
-                row += 3 * step;
-                phase ^= 1;
-            } while (row + 5 * step < rows);
-        } else {
-            fetch(b0, row);
-            if (row + step < rows) fetch(b1, row + step);
-            if (row + 2 * step < rows) fetch(b2, row + 2 * step);
-        }
-        while (true) {
-            finish(kTested, b0, row, b0, phase);
-            if ((row += step) >= rows) break;
-            finish(kTested, b1, row, b1, phase ^ 1);
-            if ((row += step) >= rows) break;
-            finish(kTested, b2, row, b2, phase);
-            if ((row += step) >= rows) break;
-            finish(kTested, b0, row, b0, phase ^ 1);
-            if ((row += step) >= rows) break;
-            finish(kTested, b1, row, b1, phase);
-            if ((row += step) >= rows) break;
-            finish(kTested, b2, row, b2, phase ^ 1);
-            if ((row += step) >= rows) break;
-        }
+    static_assert(kDepth == 2, "the walk below rotates three row buffers");
+    RowBuf b0, b1, b2;
+    if (PIPE && row + 5 * step < rows) {
+        fetch(b0, row);
+        fetch(b1, row + step);
+        fetch(b2, row + 2 * step);
+        do {
+            finish(kSure, b0, row, b0, phase);
+            finish(kSure, b1, row + step, b1, phase ^ 1);
+            finish(kSure, b2, row + 2 * step, b2, phase);
+            row += 3 * step;
+            phase ^= 1;
+        } while (row + 5 * step < rows);
     } else {
-        RowBuf b0, b1;
-        if (PIPE && row + 3 * step < rows) {
-            fetch(b0, row);
-            fetch(b1, row + step);
-            do {
-                finish(kSure, b0, row, b0, 0);
-                finish(kSure, b1, row + step, b1, 1);
-                row += 2 * step;
-            } while (row + 3 * step < rows);
-        } else {
-            fetch(b0, row);
-            if (row + step < rows) fetch(b1, row + step);
-        }
-        while (true) {
-            finish(kTested, b0, row, b0, 0);
-            if ((row += step) >= rows) break;
-            finish(kTested, b1, row, b1, 1);
-            if ((row += step) >= rows) break;
-        }
+        fetch(b0, row);
+        if (row + step < rows) fetch(b1, row + step);
+        if (row + 2 * step < rows) fetch(b2, row + 2 * step);
+    }
+    while (true) {
+        finish(kTested, b0, row, b0, phase);
+        if ((row += step) >= rows) break;
+        finish(kTested, b1, row, b1, phase ^ 1);
+        if ((row += step) >= rows) break;
+        finish(kTested, b2, row, b2, phase);
+        if ((row += step) >= rows) break;
+        finish(kTested, b0, row, b0, phase ^ 1);
+        if ((row += step) >= rows) break;
+        finish(kTested, b1, row, b1, phase);
+        if ((row += step) >= rows) break;
+        finish(kTested, b2, row, b2, phase ^ 1);
+        if ((row += step) >= rows) break;
     }
 }
 
@@ -446,16 +481,13 @@ inline void norm_launch_shape(int vecs_per_row, int preferred_vpt, int& vpt, int
 
 // Workgroups of a row kernel that walks its rows: as many as are resident at once when
 // every compute unit holds kNormResident lanes -- one workgroup per unit for wide
-// rows (workgroups of six wavefronts or more) when two further rows are in flight
-// (measured +2-4 % on 14336-wide rows; with one row in flight it costs 9 %).
-inline unsigned norm_grid(int64_t rows, int threads, int depth)
+// rows (workgroups of six wavefronts or more; measured +2-4 % on 14336-wide rows).
+inline unsigned norm_grid(int64_t rows, int threads)
 {
-    const int per_cu = (threads >= 384 && depth >= 2) ? 1 : kNormResident / threads;
+    const int per_cu = threads >= 384 ? 1 : kNormResident / threads;
     const int64_t resident = (int64_t)compute_units() * (per_cu > 0 ? per_cu : 1);
     return (unsigned)(rows < resident ? rows : resident);
 }
-
-
 
 // Calls f(std::integral_constant<int, VPT>) for vpt in {1, 2, 4}.
 template <typename F>
@@ -487,9 +519,9 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
     int vpt, threads;
-    norm_launch_shape(vecs_per_row, bits == 8 ? kNormVpt8 : kNormVpt, vpt, threads);
-    const int depth = bits == 8 ? kNormDepth8 : bits == 4 ? kNormDepth : kNormDepth56;
-    const dim3 grid(norm_grid(rows, threads, depth)), block(threads);
+    norm_launch_shape(vecs_per_row, bits == 8 ? kNormVpt8 : bits == 4 ? kNormVpt : norm_vpt56(vecs_per_row), vpt,
+                      threads);
+    const dim3 grid(norm_grid(rows, threads)), block(threads);
     const bool pipe = vecs_per_row == vpt * threads && rows >= (int64_t)grid.x * kNormPipeRows;
     auto go = [&](auto kernel) {
         return launch(kernel, grid, block, 0, st, codes, scales, n_vec_total, rows, vecs_per_row, gm, eps,
@@ -526,19 +558,23 @@ int dequant_silu_mul_impl(const void* gate_codes, const float* gate_scales, int 
         return AGOQ_ERR_ALIGN;
     const int64_t n_vec = numel / 8;
     constexpr int U = kSiUnroll;
-    const dim3 grid(blocks_for(n_vec, kSiBlock * U)), block(kSiBlock);
     hipStream_t st = (hipStream_t)stream;
     u32x4* z = (u32x4*)z_bf16;
-    auto go = [&](auto kernel) {
-        return launch(kernel, grid, block, 0, st, gate_codes, gate_scales, up_codes, up_scales, n_vec, z);
+    // workgroups of 128 lanes while a tensor's decode is several instructions per element
+    // (measured +2-4 % at 4, 5 and 6 bits; -1 to -6 % for two 8-bit tensors, which keep 256)
+    auto go = [&](auto kernel, int block) {
+        return launch(kernel, dim3(blocks_for(n_vec, block * U)), dim3(block), 0, st, gate_codes, gate_scales,
+                      up_codes, up_scales, n_vec, z);
     };
     if (fp)
-        return group == 128 ? go(act_dequant_silu_mul_kernel<4, 4, 128, U, true>)
-                            : go(act_dequant_silu_mul_kernel<4, 4, 64, U, true>);
+        return group == 128 ? go(act_dequant_silu_mul_kernel<4, 4, 128, kSiBlockNarrow, U, true>, kSiBlockNarrow)
+                            : go(act_dequant_silu_mul_kernel<4, 4, 64, kSiBlockNarrow, U, true>, kSiBlockNarrow);
     return dispatch_bits_group(gate_bits, group, [&](auto bg, auto g) {
         // the group is the same for both tensors: the inner dispatch only resolves the up width
         return dispatch_bits_group(up_bits, group, [&](auto bu, auto) {
-            return go(act_dequant_silu_mul_kernel<decltype(bg)::value, decltype(bu)::value, decltype(g)::value, U>);
+            constexpr int BG = decltype(bg)::value, BU = decltype(bu)::value, G = decltype(g)::value;
+            constexpr int B = (BG == 8 && BU == 8) ? kSiBlock : kSiBlockNarrow;
+            return go(act_dequant_silu_mul_kernel<BG, BU, G, B, U>, B);
         });
     });
 }
@@ -561,7 +597,7 @@ int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const
     const float inv_cols = 1.0f / (float)cols;
     int vpt, threads;
     norm_launch_shape(vecs_per_row, kNormFwdVpt, vpt, threads);
-    const dim3 grid(norm_grid(rows, threads, kNormFwdDepth)), block(threads);
+    const dim3 grid(norm_grid(rows, threads)), block(threads);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     const f32x4* gm = (const f32x4*)gamma;

@@ -12,14 +12,15 @@ import test_oracle_reduce_pins as reduce_pins
 import test_oracle_recompute_pins as recompute_pins
 import test_oracle_fp_pins as fp_pins
 import test_oracle_nonfinite_pins as nonfinite_pins
+import test_oracle_sr_pins as sr_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "agoq_ref.c")
 
 # (name, text in the oracle source, replacement)
 MUTANTS = [
-    ("half_away_rounding", "float r = rintf(t);", "float r = roundf(t);"),
-    ("truncation_instead_of_rounding", "float r = rintf(t);", "float r = truncf(t);"),
+    ("half_away_rounding", "r = rintf(t);", "r = roundf(t);"),
+    ("truncation_instead_of_rounding", "r = rintf(t);", "r = truncf(t);"),
     ("inv_as_reciprocal_of_scale", "const float inv = fq / amax;", "const float inv = 1.0f / scale;"),
     ("scale_by_multiplying_reciprocal", "const float scale = amax / fq;",
      "const float scale = amax * (1.0f / fq);"),
@@ -104,6 +105,28 @@ MUTANTS = [
      "        *scale = quiet_nan();\n        *inv = 0.0f;\n        return 1;"),
     ("fp_nonfinite_group_not_detected", "    if (!group_is_finite(x, G)) {\n        *scale = quiet_nan();", "    if (0) {\n        *scale = quiet_nan();"),
     ("bf16_nan_rounded_like_a_number", "    if (isnan(f))\n        return 0x7FC0u;\n", ""),
+    ("sr_rounds_to_nearest_after_the_shift", "r = floorf(shifted);", "r = rintf(shifted);"),
+    ("sr_variate_subtracted", "float shifted = t + sr_u(mode.seed, first_index + j);",
+     "float shifted = t - sr_u(mode.seed, first_index + j);"),
+    ("sr_variate_ignores_the_group_offset", "float shifted = t + sr_u(mode.seed, first_index + j);",
+     "float shifted = t + sr_u(mode.seed, j);"),
+    ("sr_one_word_per_element", "const uint32_t word = sr_word(seed, (uint64_t)i >> 2);",
+     "const uint32_t word = sr_word(seed, (uint64_t)i);"),
+    ("sr_bytes_taken_from_the_top", "const uint32_t byte = (word >> (8 * (int)(i & 3))) & 0xFFu;",
+     "const uint32_t byte = (word >> (24 - 8 * (int)(i & 3))) & 0xFFu;"),
+    ("sr_variate_can_reach_one", "return (float)byte / 256.0f;", "return (float)byte / 255.0f;"),
+    ("sr_first_multiplier_off", "h *= 0x85EBCA6Bu;", "h *= 0x85EBCA6Du;"),
+    ("sr_middle_shift_off", "h ^= h >> 13;", "h ^= h >> 15;"),
+    ("sr_seed_not_mixed", "const uint32_t key = sr_mix(seed ^ (hi * 0x9E3779B9u));",
+     "const uint32_t key = seed ^ (hi * 0x9E3779B9u);"),
+    ("sr_high_half_of_the_counter_ignored", "const uint32_t key = sr_mix(seed ^ (hi * 0x9E3779B9u));",
+     "const uint32_t key = sr_mix(seed);"),
+    ("sr_reduce_rounds_to_nearest", "return grad_reduce_any(in_codes, stride_codes, in_scales, stride_scales, K, numel, group, mode,",
+     "return grad_reduce_any(in_codes, stride_codes, in_scales, stride_scales, K, numel, group, ROUND_NEAREST,"),
+    ("sr_accumulate_drops_the_seed", "    const struct rounding mode = {1, seed};\n    return grad_accumulate_any(",
+     "    const struct rounding mode = {1, 0};\n    return grad_accumulate_any("),
+    ("sr_store_ignores_the_mode", "scales[g] = quantize_group(grad + g * group, group, 127, q, mode, g * group);",
+     "scales[g] = quantize_group(grad + g * group, group, 127, q, ROUND_NEAREST, g * group);"),
     ("dequant_uses_previous_group_scale", "const float s = scales[g];\n        for (int j = 0; j < group; ++j) {\n            float v",
      "const float s = scales[g > 0 ? g - 1 : 0];\n        for (int j = 0; j < group; ++j) {\n            float v"),
 ]
@@ -112,7 +135,7 @@ MUTANTS = [
 def pin_tests():
     """Every pin test of the two pin modules, expanded over its parametrisation."""
     cases = []
-    for mod in (quant_pins, reduce_pins, recompute_pins, fp_pins, nonfinite_pins):
+    for mod in (quant_pins, reduce_pins, recompute_pins, fp_pins, nonfinite_pins, sr_pins):
         for name, fn in inspect.getmembers(mod, inspect.isfunction):
             if not name.startswith("test_") or "ref" not in inspect.signature(fn).parameters:
                 continue
@@ -131,8 +154,14 @@ def pin_tests():
     return cases
 
 
-def killed_by(oracle_obj):
-    for fn, kwargs in pin_tests():
+def killed_by(oracle_obj, first=None):
+    """The first pin test that fails on this oracle build (None: all pass).  `first`: the pin
+    module to try before the others (the one written for the mutated function: saves running
+    every other module's pins, which pass, before the one that bites)."""
+    cases = pin_tests()
+    if first is not None:
+        cases.sort(key=lambda case: case[0].__module__ != first.__name__)
+    for fn, kwargs in cases:
         try:
             fn(ref=oracle_obj, **kwargs)
         except Exception as exc:  # an assertion, or the oracle rejecting / mangling a call
@@ -156,5 +185,5 @@ def test_planted_mistake_is_caught(tmp_path, ref, name, old, new):
                            "-w", "-shared", "-fPIC", "-o", str(lib), str(src), "-lm"])
     with warnings.catch_warnings():
         warnings.simplefilter("ignore")
-        verdict = killed_by(ref.Oracle(str(lib)))
+        verdict = killed_by(ref.Oracle(str(lib)), first=sr_pins if name.startswith("sr_") else None)
     assert verdict is not None, "no pin noticed the planted mistake %r" % name
