@@ -54,11 +54,12 @@ PEAK_HBM_GBPS = 8000.0
 GiB = 1 << 30
 # HBM bytes per launch of the K=8 reduce kernel on the step's workload, from hardware counters
 # (two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size)
-TRAFFIC_REDUCE_K8_BYTES = 2024878722
+TRAFFIC_REDUCE_K8_BYTES = 2024920722
 TRAFFIC_SOURCE = ("stored figure: rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of this command, "
                   "profiles/bench_llama8b_step_hbm_traffic.txt")
 GROUP = 128
 K_CHUNKS = 8
+MARK_MAX = 1024          # --mark-rows: most timed runs of one command (every real launch has more workgroups)
 SLOT_NAMES = ("norm1_in", "oproj_in", "norm2_in", "gate", "up")
 P = ctypes.c_void_p
 ALL_SECTIONS = ("step", "c2", "c3", "c4", "c5", "fused", "gradx", "kscan", "messages", "floor")
@@ -85,17 +86,30 @@ def rotation(bytes_each, floor=2, cap=128):
 class Rows:
     """Per-kernel rows: timing protocol, table on stderr, dict for the JSON line."""
 
-    def __init__(self, torch, launches, reps):
+    def __init__(self, torch, launches, reps, mark=None):
         self.torch = torch
         self.launches = launches
         self.reps = reps
         self.rows = {}
+        self.mark = mark            # callable(ordinal) or None: see --mark-rows
+        self.marks = 0
+        self.fresh_mark = False     # a timed run has started since the last row was added
+
+    def _mark(self):
+        """With --mark-rows, every timed run starts with one launch of the library's plain copy
+        kernel over `ordinal` workgroups: a kernel trace or counter file of the command can
+        then be cut into rows by that kernel's grid size, and a row names its ordinal."""
+        self.marks += 1
+        self.fresh_mark = True
+        if self.mark is not None:
+            self.mark(self.marks)
 
     def timed(self, fn, launches=None):
         """Median microseconds per launch over `reps` runs of back-to-back launches, events on
         the current stream (the stream every call here is launched on)."""
         torch = self.torch
         launches = launches or self.launches
+        self._mark()
         for i in range(min(10, launches)):
             fn(i)
         torch.cuda.synchronize()
@@ -116,6 +130,7 @@ class Rows:
         """Host-clock variant for launches that go to more than one stream."""
         torch = self.torch
         launches = launches or self.launches
+        self._mark()
         for i in range(min(10, launches)):
             fn(i)
         torch.cuda.synchronize()
@@ -136,6 +151,9 @@ class Rows:
                "algo_MB": round(nbytes / 1e6, 1)}
         if ok is not None:
             row["gpu_matches_oracle"] = bool(ok)
+        if self.mark is not None and self.fresh_mark:
+            row["mark"] = self.marks
+        self.fresh_mark = False
         row.update(extra)
         self.rows["%s/%s/%s" % (section, kernel, case)] = row
         print("%-9s %-28s %-46s %9.2f us %9.1f MB %8.1f GB/s %5.1f%%  %s" %
@@ -173,7 +191,17 @@ class Env:
         if self.check or not args.no_cpu_baseline:
             import oracle
             self.oracle = oracle
-        self.rows = Rows(torch, args.launches, args.reps)
+        mark = None
+        if args.mark_rows:
+            # 512 sixteen-byte items per workgroup of the copy kernel: ordinal workgroups
+            self._mark_buf = torch.zeros(2 * MARK_MAX * 512 * 16, dtype=torch.uint8, device=self.dev)
+            src, dst = P(self._mark_buf.data_ptr()), P(self._mark_buf.data_ptr() + MARK_MAX * 512 * 16)
+
+            def mark(ordinal):
+                if ordinal > MARK_MAX:
+                    raise RuntimeError("--mark-rows: more than %d timed runs" % MARK_MAX)
+                assert self.L.agoq_probe_stream(src, 16, dst, 16, 512 * ordinal, self.st) == 0
+        self.rows = Rows(torch, args.launches, args.reps, mark)
 
     def empty(self, n, dtype):
         return self.torch.empty(n, dtype=dtype, device=self.dev)
@@ -1002,6 +1030,10 @@ def main():
     ap.add_argument("--no-check", action="store_true",
                     help="skip the full-tensor comparisons of the rows with the oracle (profiler runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mark-rows", action="store_true",
+                    help="profiler runs: start every timed run with one launch of the library's copy kernel "
+                         "whose workgroup count is the run's ordinal (a row's \"mark\" in the JSON line), so "
+                         "that a kernel trace can be cut into rows")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit: gives the hardware "
                          "counters a kernel of known traffic to be scaled against")

@@ -32,6 +32,20 @@ constexpr int kNormFwdVpt = 2;      // ... the forward kernel
 // 5- and 6-bit codes (three loads per vector): two per lane on rows of up to 1024 vectors, else four
 constexpr int norm_vpt56(int vecs_per_row) { return vecs_per_row <= 1024 ? 2 : 4; }
 constexpr int kNormResident = 1024; // lanes per compute unit the grid is sized for
+// Rows of exactly 64 * kWaveRowVpt vectors (4096 columns, the hidden size of the 8B models) take
+// the wavefront-per-row kernels: measured 5-17 % faster on [8192,4096] and [4096,4096] tensors
+// than two wavefronts per row with a barrier per row (4 wavefronts x 2 workgroups per compute
+// unit; 2 x 4 and 8 x 1 are 2-8 % slower, more workgroups per unit slower still).
+constexpr int kWaveRowVpt = 8;
+constexpr int kWaveRowVecs = 64 * kWaveRowVpt;
+constexpr int kWaveRowWaves = 4;    // wavefronts (rows in progress) per workgroup
+constexpr int kWaveRowPerCu = 2;    // workgroups per compute unit the grid is sized for
+// With few rows per resident wavefront the kernels above win (half the work per wavefront on
+// the one row it ever sees): the recompute kernel changes over at four rows per resident
+// wavefront (+6 to +14 % at 8192 rows, -5 to +4 % at 4096), the forward kernel at half a
+// row (+5 to +15 % from 1024 to 8192 rows, -15 % at 512).
+constexpr int kWaveRowMinRoundsRecompute2 = 8;      // twice the rows per resident wavefront
+constexpr int kWaveRowMinRoundsForward2 = 1;
 
 // Sum of the per-wavefront partial sums of a workgroup, in wavefront order.
 __device__ __forceinline__ float block_sum(float wave_total, float* wave_part)
@@ -230,6 +244,89 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     }
 }
 
+// The same for rows of exactly kWaveRowVecs vectors, one wavefront per row: the row sum is a
+// reduction within the wavefront, so the row loop has no barrier and the wavefronts of a
+// workgroup drift apart freely (one's stores overlap another's loads).  A lane owns 8 vectors
+// of every row; gamma would take 64 registers per lane and waits in LDS instead, staged once
+// per workgroup.  Three rows per wavefront are in flight, as in the kernel above.
+template <int BITS, int GROUP, bool FP = false>
+__global__ __launch_bounds__(kWaveRowWaves * 64) void act_dequant_rmsnorm_wave_kernel(
+    const void* __restrict__ codes, const float* __restrict__ scales, int64_t n_vec_total, int64_t rows,
+    const f32x4* __restrict__ gamma, float eps, float inv_cols, u32x4* __restrict__ y, float* __restrict__ r_out)
+{
+    constexpr int LANES = GROUP / 8;
+    constexpr int VPT = kWaveRowVpt;
+    __shared__ f32x4 g_lo[kWaveRowVecs], g_hi[kWaveRowVecs];
+    for (int v = threadIdx.x; v < kWaveRowVecs; v += kWaveRowWaves * 64) {
+        g_lo[v] = gamma[2 * v];
+        g_hi[v] = gamma[2 * v + 1];
+    }
+    __syncthreads();                                    // the only barrier: before any wavefront leaves
+    const unsigned lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t step = (int64_t)gridDim.x * kWaveRowWaves;
+    int64_t row = (int64_t)blockIdx.x * kWaveRowWaves + wave;     // uniform over the wavefront
+    if (row >= rows) return;
+    struct RowBuf {
+        Codes8<BITS> c[VPT];
+        float sc[VPT];
+    };
+    constexpr int kHighBytes = BITS == 6 ? 2 : 1;     // bytes per vector in the high-bit plane
+    const uint8_t* const high = (const uint8_t*)codes + n_vec_total * 4;
+    auto fetch = [&](RowBuf& b, int64_t r) {
+        const int64_t first = r * kWaveRowVecs;
+        const void* row_lo = (const uint8_t*)codes + first * (BITS == 8 ? 8 : 4);
+        const void* row_hi = high + first * kHighBytes;
+        const float* row_sc = scales + first / LANES;               // rows are whole groups
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const unsigned v = lane + 64u * u;
+            b.c[u] = load_row_codes8<BITS>(row_lo, row_hi, v);
+            b.sc[u] = ld<false>(at_bytes(row_sc, v / LANES * 4u));
+        }
+    };
+    auto finish = [&](const RowBuf& b, int64_t r, RowBuf& refill) {
+        u32 xp[VPT][4];
+        float ss = 0.0f;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            dequant8_packed<BITS, FP>(b.c[u], b.sc[u], xp[u]);
+            ss = sumsq8(xp[u], ss);
+        }
+        const int64_t next = r + 3 * step;
+        if (next < rows) fetch(refill, next);                      // the same for every lane
+        // The row waits for its sum as the packed pairs: without this the compiler keeps the
+        // unpacked floats of the first pass instead, 64 registers more, and the kernel no
+        // longer fits two workgroups per compute unit.
+#pragma unroll
+        for (int u = 0; u < VPT; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(xp[u][k]));
+        const float total = wave_sum(ss);
+        const float rr = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
+        const float rinv = __fdiv_rn(1.0f, rr);
+        if (lane == 0) r_out[r] = rr;
+        u32x4* const y_row = y + r * kWaveRowVecs;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const unsigned v = lane + 64u * u;
+            st<true>(at_bytes(y_row, v * 16u), norm_out8(xp[u], rinv, g_lo[v], g_hi[v]));
+        }
+    };
+    RowBuf b0, b1, b2;
+    fetch(b0, row);
+    if (row + step < rows) fetch(b1, row + step);
+    if (row + 2 * step < rows) fetch(b2, row + 2 * step);
+    while (true) {
+        finish(b0, row, b0);
+        if ((row += step) >= rows) break;
+        finish(b1, row, b1);
+        if ((row += step) >= rows) break;
+        finish(b2, row, b2);
+        if ((row += step) >= rows) break;
+    }
+}
+
 // SiLU & Multiply recompute: z = bf16(u' * g' * sigmoid(g')), elementwise over the two
 // stored tensors (which may have different code widths).  The kernel is bound by vector
 // instructions as much as by memory (two decodes, exp and rcp at a quarter of the rate), so a
@@ -423,6 +520,76 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     }
 }
 
+// The same for rows of exactly kWaveRowVecs vectors, one wavefront per row (see the recompute
+// kernel of that shape).
+template <int BITS, int GROUP, bool FP = false>
+__global__ __launch_bounds__(kWaveRowWaves * 64) void rmsnorm_fwd_quant_wave_kernel(
+    const u32x4* __restrict__ x, int64_t n_vec_total, int64_t rows, const f32x4* __restrict__ gamma, float eps,
+    float inv_cols, u32x4* __restrict__ y, float* __restrict__ r_out, void* __restrict__ codes,
+    float* __restrict__ scales)
+{
+    constexpr int LANES = GROUP / 8;
+    constexpr int VPT = kWaveRowVpt;
+    __shared__ f32x4 g_lo[kWaveRowVecs], g_hi[kWaveRowVecs];
+    for (int v = threadIdx.x; v < kWaveRowVecs; v += kWaveRowWaves * 64) {
+        g_lo[v] = gamma[2 * v];
+        g_hi[v] = gamma[2 * v + 1];
+    }
+    __syncthreads();                                    // the only barrier: before any wavefront leaves
+    const unsigned lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t step = (int64_t)gridDim.x * kWaveRowWaves;
+    int64_t row = (int64_t)blockIdx.x * kWaveRowWaves + wave;     // uniform over the wavefront
+    if (row >= rows) return;
+    struct RowBuf {
+        u32x4 v[VPT];
+    };
+    auto fetch = [&](RowBuf& b, int64_t r) {
+        const u32x4* const x_row = x + r * kWaveRowVecs;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) b.v[u] = ld<true>(at_bytes(x_row, (lane + 64u * u) * 16u));
+    };
+    auto finish = [&](const RowBuf& b, int64_t r, RowBuf& refill) {
+        u32x4 v[VPT];
+        float ss = 0.0f;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            v[u] = b.v[u];
+            float f[8];
+            const u32 m = group_max_bits<LANES>(unpack8_bf16(v[u], f));
+            quantize_store8<BITS, GROUP, FP, true>(f, m, r * kWaveRowVecs + lane + 64 * u, n_vec_total, true,
+                                                      codes, scales);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ss = __fmaf_rn(f[j], f[j], ss);
+        }
+        const int64_t next = r + 3 * step;
+        if (next < rows) fetch(refill, next);                      // the same for every lane
+        const float total = wave_sum(ss);
+        const float rr = __fsqrt_rn(__fmaf_rn(total, inv_cols, eps));
+        const float rinv = __fdiv_rn(1.0f, rr);
+        if (lane == 0 && r_out) r_out[r] = rr;
+        u32x4* const y_row = y + r * kWaveRowVecs;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const unsigned c = lane + 64u * u;
+            const u32 xp[4] = {v[u][0], v[u][1], v[u][2], v[u][3]};
+            st<true>(at_bytes(y_row, c * 16u), norm_out8(xp, rinv, g_lo[c], g_hi[c]));
+        }
+    };
+    RowBuf b0, b1, b2;
+    fetch(b0, row);
+    if (row + step < rows) fetch(b1, row + step);
+    if (row + 2 * step < rows) fetch(b2, row + 2 * step);
+    while (true) {
+        finish(b0, row, b0);
+        if ((row += step) >= rows) break;
+        finish(b1, row, b1);
+        if ((row += step) >= rows) break;
+        finish(b2, row, b2);
+        if ((row += step) >= rows) break;
+    }
+}
+
 // SiLU & Multiply forward + quantize(gate), quantize(up), elementwise.
 //   z = bf16(up * gate * sigmoid(gate))
 template <int BITS_G, int BITS_U, int GROUP, int UNROLL, bool FP = false>
@@ -489,6 +656,23 @@ inline unsigned norm_grid(int64_t rows, int threads)
     return (unsigned)(rows < resident ? rows : resident);
 }
 
+// Workgroups of a wavefront-per-row kernel: kWaveRowPerCu per compute unit, or fewer when that
+// already gives every row a wavefront.
+inline unsigned wave_row_grid(int64_t rows)
+{
+    const int64_t resident = (int64_t)compute_units() * kWaveRowPerCu;
+    const int64_t needed = (rows + kWaveRowWaves - 1) / kWaveRowWaves;
+    return (unsigned)(needed < resident ? needed : resident);
+}
+
+// Whether a tensor of `rows` rows of vecs_per_row vectors goes to a wavefront-per-row kernel
+// that changes over at min_rounds2 / 2 rows per resident wavefront.
+inline bool wave_row_shape(int64_t rows, int vecs_per_row, int min_rounds2)
+{
+    const int64_t resident_waves = (int64_t)compute_units() * kWaveRowPerCu * kWaveRowWaves;
+    return vecs_per_row == kWaveRowVecs && 2 * rows >= min_rounds2 * resident_waves;
+}
+
 // Calls f(std::integral_constant<int, VPT>) for vpt in {1, 2, 4}.
 template <typename F>
 int dispatch_vpt(int vpt, F&& f)
@@ -518,6 +702,18 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
     hipStream_t st = (hipStream_t)stream;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
+    if (wave_row_shape(rows, vecs_per_row, kWaveRowMinRoundsRecompute2)) {
+        auto go = [&](auto kernel) {
+            return launch(kernel, dim3(wave_row_grid(rows)), dim3(kWaveRowWaves * 64), 0, st, codes, scales,
+                          n_vec_total, rows, gm, eps, inv_cols, y, r_out);
+        };
+        if (fp)
+            return group == 128 ? go(act_dequant_rmsnorm_wave_kernel<4, 128, true>)
+                                : go(act_dequant_rmsnorm_wave_kernel<4, 64, true>);
+        return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+            return go(act_dequant_rmsnorm_wave_kernel<decltype(b)::value, decltype(g)::value>);
+        });
+    }
     int vpt, threads;
     norm_launch_shape(vecs_per_row, bits == 8 ? kNormVpt8 : bits == 4 ? kNormVpt : norm_vpt56(vecs_per_row), vpt,
                       threads);
@@ -595,13 +791,25 @@ int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const
     const int vecs_per_row = (int)(cols / 8);
     const int64_t n_vec_total = rows * vecs_per_row;
     const float inv_cols = 1.0f / (float)cols;
-    int vpt, threads;
-    norm_launch_shape(vecs_per_row, kNormFwdVpt, vpt, threads);
-    const dim3 grid(norm_grid(rows, threads)), block(threads);
     hipStream_t st = (hipStream_t)stream;
     const u32x4* x = (const u32x4*)x_bf16;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
+    if (wave_row_shape(rows, vecs_per_row, kWaveRowMinRoundsForward2)) {
+        auto go = [&](auto kernel) {
+            return launch(kernel, dim3(wave_row_grid(rows)), dim3(kWaveRowWaves * 64), 0, st, x, n_vec_total, rows,
+                          gm, eps, inv_cols, y, r_out, codes, scales);
+        };
+        if (fp)
+            return group == 128 ? go(rmsnorm_fwd_quant_wave_kernel<4, 128, true>)
+                                : go(rmsnorm_fwd_quant_wave_kernel<4, 64, true>);
+        return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+            return go(rmsnorm_fwd_quant_wave_kernel<decltype(b)::value, decltype(g)::value>);
+        });
+    }
+    int vpt, threads;
+    norm_launch_shape(vecs_per_row, kNormFwdVpt, vpt, threads);
+    const dim3 grid(norm_grid(rows, threads)), block(threads);
     const bool pipe = vecs_per_row == vpt * threads && rows >= (int64_t)grid.x * kNormPipeRows;
     auto go = [&](auto kernel) {
         return launch(kernel, grid, block, 0, st, x, n_vec_total, rows, vecs_per_row, gm, eps, inv_cols, y,

@@ -307,7 +307,11 @@ def test_fp4_rmsnorm_forward_with_quantized_input(agoq, ref, rows, cols, group):
 # without a test) plus a tail of every length: the grid is one or two workgroups per compute
 # unit on 14336-wide rows, eight on 4096-wide ones.
 MANY_ROWS = [(2048 + 52, 14336, 4), (2048 + 52, 14336, 8), (4096 + 700, 14336, 5), (4096 + 700, 14336, 6),
-             (16384 + 1031, 4096, 4), (8192 + 515, 4096, 8), (6 * 768 + 5, 5120, 8)]
+             (16384 + 1031, 4096, 4), (8192 + 515, 4096, 8), (6 * 768 + 5, 5120, 8),
+             # 4096-wide rows take the wavefront-per-row kernels (four rows per workgroup, two
+             # workgroups per compute unit): a single row, fewer rows than a workgroup has
+             # wavefronts, one row per wavefront with a ragged last workgroup, several rounds
+             (1, 4096, 4), (3, 4096, 6), (2048 + 3, 4096, 5), (4096 + 3, 4096, 6), (6144 + 1, 4096, 5)]
 
 
 @pytest.mark.parametrize("rows,cols,bits", MANY_ROWS)
