@@ -62,7 +62,7 @@ K_CHUNKS = 8
 MARK_MAX = 1024          # --mark-rows: most timed runs of one command (every real launch has more workgroups)
 SLOT_NAMES = ("norm1_in", "oproj_in", "norm2_in", "gate", "up")
 P = ctypes.c_void_p
-ALL_SECTIONS = ("step", "c2", "c3", "c4", "c5", "fused", "gradx", "kscan", "messages", "floor")
+ALL_SECTIONS = ("step", "c2", "c3", "c4", "c5", "fused", "gradx", "sr", "kscan", "messages", "floor")
 DEFAULT_SECTIONS = ",".join(ALL_SECTIONS)
 
 
@@ -724,6 +724,82 @@ def section_gradx(env):
     torch.cuda.empty_cache()
 
 
+def section_sr(env):
+    """The stochastic-rounding entry points (not used by the paper: an extension) on the 8B
+    shapes, each compared whole with the oracle's independent implementation of the same
+    counter-based generator."""
+    import numpy as np
+    torch, L, st, R, agoq, wl = env.torch, env.L, env.st, env.rows, env.agoq, env.wl
+    seed = 0x5EED1234
+    ca = wl.CONFIGS["llama8b_act"]
+    sh = ca["acts"]["F"]
+    t = ActTensor(env, sh["rows"], sh["cols"], ca["seed"], ca["dist"], ca["outlier_frac"], ca["outlier_scale"])
+    n, group = t.n, ca["group"]
+    nx = rotation(2 * n)
+    xs = t.copies(nx)
+    for bits in (4, 8):
+        nc = rotation(n * bits // 8)
+        cs = [env.empty(n * bits // 8, torch.uint8) for _ in range(nc)]
+        ss = [env.empty(n // group, torch.float32) for _ in range(nc)]
+        m = max(nx, nc)
+        qa = [(P(xs[i % nx].data_ptr()), n, group, bits, seed, P(cs[i % nc].data_ptr()), P(ss[i % nc].data_ptr()), st)
+              for i in range(m)]
+        ok = None
+        if env.check:
+            assert L.agoq_act_quant_sr(*qa[0]) == 0
+            torch.cuda.synchronize()
+            oc, os_ = env.oracle.act_quant_sr(bits_of(torch, t.base), group, bits, seed)
+            ok = np.array_equal(cs[0].cpu().numpy(), oc) and same_u32(torch, ss[0], os_)
+        us = R.timed(lambda i: L.agoq_act_quant_sr(*qa[i % m]))
+        R.add("sr", "act_quant_sr", "F[%d,%d] b%d g%d" % (t.rows, t.cols, bits, group), us,
+              algo_bytes_act(n, bits, group), ok)
+        del cs, ss
+    del xs, t
+    torch.cuda.empty_cache()
+
+    c = wl.CONFIGS["llama8b_grad"]
+    n, group, K = c["n"], c["group"], c["K"]
+    g = [wl.grad_device(n, c["seed"] + i, c["sigma"], c["spike_frac"], c["spike_scale"]) for i in range(2)]
+    nout = rotation(n, floor=3)
+    ocs = [env.empty(n, torch.int8) for _ in range(nout)]
+    oss = [env.empty(n // group, torch.float32) for _ in range(nout)]
+    launches = max(20, min(R.launches, int(2e9 / n)))
+    ok = None
+    if env.check:
+        agoq.grad_quant(g[0], group, codes=ocs[0], scales=oss[0], sr_seed=seed)
+        torch.cuda.synchronize()
+        wc, ws = env.oracle.grad_quant_sr(g[0].cpu().numpy(), group, seed)
+        ok = np.array_equal(ocs[0].cpu().numpy(), wc) and same_u32(torch, oss[0], ws)
+    us = R.timed(lambda i: agoq.grad_quant(g[i % 2], group, codes=ocs[i % nout], scales=oss[i % nout], sr_seed=seed),
+                 launches)
+    R.add("sr", "grad_quant_sr", "n=%d g%d" % (n, group), us, algo_bytes_grad_quant(n, group), ok)
+    # accumulate: the stored gradient is the nearest-rounding store of g[1]
+    mc, ms = agoq.grad_quant(g[1], group)
+    ok = None
+    if env.check:
+        agoq.grad_accumulate(mc, ms, g[0], group, out_codes=ocs[0], out_scales=oss[0], sr_seed=seed)
+        torch.cuda.synchronize()
+        wc, ws = env.oracle.grad_accumulate_sr(mc.cpu().numpy(), ms.cpu().numpy(), g[0].cpu().numpy(), group, seed)
+        ok = np.array_equal(ocs[0].cpu().numpy(), wc) and same_u32(torch, oss[0], ws)
+    us = R.timed(lambda i: agoq.grad_accumulate(mc, ms, g[i % 2], group, out_codes=ocs[i % nout],
+                                                out_scales=oss[i % nout], sr_seed=seed), launches)
+    R.add("sr", "grad_accumulate_sr", "fp32 addend n=%d g%d" % (n, group), us, n * 6 + 8 * (n // group), ok)
+    del g, mc, ms
+    torch.cuda.empty_cache()
+    codes, scales = quantized_chunks(env, K, n, group, c["seed"] + 100, c["sigma"], c["spike_frac"], c["spike_scale"])
+    ok = None
+    if env.check:
+        agoq.grad_reduce_requant(codes, scales, n, group, out_codes=ocs[0], out_scales=oss[0], sr_seed=seed)
+        torch.cuda.synchronize()
+        wc, ws = env.oracle.grad_reduce_requant_sr(codes.cpu().numpy(), scales.cpu().numpy(), n, group, seed)
+        ok = np.array_equal(ocs[0].cpu().numpy(), wc) and same_u32(torch, oss[0], ws)
+    us = R.timed(lambda i: agoq.grad_reduce_requant(codes, scales, n, group, out_codes=ocs[i % nout],
+                                                    out_scales=oss[i % nout], sr_seed=seed), launches)
+    R.add("sr", "grad_reduce_requant_sr", "K=%d n=%d g%d" % (K, n, group), us, algo_bytes_reduce(n, K, group), ok)
+    del codes, scales, ocs, oss
+    torch.cuda.empty_cache()
+
+
 def section_kscan(env):
     """Other chunk counts on the 8B shard size (random codes and scales)."""
     import numpy as np
@@ -1070,7 +1146,7 @@ def main():
     step = section_step(env, args) if "step" in sections else None
     torch.cuda.empty_cache()
     for name, fn in (("c2", section_c2), ("c3", section_c3), ("c4", section_c4), ("c5", section_c5),
-                     ("fused", section_fused), ("gradx", section_gradx), ("kscan", section_kscan),
+                     ("fused", section_fused), ("gradx", section_gradx), ("sr", section_sr), ("kscan", section_kscan),
                      ("messages", section_messages), ("floor", section_floor)):
         if name in sections:
             fn(env)
