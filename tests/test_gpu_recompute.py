@@ -311,7 +311,8 @@ MANY_ROWS = [(2048 + 52, 14336, 4), (2048 + 52, 14336, 8), (4096 + 700, 14336, 5
              # 4096-wide rows take the wavefront-per-row kernels (four rows per workgroup, two
              # workgroups per compute unit): a single row, fewer rows than a workgroup has
              # wavefronts, one row per wavefront with a ragged last workgroup, several rounds
-             (1, 4096, 4), (3, 4096, 6), (2048 + 3, 4096, 5), (4096 + 3, 4096, 6), (6144 + 1, 4096, 5)]
+             (1, 4096, 4), (3, 4096, 6), (2048 + 3, 4096, 5), (4096 + 3, 4096, 6), (6144 + 1, 4096, 5),
+             (8192 + 7, 4096, 5), (8192 + 2, 4096, 6)]
 
 
 @pytest.mark.parametrize("rows,cols,bits", MANY_ROWS)
@@ -332,6 +333,36 @@ def test_row_kernels_with_many_rows_per_workgroup(agoq, ref, rows, cols, bits):
     check_close_bf16(bits_of(y), want_y)
     want_y2, want_r2 = ref.act_dequant_rmsnorm(wc, ws, rows, cols, group, bits, gamma, eps)
     y2, r2 = agoq.act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, torch.from_numpy(gamma).cuda(), eps)
+    torch.cuda.synchronize()
+    assert np.allclose(r2.cpu().numpy(), want_r2, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y2), want_y2)
+
+
+# The wavefront-per-row kernels (4096-wide rows, many rows) at group 64 and on E2M1 codes: the
+# forward kernel's stored form bit for bit, both layer outputs to the bar of the fused kernels.
+@pytest.mark.parametrize("group,bits,fp4", [(64, 4, False), (64, 6, False), (64, 8, False), (64, 4, True), (128, 4, True)])
+def test_wavefront_per_row_kernels_other_groups_and_code_books(agoq, ref, group, bits, fp4):
+    rows, cols = 8192 + 5, 4096
+    x = wl.act_host(rows, cols, 33000 + group + bits, "student_t3", 40, 50.0)
+    x[rows - 2] = 0
+    rng = np.random.default_rng(group + bits)
+    gamma = (1.0 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    eps = 1e-5
+    dg = torch.from_numpy(gamma).cuda()
+    y, r, codes, scales = agoq.rmsnorm_fwd_quant(dev_bf16(x), dg, eps, group, bits, fp4=fp4)
+    torch.cuda.synchronize()
+    wc, ws = ref.fp4_act_quant(x, group) if fp4 else ref.act_quant(x, group, bits)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+    want_y, want_r = ref.rmsnorm_fwd(x, rows, cols, gamma, eps)
+    assert np.allclose(r.cpu().numpy(), want_r, rtol=2e-6, atol=0)
+    check_close_bf16(bits_of(y), want_y)
+    if fp4:
+        xd = ref.fp4_act_dequant(wc, ws, rows * cols, group)
+        want_y2, want_r2 = ref.rmsnorm_fwd(xd, rows, cols, gamma, eps)
+    else:
+        want_y2, want_r2 = ref.act_dequant_rmsnorm(wc, ws, rows, cols, group, bits, gamma, eps)
+    y2, r2 = agoq.act_dequant_rmsnorm(codes, scales, rows, cols, group, bits, dg, eps, fp4=fp4)
     torch.cuda.synchronize()
     assert np.allclose(r2.cpu().numpy(), want_r2, rtol=2e-6, atol=0)
     check_close_bf16(bits_of(y2), want_y2)
