@@ -857,16 +857,29 @@ def section_messages(env):
         po = [P(t.data_ptr()) for t in out]
         prc, prs, poc, pos = P(rc.data_ptr()), P(rs.data_ptr()), P(oc.data_ptr()), P(osc.data_ptr())
 
-        def message(i):
+        def message(i, stream=st):
             r = i % nrot
-            bad = L.agoq_grad_quant(pg[r], n, group, pc[r], ps[r], st)
-            bad |= L.agoq_grad_reduce_requant(prc, ns, prs, ns // group, K, ns, group, poc, pos, st)
-            bad |= L.agoq_grad_dequant(pc[r], ps[r], n, group, po[i % 2], st)
+            bad = L.agoq_grad_quant(pg[r], n, group, pc[r], ps[r], stream)
+            bad |= L.agoq_grad_reduce_requant(prc, ns, prs, ns // group, K, ns, group, poc, pos, stream)
+            bad |= L.agoq_grad_dequant(pc[r], ps[r], n, group, po[i % 2], stream)
             assert bad == 0
         launches = max(5, min(R.launches, int(4e9 / n)))
         us = R.timed(message, launches)
-        R.add("messages", "quant+reduce+dequant", "n=2^%d (fp32 %d MiB) K=8" % (log2n, 4 * n >> 20), us,
-              2 * algo_bytes_grad_quant(n, group) + algo_bytes_reduce(ns, K, group))
+        nbytes = 2 * algo_bytes_grad_quant(n, group) + algo_bytes_reduce(ns, K, group)
+        case = "n=2^%d (fp32 %d MiB) K=8" % (log2n, 4 * n >> 20)
+        R.add("messages", "quant+reduce+dequant", case, us, nbytes)
+        if log2n <= 20:
+            # launch-latency bound: the same three kernels, 16 messages captured in a HIP graph
+            # (the library neither allocates nor synchronizes, so a caller may capture it)
+            per = 16
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                cap = P(torch.cuda.current_stream().cuda_stream)
+                for i in range(per):
+                    message(i, cap)
+            us = R.timed(lambda i: graph.replay(), max(5, launches // per)) / per
+            R.add("messages", "quant+reduce+dequant, graph", case, us, nbytes)
+            del graph
         del g, codes, scales, out, rc, rs, oc, osc
         torch.cuda.empty_cache()
 
