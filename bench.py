@@ -1010,6 +1010,35 @@ def section_step(env, args):
     red_ms = sum(a.elapsed_time(b) for a, b in red_events) / len(red_events)
     red_gbps = bytes_red / (red_ms * 1e-3) / 1e9
 
+    # The same step with the activations as ten single-tensor calls (a forward pass produces
+    # the five tensors at five different times, so a caller may not be able to batch them):
+    # reported beside `value`, not part of it.
+    P_ = ctypes.c_void_p
+    L, st = env.L, env.st
+    qcalls = [(P_(x.data_ptr()), x.numel(), GROUP, b, P_(c.data_ptr()), P_(s_.data_ptr()), st)
+              for x, b, c, s_ in zip(acts, act_bits, act_codes, act_scales)]
+    dcalls = [(P_(c.data_ptr()), P_(s_.data_ptr()), y.numel(), GROUP, b, P_(y.data_ptr()), st)
+              for y, b, c, s_ in zip(act_out, act_bits, act_codes, act_scales)]
+
+    def step_single():
+        bad = 0
+        for a in qcalls:
+            bad |= L.agoq_act_quant(*a)
+        agoq.grad_quant(grad, GROUP, codes=g_codes, scales=g_scales, stream=stream)
+        agoq.grad_reduce_requant(in_codes, in_scales, n_grad, GROUP, out_codes=r_codes,
+                                 out_scales=r_scales, stream=stream)
+        for a in dcalls:
+            bad |= L.agoq_act_dequant(*a)
+        assert bad == 0
+    for _ in range(args.warmup):
+        step_single()
+    torch.cuda.synchronize()
+    t_single = time.perf_counter()
+    for _ in range(args.steps):
+        step_single()
+    torch.cuda.synchronize()
+    single_s = (time.perf_counter() - t_single) / args.steps
+
     # per-kernel breakdown of the step (separate passes, not part of `value`)
     ev = {k: [] for k in ("t0", "t1", "t2", "t3", "t4")}
     for _ in range(min(args.steps, 20)):
@@ -1032,6 +1061,10 @@ def section_step(env, args):
     return {
         "value": round(value, 1), "ms_per_step": round(ms_per_step, 4), "bitmap": bitmap,
         "bytes_step": bytes_step, "cpu": cpu,
+        "per_tensor_calls": {"value": round(bytes_step / single_s / 1e9, 1), "ms_per_step": round(single_s * 1e3, 4),
+                             "launches_per_step": 12,
+                             "note": "the same step with the five activations quantized and dequantized by "
+                                     "single-tensor calls instead of one layer launch each"},
         "roofline": {
             "bound": "hbm", "kernel": "grad_reduce_kernel<128,8>",
             "achieved": round(red_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -1188,6 +1221,7 @@ def main():
         },
         "frac_of_peak": round(step["value"] / PEAK_HBM_GBPS, 4) if step else None,
         "roofline": step["roofline"] if step else None,
+        "step_per_tensor_calls": step["per_tensor_calls"] if step else None,
         "kernels": env.rows.rows,
         "rows_checked_against_oracle": len(checked),
         "rows_matching_oracle": sum(1 for c in checked if c),
