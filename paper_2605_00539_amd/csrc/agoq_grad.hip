@@ -105,13 +105,13 @@ __device__ __forceinline__ void reduce_term(float (&acc)[16], const u32x4& c, fl
 // of the lane issued before the first is needed, then one vector after the other is summed,
 // requantized and stored.
 constexpr int kReducePrioFromK = 16;   // chunk count from which the loads are issued at raised priority
-template <int GROUP, int KT, bool FP, int BLOCK, int RU>
+template <int GROUP, int KT, bool FP, int BLOCK, int RU, bool SR = false>
 __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __restrict__ in_codes,
                                                      int64_t stride_codes,
                                                      const float* __restrict__ in_scales,
                                                      int64_t stride_scales, int64_t n_vec,
                                                      u32x4* __restrict__ out_codes,
-                                                     float* __restrict__ out_scales)
+                                                     float* __restrict__ out_scales, u32 seed)
 {
     constexpr int LANES = GROUP / 16;
     const int64_t base = (int64_t)blockIdx.x * (BLOCK * RU) + threadIdx.x;
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(BLOCK) void grad_reduce_kernel(const int8_t* __rest
         for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
 #pragma unroll
         for (int k = 0; k < KT; ++k) reduce_term<FP>(acc, c[u][k], s[u][k]);
-        reduce_finish<GROUP, FP>(acc, vi, vi < n_vec, out_codes, out_scales);
+        reduce_finish<GROUP, FP, SR>(acc, vi, vi < n_vec, out_codes, out_scales, seed);
     }
 }
 
@@ -236,23 +236,28 @@ struct ReduceArgs {
     u32 seed;            // stochastic rounding only
 };
 
-template <int GROUP, int KT, bool FP, int BLOCK, int RU>
+template <int GROUP, int KT, bool FP, int BLOCK, int RU, bool SR = false>
 int launch_reduce_kt(const ReduceArgs& a, size_t lds)
 {
-    return launch(grad_reduce_kernel<GROUP, KT, FP, BLOCK, RU>, dim3(blocks_for(a.n_vec, BLOCK * RU)),
+    return launch(grad_reduce_kernel<GROUP, KT, FP, BLOCK, RU, SR>, dim3(blocks_for(a.n_vec, BLOCK * RU)),
                   dim3(BLOCK), lds, a.st, a.in_codes, a.stride_codes, a.in_scales, a.stride_scales,
-                  a.n_vec, a.out_codes, a.out_scales);
+                  a.n_vec, a.out_codes, a.out_scales, a.seed);
 }
 
 template <int GROUP, bool FP, bool SR>
 int launch_reduce_group(const ReduceArgs& a)
 {
-    // the stochastic variant runs the run-time-K kernel for every chunk count
-    if constexpr (SR)
+    const bool large = a.n_vec >= kReduceTwoVectorsFrom;
+    // the stochastic variant has the compile-time shapes of K = 8 only, and runs the
+    // run-time-K kernel for every other chunk count
+    if constexpr (SR) {
+        if (a.K == 8)
+            return large ? launch_reduce_kt<GROUP, 8, FP, 256, 2, true>(a, kTwoPerCuLds)
+                         : launch_reduce_kt<GROUP, 8, FP, 512, 1, true>(a, kTwoPerCuLds);
         return launch(grad_reduce_anyk_kernel<GROUP, FP, true>, dim3(blocks_for(a.n_vec, kAnyKBlock)),
                       dim3(kAnyKBlock), 0, a.st, a.in_codes, a.stride_codes, a.in_scales, a.stride_scales, a.K,
                       a.n_vec, a.out_codes, a.out_scales, a.seed);
-    const bool large = a.n_vec >= kReduceTwoVectorsFrom;
+    }
     switch (a.K) {
     case 1: return launch_reduce_kt<GROUP, 1, FP, 256, 2>(a, 0);
     case 2: return launch_reduce_kt<GROUP, 2, FP, 256, 2>(a, 0);

@@ -72,3 +72,26 @@ def test_reduce_around_the_two_vector_threshold(agoq, ref, K, group):
         assert np.array_equal(oc.cpu().numpy(), wc), (numel, "codes")
         assert same_f32(osc.cpu().numpy(), ws), (numel, "scales")
         del dc, ds, oc, osc
+
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_stochastic_reduce_around_the_two_vector_threshold(agoq, ref, group):
+    # K = 8 is the one chunk count whose compile-time shapes (one and two vectors per lane) also
+    # exist for stochastic rounding: both sides of the size threshold, and K = 7 (run-time K)
+    edge = 2500000 * 16 // 2048 * 2048
+    rng = np.random.default_rng(77 + group)
+    for K, numel in ((8, edge - group), (8, edge + 37 * group), (7, edge + 37 * group)):
+        stride_c = numel + 32
+        stride_s = numel // group + 3
+        codes = rng.integers(-127, 128, size=(K, stride_c), dtype=np.int8)
+        scales = (rng.random((K, stride_s), dtype=np.float32) * 1e-3 + 1e-6).astype(np.float32)
+        scales[:, ::97] = 0.0
+        seed = 0xABCD0000 + K
+        wc, ws = ref.grad_reduce_requant_sr(codes, scales, numel, group, seed)
+        dc = torch.from_numpy(codes).cuda()
+        ds = torch.from_numpy(scales).cuda()
+        oc, osc = agoq.grad_reduce_requant(dc, ds, numel, group, sr_seed=seed)
+        torch.cuda.synchronize()
+        assert np.array_equal(oc.cpu().numpy(), wc), (K, numel, "codes")
+        assert same_f32(osc.cpu().numpy(), ws), (K, numel, "scales")
+        del dc, ds, oc, osc
