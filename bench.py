@@ -566,10 +566,16 @@ def section_fused(env):
     c = env.wl.CONFIGS["stage_sweep"]
     torch, L, st, R, group = env.torch, env.L, env.st, env.rows, c["group"]
     eps = 1e-5
-    for name, cols in (("H", c["hidden"]), ("F", c["ffn"])):
-        rows_ = c["rows"]
-        t = ActTensor(env, rows_, cols, c["seed"], c["dist"], c["outlier_frac"], c["outlier_scale"])
-        act_single(env, "fused", name, t, [group], [5, 6])
+    c32 = env.wl.CONFIGS["llama32b_act"]
+    n32 = c32["acts"]["A"]
+    # H, F: the seq-8192 tensors of the stage sweep, all four fused calls at every width;
+    # N: the norm input of the 32B-shaped layer (5120 wide), the two RMSNorm calls at 4 and 8 bits
+    for name, rows_, cols, widths, norm_only, cf in (("H", c["rows"], c["hidden"], (4, 5, 6, 8), False, c),
+                                                     ("F", c["rows"], c["ffn"], (4, 5, 6, 8), False, c),
+                                                     ("N", n32["rows"], n32["cols"], (4, 8), True, c32)):
+        t = ActTensor(env, rows_, cols, cf["seed"], cf["dist"], cf["outlier_frac"], cf["outlier_scale"])
+        if not norm_only:
+            act_single(env, "fused", name, t, [group], [5, 6])
         n = t.n
         nx = rotation(2 * n)
         xs = t.copies(nx)
@@ -577,7 +583,7 @@ def section_fused(env):
         gamma = 0.5 + torch.rand(cols, dtype=torch.float32, device=env.dev,
                                  generator=torch.Generator(device=env.dev).manual_seed(c["seed"]))
         rs = [env.empty(rows_, torch.float32) for _ in range(4)]
-        for bits in (4, 5, 6, 8):
+        for bits in widths:
             nc = rotation(n * bits // 8)
             cs = [env.empty(n * bits // 8, torch.uint8) for _ in range(nc)]
             ss = [env.empty(n // group, torch.float32) for _ in range(nc)]
@@ -603,13 +609,14 @@ def section_fused(env):
                 hx0, hx1 = bits_of(torch, xs[0]), bits_of(torch, xs[1 % nx])
                 hg = gamma.cpu().numpy()
                 oc0, os0, _ = t.oracle(bits, group)
-                oc1, os1 = env.oracle.act_quant(hx1, group, bits)
+                if not norm_only:
+                    oc1, os1 = env.oracle.act_quant(hx1, group, bits)
                 # recompute side (slot 0 holds the codes of xs[0], slot 1 those of xs[1])
                 assert L.agoq_act_dequant_rmsnorm(*na[0]) == 0
                 torch.cuda.synchronize()
                 wy, wr = env.oracle.act_dequant_rmsnorm(oc0, os0, rows_, cols, group, bits, hg, eps)
                 ok_n = close_bf16(torch, ys[0], wy) and bool(np.allclose(rs[0].cpu().numpy(), wr, rtol=2e-6, atol=0))
-                if nc >= 2:
+                if nc >= 2 and not norm_only:
                     assert L.agoq_act_dequant_silu_mul(*sa[0]) == 0
                     torch.cuda.synchronize()
                     wz = env.oracle.act_dequant_silu_mul(oc0, os0, bits, oc1, os1, bits, n, group)
@@ -622,7 +629,7 @@ def section_fused(env):
                 wy, wr = env.oracle.rmsnorm_fwd(hx0, rows_, cols, hg, eps)
                 ok_f = (close_bf16(torch, ys[0], wy) and np.array_equal(cs[0].cpu().numpy(), oc0) and
                         same_u32(torch, ss[0], os0))
-                if nc >= 2 and nx >= 2:
+                if nc >= 2 and nx >= 2 and not norm_only:
                     assert L.agoq_silu_mul_fwd_quant(*ga[0]) == 0
                     torch.cuda.synchronize()
                     wz = env.oracle.silu_mul_fwd(hx0, hx1)
@@ -637,12 +644,13 @@ def section_fused(env):
                 R.add("fused", "act_dequant_rmsnorm", case, us, nb + 4 * rows_, ok_n)
                 us = R.timed(lambda i: L.agoq_rmsnorm_fwd_quant(*fa[i % m]))
                 R.add("fused", "rmsnorm_fwd_quant", case, us, nb + 2 * n + 4 * rows_, ok_f)
-            us = R.timed(lambda i: L.agoq_silu_mul_fwd_quant(*ga[i % m]))
-            R.add("fused", "silu_mul_fwd_quant", case, us, 2 * nb + 2 * n, ok_g)
-            for i in range(nc):
-                env.agoq.act_quant(xs[i % nx], group, bits, codes=cs[i], scales=ss[i])
-            us = R.timed(lambda i: L.agoq_act_dequant_silu_mul(*sa[i % m]))
-            R.add("fused", "act_dequant_silu_mul", case, us, 2 * (n * bits // 8 + 4 * (n // group)) + 2 * n, ok_s)
+            if not norm_only:
+                us = R.timed(lambda i: L.agoq_silu_mul_fwd_quant(*ga[i % m]))
+                R.add("fused", "silu_mul_fwd_quant", case, us, 2 * nb + 2 * n, ok_g)
+                for i in range(nc):
+                    env.agoq.act_quant(xs[i % nx], group, bits, codes=cs[i], scales=ss[i])
+                us = R.timed(lambda i: L.agoq_act_dequant_silu_mul(*sa[i % m]))
+                R.add("fused", "act_dequant_silu_mul", case, us, 2 * (n * bits // 8 + 4 * (n // group)) + 2 * n, ok_s)
             del cs, ss
         del xs, ys, t
         torch.cuda.empty_cache()

@@ -32,12 +32,12 @@ constexpr int kNormFwdVpt = 2;      // ... the forward kernel
 // 5- and 6-bit codes (three loads per vector): two per lane on rows of up to 1024 vectors, else four
 constexpr int norm_vpt56(int vecs_per_row) { return vecs_per_row <= 1024 ? 2 : 4; }
 constexpr int kNormResident = 1024; // lanes per compute unit the grid is sized for
-// Rows of exactly 64 * kWaveRowVpt vectors (4096 columns, the hidden size of the 8B models) take
-// the wavefront-per-row kernels: measured 5-17 % faster on [8192,4096] and [4096,4096] tensors
-// than two wavefronts per row with a barrier per row (4 wavefronts x 2 workgroups per compute
-// unit; 2 x 4 and 8 x 1 are 2-8 % slower, more workgroups per unit slower still).
-constexpr int kWaveRowVpt = 8;
-constexpr int kWaveRowVecs = 64 * kWaveRowVpt;
+// Rows of exactly 64 * VPT vectors for VPT = 8 or 10 (4096 and 5120 columns, the hidden sizes
+// of the 8B and 32B models) take the wavefront-per-row kernels: measured 5-17 % faster on
+// [8192,4096] and [4096,4096] tensors than two wavefronts per row with a barrier per row
+// (4 wavefronts x 2 workgroups per compute unit; 2 x 4 and 8 x 1 are 2-8 % slower, more
+// workgroups per unit slower still).
+constexpr int kWaveRowVptA = 8, kWaveRowVptB = 10;
 constexpr int kWaveRowWaves = 4;    // wavefronts (rows in progress) per workgroup
 constexpr int kWaveRowPerCu = 2;    // workgroups per compute unit the grid is sized for
 // With few rows per resident wavefront the kernels above win (half the work per wavefront on
@@ -244,18 +244,18 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void act_dequant_rmsnorm_kerne
     }
 }
 
-// The same for rows of exactly kWaveRowVecs vectors, one wavefront per row: the row sum is a
+// The same for rows of exactly 64 * VPT vectors, one wavefront per row: the row sum is a
 // reduction within the wavefront, so the row loop has no barrier and the wavefronts of a
-// workgroup drift apart freely (one's stores overlap another's loads).  A lane owns 8 vectors
-// of every row; gamma would take 64 registers per lane and waits in LDS instead, staged once
-// per workgroup.  Three rows per wavefront are in flight, as in the kernel above.
-template <int BITS, int GROUP, bool FP = false>
+// workgroup drift apart freely (one's stores overlap another's loads).  A lane owns VPT
+// vectors of every row; gamma would take 8 * VPT registers per lane and waits in LDS instead,
+// staged once per workgroup.  Three rows per wavefront are in flight, as in the kernel above.
+template <int BITS, int GROUP, int VPT, bool FP = false>
 __global__ __launch_bounds__(kWaveRowWaves * 64) void act_dequant_rmsnorm_wave_kernel(
     const void* __restrict__ codes, const float* __restrict__ scales, int64_t n_vec_total, int64_t rows,
     const f32x4* __restrict__ gamma, float eps, float inv_cols, u32x4* __restrict__ y, float* __restrict__ r_out)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int VPT = kWaveRowVpt;
+    constexpr int kWaveRowVecs = 64 * VPT;
     __shared__ f32x4 g_lo[kWaveRowVecs], g_hi[kWaveRowVecs];
     for (int v = threadIdx.x; v < kWaveRowVecs; v += kWaveRowWaves * 64) {
         g_lo[v] = gamma[2 * v];
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kWaveRowWaves * 64) void act_dequant_rmsnorm_wave_k
         const int64_t next = r + 3 * step;
         if (next < rows) fetch(refill, next);                      // the same for every lane
         // The row waits for its sum as the packed pairs: without this the compiler keeps the
-        // unpacked floats of the first pass instead, 64 registers more, and the kernel no
+        // unpacked floats of the first pass instead, 8 * VPT registers more, and the kernel no
         // longer fits two workgroups per compute unit.
 #pragma unroll
         for (int u = 0; u < VPT; ++u)
@@ -520,16 +520,16 @@ __global__ __launch_bounds__(norm_max_block(VPT)) void rmsnorm_fwd_quant_kernel(
     }
 }
 
-// The same for rows of exactly kWaveRowVecs vectors, one wavefront per row (see the recompute
+// The same for rows of exactly 64 * VPT vectors, one wavefront per row (see the recompute
 // kernel of that shape).
-template <int BITS, int GROUP, bool FP = false>
+template <int BITS, int GROUP, int VPT, bool FP = false>
 __global__ __launch_bounds__(kWaveRowWaves * 64) void rmsnorm_fwd_quant_wave_kernel(
     const u32x4* __restrict__ x, int64_t n_vec_total, int64_t rows, const f32x4* __restrict__ gamma, float eps,
     float inv_cols, u32x4* __restrict__ y, float* __restrict__ r_out, void* __restrict__ codes,
     float* __restrict__ scales)
 {
     constexpr int LANES = GROUP / 8;
-    constexpr int VPT = kWaveRowVpt;
+    constexpr int kWaveRowVecs = 64 * VPT;
     __shared__ f32x4 g_lo[kWaveRowVecs], g_hi[kWaveRowVecs];
     for (int v = threadIdx.x; v < kWaveRowVecs; v += kWaveRowWaves * 64) {
         g_lo[v] = gamma[2 * v];
@@ -670,7 +670,16 @@ inline unsigned wave_row_grid(int64_t rows)
 inline bool wave_row_shape(int64_t rows, int vecs_per_row, int min_rounds2)
 {
     const int64_t resident_waves = (int64_t)compute_units() * kWaveRowPerCu * kWaveRowWaves;
-    return vecs_per_row == kWaveRowVecs && 2 * rows >= min_rounds2 * resident_waves;
+    return (vecs_per_row == 64 * kWaveRowVptA || vecs_per_row == 64 * kWaveRowVptB) &&
+           2 * rows >= min_rounds2 * resident_waves;
+}
+
+// Calls f(std::integral_constant<int, VPT>) for the wavefront-per-row kernel of that row width.
+template <typename F>
+int dispatch_wave_row_vpt(int vecs_per_row, F&& f)
+{
+    return vecs_per_row == 64 * kWaveRowVptA ? f(std::integral_constant<int, kWaveRowVptA>{})
+                                             : f(std::integral_constant<int, kWaveRowVptB>{});
 }
 
 // Calls f(std::integral_constant<int, VPT>) for vpt in {1, 2, 4}.
@@ -707,11 +716,14 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
             return launch(kernel, dim3(wave_row_grid(rows)), dim3(kWaveRowWaves * 64), 0, st, codes, scales,
                           n_vec_total, rows, gm, eps, inv_cols, y, r_out);
         };
-        if (fp)
-            return group == 128 ? go(act_dequant_rmsnorm_wave_kernel<4, 128, true>)
-                                : go(act_dequant_rmsnorm_wave_kernel<4, 64, true>);
-        return dispatch_bits_group(bits, group, [&](auto b, auto g) {
-            return go(act_dequant_rmsnorm_wave_kernel<decltype(b)::value, decltype(g)::value>);
+        return dispatch_wave_row_vpt(vecs_per_row, [&](auto v) {
+            constexpr int V = decltype(v)::value;
+            if (fp)
+                return group == 128 ? go(act_dequant_rmsnorm_wave_kernel<4, 128, V, true>)
+                                    : go(act_dequant_rmsnorm_wave_kernel<4, 64, V, true>);
+            return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+                return go(act_dequant_rmsnorm_wave_kernel<decltype(b)::value, decltype(g)::value, V>);
+            });
         });
     }
     int vpt, threads;
@@ -800,11 +812,14 @@ int rmsnorm_fwd_quant_impl(const void* x_bf16, int64_t rows, int64_t cols, const
             return launch(kernel, dim3(wave_row_grid(rows)), dim3(kWaveRowWaves * 64), 0, st, x, n_vec_total, rows,
                           gm, eps, inv_cols, y, r_out, codes, scales);
         };
-        if (fp)
-            return group == 128 ? go(rmsnorm_fwd_quant_wave_kernel<4, 128, true>)
-                                : go(rmsnorm_fwd_quant_wave_kernel<4, 64, true>);
-        return dispatch_bits_group(bits, group, [&](auto b, auto g) {
-            return go(rmsnorm_fwd_quant_wave_kernel<decltype(b)::value, decltype(g)::value>);
+        return dispatch_wave_row_vpt(vecs_per_row, [&](auto v) {
+            constexpr int V = decltype(v)::value;
+            if (fp)
+                return group == 128 ? go(rmsnorm_fwd_quant_wave_kernel<4, 128, V, true>)
+                                    : go(rmsnorm_fwd_quant_wave_kernel<4, 64, V, true>);
+            return dispatch_bits_group(bits, group, [&](auto b, auto g) {
+                return go(rmsnorm_fwd_quant_wave_kernel<decltype(b)::value, decltype(g)::value, V>);
+            });
         });
     }
     int vpt, threads;
