@@ -40,11 +40,14 @@ constexpr int kNormResident = 1024; // lanes per compute unit the grid is sized 
 constexpr int kWaveRowVptA = 8, kWaveRowVptB = 10;
 constexpr int kWaveRowWaves = 4;    // wavefronts (rows in progress) per workgroup
 constexpr int kWaveRowPerCu = 2;    // workgroups per compute unit the grid is sized for
-// With few rows per resident wavefront the kernels above win (half the work per wavefront on
-// the one row it ever sees): the recompute kernel changes over at four rows per resident
-// wavefront (+6 to +14 % at 8192 rows, -5 to +4 % at 4096), the forward kernel at half a
-// row (+5 to +15 % from 1024 to 8192 rows, -15 % at 512).
-constexpr int kWaveRowMinRoundsRecompute2 = 8;      // twice the rows per resident wavefront
+// With few rows per resident wavefront the kernels above win (half the work, or less, per
+// wavefront on the one row it ever sees).  The recompute kernel changes over at one row per
+// resident wavefront for 8-bit codes (whose other form puts four wavefronts on a row), two
+// for 5 and 6 bits, four for 4 bits (measured on 4096- and 5120-wide rows, 1024 to 16384
+// rows: 8-bit +2 to +14 % from 2048 rows on; 6-bit -6 % at 3072, +2 to +8 % from 4096;
+// 4-bit -11 % at 3072, -5 % at 4096, +5 to +12 % at 8192); the forward kernel at half a row
+// (+5 to +15 % from 1024 to 8192 rows, -15 % at 512).
+constexpr int wave_row_min_rounds_recompute2(int bits) { return bits == 8 ? 2 : bits == 4 ? 8 : 4; }
 constexpr int kWaveRowMinRoundsForward2 = 1;
 
 // Sum of the per-wavefront partial sums of a workgroup, in wavefront order.
@@ -711,7 +714,7 @@ int dequant_rmsnorm_impl(const void* codes, const float* scales, int64_t rows, i
     hipStream_t st = (hipStream_t)stream;
     const f32x4* gm = (const f32x4*)gamma;
     u32x4* y = (u32x4*)y_bf16;
-    if (wave_row_shape(rows, vecs_per_row, kWaveRowMinRoundsRecompute2)) {
+    if (wave_row_shape(rows, vecs_per_row, wave_row_min_rounds_recompute2(bits))) {
         auto go = [&](auto kernel) {
             return launch(kernel, dim3(wave_row_grid(rows)), dim3(kWaveRowWaves * 64), 0, st, codes, scales,
                           n_vec_total, rows, gm, eps, inv_cols, y, r_out);

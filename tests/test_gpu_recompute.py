@@ -314,7 +314,9 @@ MANY_ROWS = [(2048 + 52, 14336, 4), (2048 + 52, 14336, 8), (4096 + 700, 14336, 5
              (1, 4096, 4), (3, 4096, 6), (2048 + 3, 4096, 5), (4096 + 3, 4096, 6), (6144 + 1, 4096, 5),
              (8192 + 7, 4096, 5), (8192 + 2, 4096, 6),
              # 5120-wide rows: ten vectors per lane in the same kernels
-             (1024 + 1, 5120, 4), (8192 + 3, 5120, 5), (8192 + 9, 5120, 6), (8192 + 1, 5120, 4)]
+             (1024 + 1, 5120, 4), (8192 + 3, 5120, 5), (8192 + 9, 5120, 6), (8192 + 1, 5120, 4),
+             # the recompute kernel changes form at 2048 rows (8-bit), 4096 (5/6-bit), 8192 (4-bit)
+             (2048 + 5, 4096, 8), (2048 - 1, 4096, 8), (2048 + 1, 5120, 8), (4096 + 1, 5120, 5), (4096 - 1, 4096, 6)]
 
 
 @pytest.mark.parametrize("rows,cols,bits", MANY_ROWS)
