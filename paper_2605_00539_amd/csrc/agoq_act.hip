@@ -295,9 +295,12 @@ int agoq_act_dequant(const void* codes, const float* scales, int64_t numel, int 
     // measured: a tensor small enough for (about) the whole grid to be resident at once runs
     // best with four vectors per lane, 8-bit codes then with paced stores; larger tensors
     // with two
-    // ("about": up to one and a half rounds; for 8-bit codes exactly one)
-    const bool small = bits == 8 ? fits_rounds(n_vec, kDqBlock, 4, 1, 1)
-                                 : fits_rounds(n_vec, kDqBlock, 4, 3, 2);
+    // ("about": up to one and a half rounds; for 8-bit codes exactly one).  5- and 6-bit
+    // codes, with three loads per vector, stay at two vectors per lane at every size
+    // (+2 to +5 % on 8M to 21M elements, nothing from 33M on).
+    const bool small = bits == 8   ? fits_rounds(n_vec, kDqBlock, 4, 1, 1)
+                       : bits == 4 ? fits_rounds(n_vec, kDqBlock, 4, 3, 2)
+                                   : false;
     const int unroll = small ? 4 : 2;
     const dim3 grid(blocks_for(n_vec, kDqBlock * unroll)), block(kDqBlock);
     const size_t cap = (bits == 8 && !small) ? kCapDq8 : 0;
