@@ -54,7 +54,7 @@ PEAK_HBM_GBPS = 8000.0
 GiB = 1 << 30
 # HBM bytes per launch of the K=8 reduce kernel on the step's workload, from hardware counters
 # (two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size)
-TRAFFIC_REDUCE_K8_BYTES = 2025227945
+TRAFFIC_REDUCE_K8_BYTES = 2024896318
 TRAFFIC_SOURCE = ("stored figure: rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of this command, "
                   "profiles/bench_llama8b_step_hbm_traffic.txt")
 GROUP = 128
