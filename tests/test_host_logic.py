@@ -160,3 +160,25 @@ def test_layer_call_argument_checks(agoq):
         assert call(fn, [good, Slot(0x10000, 0x20000, 0x30000, 0, 4)], 2) == 4
         assert call(fn, [good, Slot(0x10008, 0x20000, 0x30000, 1024, 4)], 2) == 5
     assert "count" in agoq.strerror(8)
+
+
+def test_profile_summaries_quote_committed_commands():
+    """Every summary under profiles/ is short text that quotes the rocprofv3 command that made
+    it, and that command runs a committed file (bench.py) and nothing else."""
+    import re
+    folder = os.path.join(ROOT, "profiles")
+    names = sorted(os.listdir(folder))
+    assert names, "profiles/ is empty"
+    for name in names:
+        path = os.path.join(folder, name)
+        assert name.endswith((".txt", ".md")), name
+        assert os.path.getsize(path) < 64 * 1024, name
+        text = open(path).read()
+        commands = re.findall(r"rocprofv3 .* -- (\S+) (\S+)", text)
+        assert commands, "%s quotes no rocprofv3 command" % name
+        for program, script in commands:
+            assert program == "python3" and script == "bench.py", (name, program, script)
+        # counters and traces never share a run
+        for line in text.splitlines():
+            if "rocprofv3" in line and "--pmc" in line:
+                assert "--kernel-trace" not in line and "--stats" not in line, (name, line)
